@@ -1,0 +1,150 @@
+/* moeq.h - C ABI of the MI355X (gfx950) mixed-bitwidth MoE layer forward.
+ *
+ * The path (EdgeMoE, arxiv 2308.14352): a router sends every token to its top-K experts
+ * (Section 1, Section 2.1); each expert is an independent FFN whose weights are stored at a
+ * per-expert bitwidth (INT2/INT4/INT8) by linear, scale-only quantization with float16
+ * scales and are decompressed by the mirror map before use (Section 3.2); the K expert
+ * outputs are combined with the router's gate weights. Here the decompression is fused into
+ * the FFN kernels: packed codes are streamed from HBM once and never materialised as floats.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers are host
+ *     memory. The library borrows them for the duration of a call (for moe_layer_create: for
+ *     the lifetime of the layer handle) and never frees them.
+ *   - The library allocates no device memory. Scratch comes in through `ws` (size from
+ *     moe_workspace_bytes); the per-layer expert table lives in a caller-provided device
+ *     buffer (size from moe_layer_table_bytes).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Compute entry
+ *     points only enqueue work and return; they never synchronise. Results are valid once
+ *     the stream reaches the end of the enqueued work. The top-k indices stay on the device
+ *     between the router and the expert kernels.
+ *   - Every entry point validates its arguments before the first HIP call and reports
+ *     problems as a status code; nothing throws, nothing aborts.
+ *   - Calls that share a workspace must be ordered on one stream (or otherwise serialised).
+ *
+ * Packed weight format (the boundary format; "canonical")
+ *   A matrix W[rows][cols] (row = output channel, cols = input dimension) at b bits with group
+ *   size g (g consecutive input indices of one row share a scale; g = cols is the paper's
+ *   per-channel case):
+ *     codes : rows * cols*b/8 bytes, row-major. Element i of a row is the unsigned field
+ *             u = q + 2^(b-1) (q in [-(2^(b-1)-1), 2^(b-1)-1]) at bits [i*b mod 8, +b) of byte
+ *             floor(i*b/8). cols*b must be a multiple of 128 (16-byte rows).
+ *     scales: rows * cols/g IEEE binary16 values, row-major. W^[o][i] = scale[o][i/g] * q[o][i].
+ */
+#ifndef MOEQ_H
+#define MOEQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOEQ_OK = 0,
+  MOEQ_EINVAL = 1,       /* malformed argument (null pointer, bad shape, bad bitwidth ...)   */
+  MOEQ_EUNSUPPORTED = 2, /* well-formed but outside what the kernels cover                    */
+  MOEQ_EWORKSPACE = 3,   /* ws is NULL or smaller than moe_workspace_bytes() for this call    */
+  MOEQ_EDEVICE = 4       /* a HIP call failed (no device, launch error); see hipGetLastError  */
+} moeq_status;
+
+typedef enum { MOEQ_ACT_RELU = 0, MOEQ_ACT_SWIGLU = 1 } moeq_act;
+typedef enum { MOEQ_F32 = 0, MOEQ_BF16 = 1 } moeq_dtype;
+
+/* One expert's packed weights: dev pointers, read-only, in the canonical format.
+ * ReLU   (Switch-style): h = relu(W_in x),            y = W_out h;   q_gate/s_gate = NULL
+ * SwiGLU (Mixtral-style): h = silu(W_in x) * (W_gate x), y = W_out h
+ * W_in, W_gate: [d_ff][d_model]; W_out: [d_model][d_ff]. `bits` is this expert's entry of the
+ * per-expert bitwidth table (Section 3.2, "Selecting expert-wise bitwidths").               */
+typedef struct moeq_expert {
+  int32_t bits; /* 2, 4 or 8 */
+  const void *q_in, *s_in;
+  const void *q_gate, *s_gate;
+  const void *q_out, *s_out;
+} moeq_expert;
+
+/* Description of one MoE layer (host struct). */
+typedef struct moeq_layer_desc {
+  int32_t d_model, d_ff, n_experts, top_k, group;
+  int32_t act;              /* moeq_act                                                        */
+  int32_t renorm;           /* 0: gate = softmax probability of the chosen expert;
+                               1: gates divided by the sum of the K chosen probabilities      */
+  int32_t x_dtype;          /* moeq_dtype of the hidden states; outputs are always fp32        */
+  const float *router_w;    /* dev [n_experts][d_model] fp32                                   */
+  const float *router_bias; /* dev [n_experts] fp32 or NULL                                    */
+  const moeq_expert *experts; /* host array [n_experts] of dev pointers                        */
+} moeq_layer_desc;
+
+typedef struct moeq_layer moeq_layer; /* opaque, host-side handle */
+
+/* ---- set-up (not on the hot path) -------------------------------------------------------- */
+
+/* Bytes of device memory the expert table of a layer with n_experts experts needs. */
+size_t moe_layer_table_bytes(int32_t n_experts);
+
+/* Validates `desc`, copies the expert table into `table_dev` (synchronous copy) and returns a
+ * handle. `table_dev` (dev, >= moe_layer_table_bytes(n_experts), 16-byte aligned) and every
+ * pointer in `desc` must stay valid until moe_layer_destroy. Limits: d_model, d_ff multiples of
+ * `group`; group a multiple of 32 (a multiple of 64 or exactly 32 for 2-bit experts);
+ * d_model*bits and d_ff*bits multiples of 128 for every expert; 1 <= top_k <= min(8, n_experts);
+ * n_experts <= 1024; d_model, d_ff <= 32768.
+ * Errors: MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EDEVICE (copy failed). */
+moeq_status moe_layer_create(const moeq_layer_desc *desc, void *table_dev, size_t table_bytes,
+                             moeq_layer **out);
+void moe_layer_destroy(moeq_layer *layer);
+
+/* Workspace bytes needed by any compute call on `layer` with up to max_tokens tokens. */
+size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);
+
+/* Codes bytes of a packed [rows][cols] matrix; *scale_bytes_opt receives the bytes of its scales.
+ * Returns 0 when the arguments are not a valid packed shape. Host-only arithmetic. */
+size_t moe_packed_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group,
+                        size_t *scale_bytes_opt);
+
+/* ---- the path ---------------------------------------------------------------------------- */
+
+/* Router: logits = router_w x (+ bias), p = softmax(logits), the top_k largest (ties to the lowest
+ * expert index, results in descending gate order), gates per `renorm` (Section 1; Section 2.1).
+ * x: dev [n_tokens][d_model] in the layer's x_dtype. topk_idx: dev [n_tokens][top_k] int32.
+ * topk_gate: dev [n_tokens][top_k] fp32. probs_opt: dev [n_tokens][n_experts] fp32 or NULL.
+ * n_tokens == 0 is a no-op. */
+moeq_status moe_router_topk(const moeq_layer *layer, const void *x, int32_t n_tokens,
+                            int32_t *topk_idx, float *topk_gate, float *probs_opt, void *stream);
+
+/* One expert's dequantize-fused FFN on n_tokens tokens (Section 3.2: decompress, then use):
+ * y[t] (+)= gate[t] * W_out^ act(W_in^ x[t]). gate_opt: dev [n_tokens] fp32 or NULL (= 1).
+ * accumulate != 0 adds into y, else overwrites. y: dev [n_tokens][d_model] fp32. */
+moeq_status moe_expert_ffn_q(const moeq_layer *layer, int32_t expert, const void *x,
+                             int32_t n_tokens, const float *gate_opt, int32_t accumulate,
+                             float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* The whole layer: router, top-k, the chosen experts' FFNs, gate-weighted combine:
+ * y[t] = sum_j gate[t][j] * FFN_{idx[t][j]}(x[t]). topk_idx_opt / topk_gate_opt (dev, may be NULL)
+ * receive the routing decision. */
+moeq_status moe_layer_forward(const moeq_layer *layer, const void *x, int32_t n_tokens, float *y,
+                              int32_t *topk_idx_opt, float *topk_gate_opt, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* ---- compression primitives (offline side of the path, Section 3.2) ---------------------- */
+
+/* Quantize and pack on the device: w dev [rows][cols] fp32 -> codes (q_out) and fp16 scales (s_out)
+ * in the canonical format. scale = fp16(absmax/qmax) (nearest even, moved one fp16 step up if the
+ * largest element would otherwise clamp), q = rint(w/scale) with fp32 division. */
+moeq_status moe_quantize_pack(const float *w, int64_t rows, int64_t cols, int32_t bits,
+                              int32_t group, void *q_out, void *s_out, void *stream);
+
+/* Packed codes -> signed codes, one int8 per weight (dev [rows][cols]); for bit-exact checks. */
+moeq_status moe_unpack_codes(const void *q, int64_t rows, int64_t cols, int32_t bits,
+                             int8_t *codes_out, void *stream);
+
+/* Stand-alone decompression (the paper's own step): packed -> fp32 dev [rows][cols]. */
+moeq_status moe_dequantize(const void *q, const void *s, int64_t rows, int64_t cols, int32_t bits,
+                           int32_t group, float *w_out, void *stream);
+
+const char *moe_status_str(moeq_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEQ_H */

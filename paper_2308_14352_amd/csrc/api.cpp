@@ -1,0 +1,206 @@
+// Host side of the C ABI: argument validation, workspace carving, kernel dispatch.
+// Every check runs before the first HIP call, so the error paths work on a host without a GPU.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "moeq_internal.h"
+
+using namespace moeq;
+
+struct moeq_layer {
+  LayerDims dims;
+  const float* router_w;
+  const float* router_bias;
+  const DevExpert* table;          // device
+  std::vector<int32_t> bits;       // host copy of the bitwidth table
+};
+
+namespace {
+
+inline bool bits_ok(int32_t b) { return b == 2 || b == 4 || b == 8; }
+
+inline bool group_ok(int32_t g, int32_t bits) {
+  if (g <= 0 || g % 32) return false;
+  if (bits == 2 && !(g == 32 || g % 64 == 0)) return false;
+  return true;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WsLayout {
+  size_t idx_off, gate_off, h_off, total;
+};
+
+WsLayout ws_layout(const LayerDims& L, int64_t T) {
+  WsLayout w;
+  const size_t slots = (size_t)T * L.top_k;
+  w.idx_off = 0;
+  w.gate_off = align_up(slots * sizeof(int32_t), 256);
+  w.h_off = w.gate_off + align_up(slots * sizeof(float), 256);
+  w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(float), 256);
+  return w;
+}
+
+inline moeq_status dev(hipError_t e) { return e == hipSuccess ? MOEQ_OK : MOEQ_EDEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_str(moeq_status st) {
+  switch (st) {
+    case MOEQ_OK: return "ok";
+    case MOEQ_EINVAL: return "invalid argument";
+    case MOEQ_EUNSUPPORTED: return "unsupported configuration";
+    case MOEQ_EWORKSPACE: return "workspace missing or too small";
+    case MOEQ_EDEVICE: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+size_t moe_layer_table_bytes(int32_t n_experts) {
+  return n_experts > 0 ? (size_t)n_experts * sizeof(DevExpert) : 0;
+}
+
+size_t moe_packed_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group, size_t* scale_bytes_opt) {
+  if (scale_bytes_opt) *scale_bytes_opt = 0;
+  if (rows <= 0 || cols <= 0 || !bits_ok(bits) || group <= 0 || cols % group || (cols * bits) % 8) return 0;
+  if (scale_bytes_opt) *scale_bytes_opt = (size_t)rows * (size_t)(cols / group) * 2;
+  return (size_t)rows * (size_t)(cols * bits / 8);
+}
+
+moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_t table_bytes,
+                             moeq_layer** out) {
+  if (out) *out = nullptr;
+  if (!desc || !out || !table_dev || !desc->experts || !desc->router_w) return MOEQ_EINVAL;
+  const int32_t d = desc->d_model, f = desc->d_ff, E = desc->n_experts, k = desc->top_k, g = desc->group;
+  if (d <= 0 || f <= 0 || E <= 0 || k <= 0 || g <= 0) return MOEQ_EINVAL;
+  if (k > E) return MOEQ_EINVAL;
+  if (desc->act != MOEQ_ACT_RELU && desc->act != MOEQ_ACT_SWIGLU) return MOEQ_EINVAL;
+  if (desc->x_dtype != MOEQ_F32 && desc->x_dtype != MOEQ_BF16) return MOEQ_EINVAL;
+  if (d % g || f % g) return MOEQ_EINVAL;
+  if (((uintptr_t)table_dev & 15u) || table_bytes < moe_layer_table_bytes(E)) return MOEQ_EINVAL;
+  if (k > 8 || E > 1024 || d > 32768 || f > 32768 || d % 8 || f % 8) return MOEQ_EUNSUPPORTED;
+  std::vector<DevExpert> tab((size_t)E);
+  std::vector<int32_t> bits((size_t)E);
+  for (int32_t e = 0; e < E; ++e) {
+    const moeq_expert& x = desc->experts[e];
+    if (!bits_ok(x.bits)) return MOEQ_EINVAL;
+    if (!x.q_in || !x.s_in || !x.q_out || !x.s_out) return MOEQ_EINVAL;
+    if (desc->act == MOEQ_ACT_SWIGLU && (!x.q_gate || !x.s_gate)) return MOEQ_EINVAL;
+    if (((int64_t)d * x.bits) % 128 || ((int64_t)f * x.bits) % 128) return MOEQ_EINVAL;
+    if (!group_ok(g, x.bits)) return MOEQ_EUNSUPPORTED;
+    const uintptr_t align_or = (uintptr_t)x.q_in | (uintptr_t)x.q_out | (uintptr_t)x.q_gate;
+    if (align_or & 15u) return MOEQ_EINVAL;  // 16-byte loads on the code rows
+    if (((uintptr_t)x.s_in | (uintptr_t)x.s_out | (uintptr_t)x.s_gate) & 1u) return MOEQ_EINVAL;
+    DevExpert& t = tab[(size_t)e];
+    std::memset(&t, 0, sizeof(t));
+    t.q_in = (const uint8_t*)x.q_in;     t.s_in = (const uint16_t*)x.s_in;
+    t.q_gate = (const uint8_t*)x.q_gate; t.s_gate = (const uint16_t*)x.s_gate;
+    t.q_out = (const uint8_t*)x.q_out;   t.s_out = (const uint16_t*)x.s_out;
+    t.bits = x.bits;
+    bits[(size_t)e] = x.bits;
+  }
+  moeq_layer* L = new (std::nothrow) moeq_layer();
+  if (!L) return MOEQ_EDEVICE;
+  L->dims = LayerDims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0};
+  L->router_w = desc->router_w;
+  L->router_bias = desc->router_bias;
+  L->table = (const DevExpert*)table_dev;
+  L->bits = std::move(bits);
+  if (hipMemcpy(table_dev, tab.data(), tab.size() * sizeof(DevExpert), hipMemcpyHostToDevice) != hipSuccess) {
+    delete L;
+    return MOEQ_EDEVICE;
+  }
+  *out = L;
+  return MOEQ_OK;
+}
+
+void moe_layer_destroy(moeq_layer* layer) { delete layer; }
+
+size_t moe_workspace_bytes(const moeq_layer* layer, int32_t max_tokens) {
+  if (!layer || max_tokens <= 0) return 0;
+  return ws_layout(layer->dims, max_tokens).total;
+}
+
+moeq_status moe_router_topk(const moeq_layer* layer, const void* x, int32_t n_tokens, int32_t* topk_idx,
+                            float* topk_gate, float* probs_opt, void* stream) {
+  if (!layer || n_tokens < 0) return MOEQ_EINVAL;
+  if (n_tokens == 0) return MOEQ_OK;
+  if (!x || !topk_idx || !topk_gate || ((uintptr_t)x & 15u)) return MOEQ_EINVAL;
+  if (n_tokens > 65535) return MOEQ_EUNSUPPORTED;
+  return dev(launch_router_topk(layer->dims, layer->router_w, layer->router_bias, x, n_tokens, topk_idx,
+                                topk_gate, probs_opt, (hipStream_t)stream));
+}
+
+moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void* x, int32_t n_tokens,
+                             const float* gate_opt, int32_t accumulate, float* y, void* ws, size_t ws_bytes,
+                             void* stream) {
+  if (!layer || n_tokens < 0) return MOEQ_EINVAL;
+  if (expert < 0 || expert >= layer->dims.n_experts) return MOEQ_EINVAL;
+  if (n_tokens == 0) return MOEQ_OK;
+  if (!x || !y || ((uintptr_t)x & 15u) || ((uintptr_t)y & 3u)) return MOEQ_EINVAL;
+  if (n_tokens > 65535) return MOEQ_EUNSUPPORTED;
+  const WsLayout w = ws_layout(layer->dims, n_tokens);
+  if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
+  if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
+  float* h = (float*)((char*)ws + w.h_off);
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, expert, x, n_tokens, h, st);
+  if (e != hipSuccess) return MOEQ_EDEVICE;
+  return dev(launch_ffn_out(layer->dims, layer->table, nullptr, gate_opt, expert, accumulate ? 1 : 0, h,
+                            n_tokens, y, st));
+}
+
+moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_tokens, float* y,
+                              int32_t* topk_idx_opt, float* topk_gate_opt, void* ws, size_t ws_bytes,
+                              void* stream) {
+  if (!layer || n_tokens < 0) return MOEQ_EINVAL;
+  if (n_tokens == 0) return MOEQ_OK;
+  if (!x || !y || ((uintptr_t)x & 15u) || ((uintptr_t)y & 3u)) return MOEQ_EINVAL;
+  if ((int64_t)n_tokens * layer->dims.top_k > 65535) return MOEQ_EUNSUPPORTED;
+  const LayerDims& L = layer->dims;
+  const WsLayout w = ws_layout(L, n_tokens);
+  if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
+  if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
+  int32_t* idx = topk_idx_opt ? topk_idx_opt : (int32_t*)((char*)ws + w.idx_off);
+  float* gate = topk_gate_opt ? topk_gate_opt : (float*)((char*)ws + w.gate_off);
+  float* h = (float*)((char*)ws + w.h_off);
+  hipStream_t st = (hipStream_t)stream;
+  if (launch_router_topk(L, layer->router_w, layer->router_bias, x, n_tokens, idx, gate, nullptr, st) != hipSuccess)
+    return MOEQ_EDEVICE;
+  if (launch_ffn_in(L, layer->table, idx, -1, x, n_tokens * L.top_k, h, st) != hipSuccess) return MOEQ_EDEVICE;
+  return dev(launch_ffn_out(L, layer->table, idx, gate, -1, 0, h, n_tokens, y, st));
+}
+
+moeq_status moe_quantize_pack(const float* w, int64_t rows, int64_t cols, int32_t bits, int32_t group,
+                              void* q_out, void* s_out, void* stream) {
+  if (!w || !q_out || !s_out || rows < 0 || cols <= 0) return MOEQ_EINVAL;
+  if (!bits_ok(bits) || group <= 0 || cols % group || group % 4 || (cols * bits) % 128) return MOEQ_EINVAL;
+  if (((uintptr_t)w & 15u) || ((uintptr_t)q_out & 3u) || ((uintptr_t)s_out & 1u)) return MOEQ_EINVAL;
+  if (rows == 0) return MOEQ_OK;
+  if (rows * (cols / group) > (int64_t)1 << 40) return MOEQ_EUNSUPPORTED;
+  return dev(launch_quantize_pack(w, rows, cols, bits, group, (uint8_t*)q_out, (uint16_t*)s_out,
+                                  (hipStream_t)stream));
+}
+
+moeq_status moe_unpack_codes(const void* q, int64_t rows, int64_t cols, int32_t bits, int8_t* codes_out,
+                             void* stream) {
+  if (!q || !codes_out || rows < 0 || cols <= 0) return MOEQ_EINVAL;
+  if (!bits_ok(bits) || (cols * bits) % 8) return MOEQ_EINVAL;
+  if (rows == 0) return MOEQ_OK;
+  return dev(launch_unpack_codes((const uint8_t*)q, rows, cols, bits, codes_out, (hipStream_t)stream));
+}
+
+moeq_status moe_dequantize(const void* q, const void* s, int64_t rows, int64_t cols, int32_t bits,
+                           int32_t group, float* w_out, void* stream) {
+  if (!q || !s || !w_out || rows < 0 || cols <= 0) return MOEQ_EINVAL;
+  if (!bits_ok(bits) || group <= 0 || cols % group || (cols * bits) % 8) return MOEQ_EINVAL;
+  if (rows == 0) return MOEQ_OK;
+  return dev(launch_dequantize((const uint8_t*)q, (const uint16_t*)s, rows, cols, bits, group, w_out,
+                               (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moeq.h"
+
+namespace moeq {
+
+// Device-resident view of one expert (the expert table is an array of these).
+struct alignas(64) DevExpert {
+  const uint8_t* q_in;
+  const uint16_t* s_in;
+  const uint8_t* q_gate;
+  const uint16_t* s_gate;
+  const uint8_t* q_out;
+  const uint16_t* s_out;
+  int32_t bits;
+  int32_t pad_[3];
+};
+static_assert(sizeof(DevExpert) == 64, "expert table entry is 64 bytes");
+
+struct LayerDims {
+  int32_t d_model, d_ff, n_experts, top_k, group, act, renorm, x_bf16;
+};
+
+// Launchers (defined in the .hip files). All enqueue on `st` and return the launch status.
+hipError_t launch_router_topk(const LayerDims& L, const float* router_w, const float* router_bias,
+                              const void* x, int32_t T, int32_t* idx, float* gate, float* probs,
+                              hipStream_t st);
+
+// Phase 1 of the expert FFN for `slots` (token, choice) pairs: h[slot][f] = act(W_in x [, W_gate x]).
+// fixed_expert >= 0: every slot uses that expert and slot == token; else expert = idx[slot],
+// token = slot / top_k.
+hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const int32_t* idx,
+                         int32_t fixed_expert, const void* x, int32_t slots, float* h,
+                         hipStream_t st);
+
+// Phase 2 + combine: y[t] (+)= sum_j gate * W_out h[slot].
+hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx,
+                          const float* gate, int32_t fixed_expert, int32_t accumulate,
+                          const float* h, int32_t T, float* y, hipStream_t st);
+
+hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
+                                uint8_t* q, uint16_t* s, hipStream_t st);
+hipError_t launch_unpack_codes(const uint8_t* q, int64_t rows, int64_t cols, int bits, int8_t* codes,
+                               hipStream_t st);
+hipError_t launch_dequantize(const uint8_t* q, const uint16_t* s, int64_t rows, int64_t cols, int bits,
+                             int group, float* w, hipStream_t st);
+
+}  // namespace moeq

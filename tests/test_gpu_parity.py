@@ -1,0 +1,220 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element, on seeded
+inputs drawn once and handed to both sides. Bars: top-k indices and packed codes bit-exact; decode
+outputs within 2e-3 in the per-token max norm (||y - y_ref||_inf / ||y_ref||_inf)."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+import paper_2308_14352_amd as moeq
+from helpers import (build_layer_pair, near_tie_tokens, oracle_layer, pack_expert_gpu, pack_expert_oracle, rel_err)
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3          # decode paths accumulate in fp32
+DEV = "cuda:0"
+
+
+def s16(t):
+    """fp16 scale tensor -> raw bits as numpy uint16."""
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+# ------------------------------------------------------------------ compression primitives
+@pytest.mark.parametrize("bits", (2, 4, 8))
+@pytest.mark.parametrize("rows,cols,group", [(37, 256, 32), (5, 768, 64), (3, 1024, 128), (2, 3072, 3072), (1, 64, 64),
+                                             (300, 4096, 128)])
+def test_quantize_pack_codes_and_scales_bit_exact(bits, rows, cols, group):
+    if bits == 2 and cols * bits % 128:
+        pytest.skip("row is not a whole number of 16-byte chunks")
+    w = gen.normal((rows, cols), 0.02, gen.seed_for("qp", bits, rows, cols), DEV)
+    w[0, :group] = 0.0                                  # an all-zero group
+    if rows > 1:
+        w[1, :group] *= 1e-4                            # a group whose scale is an fp16 subnormal
+        w[1, group - 1] = 3.0e-7
+    q, s = moeq.moe_quantize_pack(w, bits, group)
+    torch.cuda.synchronize()
+    q_ref, s_ref = oracle.quantize_pack(w.cpu().numpy(), bits, group)
+    assert np.array_equal(s16(s), s_ref), "scales differ"
+    assert np.array_equal(q.cpu().numpy(), q_ref), "packed codes differ"
+    codes = moeq.moe_unpack_codes(q, cols, bits)
+    wd = moeq.moe_dequantize(q, s, cols, bits, group)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), oracle.unpack(q_ref, cols, bits))
+    assert np.array_equal(wd.cpu().numpy(), oracle.dequant(q_ref, s_ref, cols, bits, group))
+
+
+def test_quantize_pack_ties_and_bump_cases_bit_exact():
+    """Exact .5 ties (round half to even) and max-abs values whose fp16 scale must be bumped."""
+    g = 32
+    rng = np.random.default_rng(5)
+    w = np.zeros((512, 2 * g), np.float32)            # two groups per row: 2-bit rows need 64 columns
+    w[:, 0] = rng.uniform(0.01, 0.1, 512).astype(np.float32)
+    w[:, g] = rng.uniform(0.01, 0.1, 512).astype(np.float32)
+    for r in range(512):
+        for c0 in (0, g):
+            s = np.float32(w[r, c0]) / np.float32(7)
+            w[r, c0 + 1:c0 + 8] = (np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5], np.float32)
+                                   * np.float32(np.float16(s)))
+    wt = torch.from_numpy(w).to(DEV)
+    for bits in (2, 4, 8):
+        q, s = moeq.moe_quantize_pack(wt, bits, g)
+        torch.cuda.synchronize()
+        q_ref, s_ref = oracle.quantize_pack(w, bits, g)
+        assert np.array_equal(s16(s), s_ref) and np.array_equal(q.cpu().numpy(), q_ref)
+
+
+# ------------------------------------------------------------------ router
+@pytest.mark.parametrize("cfg_id,T", [("c1", 64), ("c2", 33), ("c3", 8), ("c4", 5), ("c5", 257)])
+def test_router_topk_matches_oracle(cfg_id, T):
+    cfg = gen.CONFIGS[cfg_id]
+    Wr, bias = gen.router_weights(cfg, 0, DEV)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    layer = _router_only_layer(cfg, Wr, bias)
+    idx, gate, probs = moeq.moe_router_topk(layer, x, want_probs=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, probs_ref = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(),
+                                                      None if bias is None else bias.cpu().numpy(), cfg.top_k,
+                                                      cfg.renorm)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    assert len(skip) <= max(1, T // 50)
+    keep = [t for t in range(T) if t not in skip]
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep]), "top-k indices must be bit-exact"
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    assert np.allclose(probs.cpu().numpy(), probs_ref, rtol=2e-5, atol=1e-7)
+    assert np.allclose(probs.cpu().numpy().sum(1), 1.0, atol=1e-5)
+
+
+def _router_only_layer(cfg, Wr, bias):
+    """A layer whose expert pointers are valid but tiny: only the router entry point is exercised."""
+    dummy_q = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    dummy_s = torch.zeros(8, dtype=torch.float16, device=DEV)
+    ex = [moeq.PackedExpert(4, dummy_q, dummy_s, dummy_q, dummy_s, dummy_q if cfg.swiglu else None,
+                            dummy_s if cfg.swiglu else None) for _ in range(cfg.n_experts)]
+    return moeq.Layer(cfg.d_model, cfg.d_ff, cfg.top_k, cfg.group,
+                      moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU, cfg.renorm,
+                      moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32, Wr, bias, ex)
+
+
+def test_router_exact_ties_go_to_lowest_index():
+    cfg = gen.tiny_config("c4", 256, 512)
+    Wr = torch.zeros((cfg.n_experts, cfg.d_model), device=DEV)
+    row = gen.normal((cfg.d_model,), 0.1, 7, DEV)
+    Wr[2] = row; Wr[5] = row; Wr[6] = row          # identical rows -> identical fp32 logits
+    x = row.to(torch.bfloat16)[None, :].contiguous()      # x . row > 0 beats the all-zero rows
+    layer = _router_only_layer(cfg, Wr, None)
+    idx, gate = moeq.moe_router_topk(layer, x)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == [[2, 5]]
+    assert abs(float(gate.sum()) - 1.0) < 1e-6 and float(gate[0, 0]) == float(gate[0, 1])
+
+
+# ------------------------------------------------------------------ single expert FFN
+@pytest.mark.parametrize("bits", (2, 4, 8))
+@pytest.mark.parametrize("base,d,f,g,T", [
+    ("c1", 768, 3072, 32, 1),      # Switch-base expert, full size
+    ("c1", 192, 320, 32, 3),       # short ragged rows (3 / 6 / 12 chunks per row)
+    ("c3", 1024, 4096, 64, 2),     # Switch-large expert, full size
+    ("c4", 512, 1792, 128, 2),     # SwiGLU, Mixtral-like 7 * 2^k row length
+    ("c4", 4096, 14336, 128, 1),   # Mixtral expert, full size
+])
+def test_expert_ffn_q_matches_oracle(bits, base, d, f, g, T):
+    if bits == 2 and (d % 64 or f % 64):
+        pytest.skip("2-bit rows must be whole 16-byte chunks")
+    cfg = gen.tiny_config(base, d, f, n_experts=2, group=g)
+    w = gen.expert_weights(cfg, 0, 1, DEV)
+    ex_gpu = pack_expert_gpu(w, bits, g)
+    ex_orc = pack_expert_oracle(w, bits, g)
+    del w
+    Wr, _ = gen.router_weights(cfg, 0, DEV)
+    layer = moeq.Layer(d, f, cfg.top_k, g, moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU, cfg.renorm,
+                       moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32, Wr, None, [ex_gpu, ex_gpu])
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y_ref = oracle.expert_ffn(ex_orc, d, f, g, int(cfg.swiglu), x.float().cpu().numpy())
+    y = moeq.moe_expert_ffn_q(layer, 1, x)
+    torch.cuda.synchronize()
+    assert rel_err(y.cpu().numpy(), y_ref).max() < TOL
+    # gate and accumulate: y2 = y0 + gate * FFN(x)
+    gate = torch.linspace(0.25, 0.75, T, device=DEV)
+    y0 = gen.normal((T, d), 1.0, 99, DEV)
+    y2 = moeq.moe_expert_ffn_q(layer, 0, x, gate=gate, y=y0.clone(), accumulate=True)
+    torch.cuda.synchronize()
+    ref2 = y0.cpu().numpy() + gate.cpu().numpy()[:, None] * y_ref
+    assert np.abs(y2.cpu().numpy() - ref2).max() < TOL * np.abs(y_ref).max() + 1e-6
+
+
+# ------------------------------------------------------------------ whole layer, shrunken copies of the five configs
+@pytest.mark.parametrize("base,d,f,E,T", [
+    ("c1", 256, 512, 8, 5), ("c2", 384, 768, 16, 4), ("c3", 512, 1024, 32, 8), ("c4", 512, 1792, 8, 3),
+    ("c5", 512, 1024, 8, 40),
+])
+def test_layer_forward_small(base, d, f, E, T):
+    cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 1
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+    # purity (Section 4.2: results never depend on what ran before): a second call is bit-identical
+    y_b = moeq.moe_layer_forward(layer, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_b)
+    # zero tokens: a no-op
+    moeq.moe_layer_forward(layer, x[:0])
+
+
+def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
+    """Oracle-side experts for the activated ones only; the rest are never dereferenced."""
+    dummy = oracle.Expert(4, np.zeros(1, np.uint8), np.zeros(1, np.uint16), np.zeros(1, np.uint8),
+                          np.zeros(1, np.uint16), np.zeros(1, np.uint8), np.zeros(1, np.uint16))
+    out = [dummy] * cfg.n_experts
+    for e in sorted(needed):
+        out[e] = pack_expert_oracle(gen.expert_weights(cfg, layer_id, e, DEV), bits_table[e], cfg.group)
+    return out
+
+
+@pytest.mark.parametrize("cfg_id,layer_id,T", [("c1", 0, 8), ("c2", 3, 6), ("c3", 7, 8), ("c4", 5, 2)])
+def test_layer_forward_full_size(cfg_id, layer_id, T):
+    """One layer of each decode configuration at its real shape; the oracle runs the activated experts."""
+    cfg = gen.CONFIGS[cfg_id]
+    bits_table = gen.bitwidth_table(cfg, layer_id)
+    layer, _, Wr, bias = build_layer_pair(cfg, layer_id, DEV, bits_table, want_oracle=False)
+    x = gen.hidden(cfg, layer_id, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, _ = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(),
+                                              None if bias is None else bias.cpu().numpy(), cfg.top_k, cfg.renorm)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 1
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    experts = _lazy_oracle_experts(cfg, layer_id, bits_table, set(idx_ref.flatten().tolist()))
+    y_ref, _, _ = oracle_layer(cfg, experts, Wr, bias, x)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+    # the library's packed copy of one activated expert equals the oracle's, bit for bit
+    e = int(idx_ref[0, 0])
+    assert np.array_equal(layer.experts[e].q_in.cpu().numpy(), experts[e].q_in)
+    assert np.array_equal(s16(layer.experts[e].s_out), experts[e].s_out)
+
+
+def test_layer_forward_batch8_switch_large_and_workspace_errors():
+    cfg = gen.tiny_config("c3", 1024, 4096, n_experts=16, n_layers=1)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
+    x = gen.hidden(cfg, 0, 1, 8, DEV)
+    y = moeq.moe_layer_forward(layer, x)
+    torch.cuda.synchronize()
+    y_ref, _, _ = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    assert rel_err(y.cpu().numpy(), y_ref).max() < TOL
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(moeq.MoeqError) as ei:
+        moeq.moe_layer_forward(layer, x, ws=small)
+    assert ei.value.status == moeq.binding.MOEQ_EWORKSPACE
+    with pytest.raises(moeq.MoeqError):
+        moeq.moe_expert_ffn_q(layer, 99, x)
