@@ -1,0 +1,293 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-bitwidth MoE layer forward on one MI355X.
+
+A step is one decode step of the whole stack: every MoE layer of the workload runs router ->
+top-k -> dequantize-fused expert FFNs -> gate-weighted combine on that step's hidden states, the
+layers strictly in order on one stream. Inputs (packed experts, router weights, all hidden states)
+are resident in HBM before the timed region. Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c3|c3b8] [--no-extras]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c3b8", "c4"])
+    ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other decode workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every layer from Python instead of a HIP graph")
+    ap.add_argument("--layers", type=int, default=None, help="debug: truncate the stack")
+    return ap.parse_args()
+
+
+class Stack:
+    """All layers of one workload, packed in HBM, plus the hidden states of every (step, layer)."""
+
+    def __init__(self, cfg, batch, steps, dev, n_layers=None):
+        import torch
+        import gen
+        import paper_2308_14352_amd as moeq
+        self.cfg, self.batch, self.steps = cfg, batch, steps
+        self.L = n_layers or cfg.n_layers
+        self.layers, self.bits = [], []
+        act = moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU
+        xdt = moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32
+        for l in range(self.L):
+            bits = gen.bitwidth_table(cfg, l)
+            experts = []
+            for e in range(cfg.n_experts):
+                w = gen.expert_weights(cfg, l, e, dev)
+                q_in, s_in = moeq.moe_quantize_pack(w["w_in"], bits[e], cfg.group)
+                q_out, s_out = moeq.moe_quantize_pack(w["w_out"], bits[e], cfg.group)
+                q_g = s_g = None
+                if cfg.swiglu:
+                    q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], bits[e], cfg.group)
+                experts.append(moeq.PackedExpert(bits[e], q_in, s_in, q_out, s_out, q_g, s_g))
+                del w
+            Wr, bias = gen.router_weights(cfg, l, dev)
+            self.layers.append(moeq.Layer(cfg.d_model, cfg.d_ff, cfg.top_k, cfg.group, act, cfg.renorm, xdt, Wr,
+                                          bias, experts))
+            self.bits.append(bits)
+        torch.cuda.synchronize()
+        # hidden states of every (step, layer): [steps][L][batch][d]
+        self.x_all = torch.stack([torch.stack([gen.hidden(cfg, l, s, batch, dev) for l in range(self.L)])
+                                  for s in range(steps)])
+        self.xs = torch.empty_like(self.x_all[0])               # staging: the current step's inputs
+        self.y = torch.empty((self.L, batch, cfg.d_model), dtype=torch.float32, device=dev)
+        self.ws = torch.empty(max(l.workspace_bytes(batch) for l in self.layers), dtype=torch.uint8, device=dev)
+        self.packed_bytes = sum(e.nbytes() for l in self.layers for e in l.experts)
+
+    def routing(self):
+        """Top-k indices of every (step, layer, token), computed up front (untimed) for byte accounting."""
+        import torch
+        import paper_2308_14352_amd as moeq
+        out = []
+        for s in range(self.steps):
+            out.append(torch.stack([moeq.moe_router_topk(self.layers[l], self.x_all[s, l])[0]
+                                    for l in range(self.L)]))
+        torch.cuda.synchronize()
+        return torch.stack(out).cpu().numpy()                   # [steps][L][batch][k]
+
+    def algorithmic_bytes(self, idx):
+        """Bytes the path must move per (step, layer): packed codes+scales of the DISTINCT activated
+        experts, the router weights (+bias), the hidden states in and the outputs out."""
+        import numpy as np
+        cfg = self.cfg
+        xb = 2 if cfg.x_dtype == "bf16" else 4
+        per = np.zeros((self.steps, self.L))
+        for l, layer in enumerate(self.layers):
+            eb = np.array([e.nbytes() for e in layer.experts], dtype=np.float64)
+            fixed = layer.router_w.numel() * 4 + (0 if layer.router_bias is None else cfg.n_experts * 4) \
+                + self.batch * cfg.d_model * (xb + 4)
+            for s in range(self.steps):
+                per[s, l] = eb[np.unique(idx[s, l])].sum() + fixed
+        return per
+
+    def run_step_eager(self, s):
+        import paper_2308_14352_amd as moeq
+        self.xs.copy_(self.x_all[s])
+        for l in range(self.L):
+            moeq.moe_layer_forward(self.layers[l], self.xs[l], y=self.y[l], ws=self.ws)
+
+    def capture(self):
+        import torch
+        import paper_2308_14352_amd as moeq
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for l in range(self.L):
+                moeq.moe_layer_forward(self.layers[l], self.xs[l], y=self.y[l], ws=self.ws)
+        return g
+
+    def run_step_graph(self, g, s):
+        self.xs.copy_(self.x_all[s])
+        g.replay()
+
+
+def time_steps(stack, steps, warmup, use_graph):
+    import torch
+    g = None
+    stack.run_step_eager(0)                       # first call sets kernel attributes; never inside a capture
+    torch.cuda.synchronize()
+    if use_graph:
+        g = stack.capture()
+    run = (lambda s: stack.run_step_graph(g, s)) if use_graph else stack.run_step_eager
+    for s in range(warmup):
+        run(s % stack.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        run(s % stack.steps)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0), g
+
+
+def per_launch_events(stack, steps):
+    """Eager pass with a HIP event pair around every layer call, on the stream the kernels run on.
+    Returns the average duration in ms of one layer call (router + FFN kernels of one layer)."""
+    import torch
+    import paper_2308_14352_amd as moeq
+    st = torch.cuda.current_stream()
+    pairs = []
+    for s in range(steps):
+        stack.xs.copy_(stack.x_all[s % stack.steps])
+        for l in range(stack.L):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(st)
+            moeq.moe_layer_forward(stack.layers[l], stack.xs[l], y=stack.y[l], ws=stack.ws, stream=st)
+            b.record(st)
+            pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in pairs]
+    return sum(ms) / len(ms)
+
+
+def cpu_baseline(stack, dev, budget_layers):
+    """The CPU oracle on a bounded sample: `budget_layers` (step 0, layer l) pairs, each the full
+    paper-order path (decompress the activated experts to fp32, FFN, combine). The oracle quantizes its
+    own copy of the weights from the same fp32 bits; only its forward pass is timed."""
+    import numpy as np
+    import gen
+    import oracle
+    cfg = stack.cfg
+    total, n = 0.0, 0
+    for l in range(min(budget_layers, stack.L)):
+        Wr, bias = gen.router_weights(cfg, l, dev)
+        x = stack.x_all[0, l].float().cpu().numpy()
+        Wr_h = Wr.cpu().numpy()
+        b_h = None if bias is None else bias.cpu().numpy()
+        idx, _, _ = oracle.router_topk(x, Wr_h, b_h, cfg.top_k, cfg.renorm)
+        dummy = oracle.Expert(4, np.zeros(1, np.uint8), np.zeros(1, np.uint16), np.zeros(1, np.uint8),
+                              np.zeros(1, np.uint16), np.zeros(1, np.uint8), np.zeros(1, np.uint16))
+        experts = [dummy] * cfg.n_experts
+        for e in sorted(set(idx.flatten().tolist())):
+            w = {k: v.cpu().numpy() for k, v in gen.expert_weights(cfg, l, e, dev).items()}
+            b = stack.bits[l][e]
+            qi, si = oracle.quantize_pack(w["w_in"], b, cfg.group)
+            qo, so = oracle.quantize_pack(w["w_out"], b, cfg.group)
+            qg, sg = oracle.quantize_pack(w["w_gate"], b, cfg.group) if cfg.swiglu else (None, None)
+            experts[e] = oracle.Expert(b, qi, si, qo, so, qg, sg)
+            del w
+        t0 = time.perf_counter()
+        oracle.layer_forward(experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), cfg.top_k, cfg.renorm,
+                             Wr_h, b_h, x)
+        total += time.perf_counter() - t0
+        n += 1
+    per_layer = total / n
+    return {"value": stack.batch / (per_layer * stack.L), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"step 0 of layers 0..{n - 1} ({n} token-layers, batch {stack.batch}); "
+                      f"{per_layer * 1e3:.1f} ms per token-layer, scaled to the {stack.L}-layer stack"}
+
+
+WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8), "c4": ("c4", 1)}
+DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
+
+
+def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True):
+    import gen
+    cfg_id, batch = WORKLOADS[name]
+    cfg = gen.CONFIGS[cfg_id]
+    n_distinct = min(steps, cfg.steps)
+    stack = Stack(cfg, batch, n_distinct, dev, n_layers)
+    idx = stack.routing()
+    bytes_sl = stack.algorithmic_bytes(idx)
+    elapsed, _ = time_steps(stack, steps, warmup, use_graph)
+    # bytes over the timed steps (steps may wrap around the distinct inputs)
+    order = [s % n_distinct for s in range(steps)]
+    total_bytes = float(bytes_sl[order].sum())
+    res = {
+        "tokens_per_s": steps * batch / elapsed,
+        "layer_tokens_per_s": steps * batch * stack.L / elapsed,
+        "ms_per_step": elapsed / steps * 1e3,
+        "algorithmic_GBps": total_bytes / elapsed / 1e9,
+        "bytes_per_layer_call": total_bytes / (steps * stack.L),
+        "layers": stack.L, "batch": batch, "steps": steps,
+        "packed_GB": stack.packed_bytes / 1e9,
+    }
+    if want_events:
+        ms = per_launch_events(stack, min(steps, 64))
+        o2 = [s % n_distinct for s in range(min(steps, 64))]
+        res["layer_call_ms"] = ms
+        res["layer_call_bytes"] = float(bytes_sl[o2].mean())
+    if cfg.bias_rule == "hotset":
+        import numpy as np
+        hot_share = []
+        for l in range(stack.L):
+            hot = (stack.layers[l].router_bias > 0).cpu().numpy()
+            hot_share.append(hot[idx[:, l].reshape(-1)].mean())
+        res["hot_expert_share"] = float(np.mean(hot_share))
+    return stack, res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are not part of it",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import gen
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    name = args.workload
+    steps = args.steps or DEFAULT_STEPS[name]
+    use_graph = not args.no_graph
+    stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers)
+    cfg = stack.cfg
+    achieved = res["layer_call_bytes"] / (res["layer_call_ms"] * 1e-3) / 1e9
+    out = {
+        "metric": "decode MoE-layer tokens/s + achieved HBM GB/s on packed experts (% peak)",
+        "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{name}: {cfg.name}", "layers": stack.L, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+                   "experts": cfg.n_experts, "top_k": cfg.top_k, "act": cfg.act, "group": cfg.group,
+                   "batch": stack.batch, "x_dtype": cfg.x_dtype, "bitwidths": cfg.bit_rule,
+                   "packed_GB": round(res["packed_GB"], 3), "launch": "hip-graph" if use_graph else "eager"},
+        "layer_tokens_per_s": res["layer_tokens_per_s"],
+        "algorithmic_GBps": res["algorithmic_GBps"],
+        "pct_hbm_peak": 100.0 * res["algorithmic_GBps"] / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "moe_layer_forward (one call = the kernels of one layer)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "bytes_per_launch": res["layer_call_bytes"], "avg_launch_ms": res["layer_call_ms"],
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(stack, dev, 4 if name == "c4" else 12)
+    del stack
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        extras = {}
+        for other, k in (("c1", 64), ("c2", 256), ("c3", 128), ("c3b8", 128)):
+            if other == name:
+                continue
+            st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False)
+            extras[other] = {kk: r[kk] for kk in ("tokens_per_s", "layer_tokens_per_s", "ms_per_step",
+                                                  "algorithmic_GBps", "layers", "batch", "steps", "packed_GB")
+                             if kk in r}
+            if "hot_expert_share" in r:
+                extras[other]["hot_expert_share"] = r["hot_expert_share"]
+            del st
+            torch.cuda.empty_cache()
+        out["other_workloads"] = extras
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -108,9 +108,10 @@ size_t moe_packed_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group,
  * expert index, results in descending gate order), gates per `renorm` (Section 1; Section 2.1).
  * x: dev [n_tokens][d_model] in the layer's x_dtype. topk_idx: dev [n_tokens][top_k] int32.
  * topk_gate: dev [n_tokens][top_k] fp32. probs_opt: dev [n_tokens][n_experts] fp32 or NULL.
- * n_tokens == 0 is a no-op. */
+ * ws holds the logits between the two kernels. n_tokens == 0 is a no-op. */
 moeq_status moe_router_topk(const moeq_layer *layer, const void *x, int32_t n_tokens,
-                            int32_t *topk_idx, float *topk_gate, float *probs_opt, void *stream);
+                            int32_t *topk_idx, float *topk_gate, float *probs_opt, void *ws,
+                            size_t ws_bytes, void *stream);
 
 /* One expert's dequantize-fused FFN on n_tokens tokens (Section 3.2: decompress, then use):
  * y[t] (+)= gate[t] * W_out^ act(W_in^ x[t]). gate_opt: dev [n_tokens] fp32 or NULL (= 1).

@@ -63,7 +63,7 @@ def lib():
     L.moe_workspace_bytes.restype = sz
     L.moe_workspace_bytes.argtypes = [vp, i32]
     L.moe_router_topk.restype = C.c_int
-    L.moe_router_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.moe_router_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.moe_expert_ffn_q.restype = C.c_int
     L.moe_expert_ffn_q.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, sz, vp]
     L.moe_layer_forward.restype = C.c_int
@@ -199,14 +199,16 @@ class Layer:
         return self._ws
 
 
-def moe_router_topk(layer, x, want_probs=False, stream=None):
+def moe_router_topk(layer, x, want_probs=False, ws=None, stream=None):
     T = x.shape[0]
     dev = x.device
+    if ws is None:
+        ws = layer.workspace(T)
     idx = torch.empty((T, layer.top_k), dtype=torch.int32, device=dev)
     gate = torch.empty((T, layer.top_k), dtype=torch.float32, device=dev)
     probs = torch.empty((T, layer.n_experts), dtype=torch.float32, device=dev) if want_probs else None
-    _check(lib().moe_router_topk(layer.handle, _ptr(x), T, _ptr(idx), _ptr(gate), _ptr(probs), _stream(stream)),
-           "moe_router_topk")
+    _check(lib().moe_router_topk(layer.handle, _ptr(x), T, _ptr(idx), _ptr(gate), _ptr(probs), _ptr(ws), ws.numel(),
+                                 _stream(stream)), "moe_router_topk")
     return (idx, gate, probs) if want_probs else (idx, gate)
 
 

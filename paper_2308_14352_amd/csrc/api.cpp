@@ -30,7 +30,7 @@ inline bool group_ok(int32_t g, int32_t bits) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {
-  size_t idx_off, gate_off, h_off, total;
+  size_t idx_off, gate_off, logits_off, h_off, total;
 };
 
 WsLayout ws_layout(const LayerDims& L, int64_t T) {
@@ -38,7 +38,8 @@ WsLayout ws_layout(const LayerDims& L, int64_t T) {
   const size_t slots = (size_t)T * L.top_k;
   w.idx_off = 0;
   w.gate_off = align_up(slots * sizeof(int32_t), 256);
-  w.h_off = w.gate_off + align_up(slots * sizeof(float), 256);
+  w.logits_off = w.gate_off + align_up(slots * sizeof(float), 256);
+  w.h_off = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
   w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(float), 256);
   return w;
 }
@@ -126,13 +127,19 @@ size_t moe_workspace_bytes(const moeq_layer* layer, int32_t max_tokens) {
 }
 
 moeq_status moe_router_topk(const moeq_layer* layer, const void* x, int32_t n_tokens, int32_t* topk_idx,
-                            float* topk_gate, float* probs_opt, void* stream) {
+                            float* topk_gate, float* probs_opt, void* ws, size_t ws_bytes, void* stream) {
   if (!layer || n_tokens < 0) return MOEQ_EINVAL;
   if (n_tokens == 0) return MOEQ_OK;
   if (!x || !topk_idx || !topk_gate || ((uintptr_t)x & 15u)) return MOEQ_EINVAL;
   if (n_tokens > 65535) return MOEQ_EUNSUPPORTED;
-  return dev(launch_router_topk(layer->dims, layer->router_w, layer->router_bias, x, n_tokens, topk_idx,
-                                topk_gate, probs_opt, (hipStream_t)stream));
+  const WsLayout w = ws_layout(layer->dims, n_tokens);
+  if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
+  if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
+  float* logits = (float*)((char*)ws + w.logits_off);
+  hipStream_t st = (hipStream_t)stream;
+  if (launch_router_logits(layer->dims, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
+    return MOEQ_EDEVICE;
+  return dev(launch_topk(layer->dims, logits, n_tokens, topk_idx, topk_gate, probs_opt, st));
 }
 
 moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void* x, int32_t n_tokens,
@@ -148,7 +155,7 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
   float* h = (float*)((char*)ws + w.h_off);
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, expert, x, n_tokens, h, st);
+  hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, nullptr, nullptr, expert, x, n_tokens, h, st);
   if (e != hipSuccess) return MOEQ_EDEVICE;
   return dev(launch_ffn_out(layer->dims, layer->table, nullptr, gate_opt, expert, accumulate ? 1 : 0, h,
                             n_tokens, y, st));
@@ -169,9 +176,10 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   float* gate = topk_gate_opt ? topk_gate_opt : (float*)((char*)ws + w.gate_off);
   float* h = (float*)((char*)ws + w.h_off);
   hipStream_t st = (hipStream_t)stream;
-  if (launch_router_topk(L, layer->router_w, layer->router_bias, x, n_tokens, idx, gate, nullptr, st) != hipSuccess)
+  float* logits = (float*)((char*)ws + w.logits_off);
+  if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
-  if (launch_ffn_in(L, layer->table, idx, -1, x, n_tokens * L.top_k, h, st) != hipSuccess) return MOEQ_EDEVICE;
+  if (launch_ffn_in(L, layer->table, logits, idx, gate, -1, x, n_tokens, h, st) != hipSuccess) return MOEQ_EDEVICE;
   return dev(launch_ffn_out(L, layer->table, idx, gate, -1, 0, h, n_tokens, y, st));
 }
 

@@ -25,16 +25,21 @@ struct LayerDims {
 };
 
 // Launchers (defined in the .hip files). All enqueue on `st` and return the launch status.
-hipError_t launch_router_topk(const LayerDims& L, const float* router_w, const float* router_bias,
-                              const void* x, int32_t T, int32_t* idx, float* gate, float* probs,
-                              hipStream_t st);
 
-// Phase 1 of the expert FFN for `slots` (token, choice) pairs: h[slot][f] = act(W_in x [, W_gate x]).
-// fixed_expert >= 0: every slot uses that expert and slot == token; else expert = idx[slot],
-// token = slot / top_k.
-hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const int32_t* idx,
-                         int32_t fixed_expert, const void* x, int32_t slots, float* h,
-                         hipStream_t st);
+// logits[t][e] = router_w[e] . x[t] (+ bias[e])
+hipError_t launch_router_logits(const LayerDims& L, const float* router_w, const float* router_bias,
+                                const void* x, int32_t T, float* logits, hipStream_t st);
+// softmax + top-k of every token from its logits
+hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32_t* idx, float* gate,
+                       float* probs, hipStream_t st);
+
+// Phase 1 of the expert FFN: h[slot][f] = act(W_in x [, W_gate x]).
+// fixed_expert >= 0: every token uses that expert (slot == token). Otherwise each workgroup derives
+// the token's top-k from `logits`, the routing is also written to idx_out/gate_out, and
+// slot = token * top_k + j.
+hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits,
+                         int32_t* idx_out, float* gate_out, int32_t fixed_expert, const void* x,
+                         int32_t T, float* h, hipStream_t st);
 
 // Phase 2 + combine: y[t] (+)= sum_j gate * W_out h[slot].
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx,

@@ -106,7 +106,7 @@ def test_layer_create_rejects_bad_experts():
 
 def test_compute_entry_points_reject_null_handles_and_shapes():
     L = B.lib()
-    assert L.moe_router_topk(None, None, 1, None, None, None, None) == B.MOEQ_EINVAL
+    assert L.moe_router_topk(None, None, 1, None, None, None, None, 0, None) == B.MOEQ_EINVAL
     assert L.moe_layer_forward(None, None, 1, None, None, None, None, 0, None) == B.MOEQ_EINVAL
     assert L.moe_expert_ffn_q(None, 0, None, 1, None, 0, None, None, 0, None) == B.MOEQ_EINVAL
     assert L.moe_quantize_pack(None, 1, 64, 4, 32, None, None, None) == B.MOEQ_EINVAL
