@@ -9,7 +9,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmoeq.so")
+# MOEQ_LIB lets a developer point the binding at another build of the same library.
+LIB_PATH = os.environ.get("MOEQ_LIB") or os.path.join(_HERE, "libmoeq.so")
 
 MOEQ_OK, MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EWORKSPACE, MOEQ_EDEVICE = range(5)
 MOEQ_ACT_RELU, MOEQ_ACT_SWIGLU = 0, 1

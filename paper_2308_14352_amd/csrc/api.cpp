@@ -40,7 +40,7 @@ WsLayout ws_layout(const LayerDims& L, int64_t T) {
   w.gate_off = align_up(slots * sizeof(int32_t), 256);
   w.logits_off = w.gate_off + align_up(slots * sizeof(float), 256);
   w.h_off = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
-  w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(float), 256);
+  w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
   return w;
 }
 
@@ -153,7 +153,7 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   const WsLayout w = ws_layout(layer->dims, n_tokens);
   if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
-  float* h = (float*)((char*)ws + w.h_off);
+  uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, nullptr, nullptr, expert, x, n_tokens, h, st);
   if (e != hipSuccess) return MOEQ_EDEVICE;
@@ -174,7 +174,7 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
   int32_t* idx = topk_idx_opt ? topk_idx_opt : (int32_t*)((char*)ws + w.idx_off);
   float* gate = topk_gate_opt ? topk_gate_opt : (float*)((char*)ws + w.gate_off);
-  float* h = (float*)((char*)ws + w.h_off);
+  uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   hipStream_t st = (hipStream_t)stream;
   float* logits = (float*)((char*)ws + w.logits_off);
   if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)

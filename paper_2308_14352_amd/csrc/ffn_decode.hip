@@ -14,11 +14,12 @@
 //
 // Work split. P lanes of a wavefront share a row (P = the largest power of two dividing the chunks
 // per row, at most 64); a lane walks its chunks j = p, p+P, ... and, for each, NR rows that share the
-// activation registers (for SwiGLU the rows of w1 and w3 are interleaved as "virtual rows"). Loads
-// run D tiles ahead of the arithmetic through a register ring. Row totals are folded across the P
-// lanes with a transposing butterfly (about one shuffle per row). A workgroup owns a fixed range of
-// output rows for all k chosen experts of its token, so the gate-weighted sum over the experts is
-// ordered and needs no atomics.
+// activation registers (for SwiGLU the rows of w1 and w3 count as separate "virtual rows"). The
+// loads of the next block of tiles are issued before the arithmetic of the current one, across task
+// boundaries, so a wavefront always has 4 to 8 loads in flight. Row totals are folded across the P
+// lanes with a transposing butterfly on DPP. A workgroup owns a fixed range of output rows for all
+// k chosen experts of its token, so the gate-weighted sum over the experts is ordered and needs no
+// atomics.
 #include <hip/hip_fp16.h>
 
 #include <type_traits>
@@ -29,8 +30,18 @@ namespace moeq {
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+// 16-byte load with the non-temporal hint: packed weights are read once per call and should not
+// displace the activations and scales that are reused from the caches.
+__device__ __forceinline__ uint4 load_stream16(const uint8_t* ptr) {
+  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)ptr);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float v) { return (uint32_t)__half_as_ushort(__float2half_rn(v)); }
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) { return __half2float(__ushort_as_half((uint16_t)h)); }
 
 template <int BITS>
 struct Fmt {
@@ -87,62 +98,140 @@ __device__ __forceinline__ float dword_dot(uint32_t w, const uint32_t* xr, float
   return acc;
 }
 
-// Stage `cols` activations into LDS for BITS: pair register pi of chunk c goes to word
-// ((pi/4) * C + c) * 4 + pi%4, so a lane's 128-bit reads of consecutive chunks are conflict-free.
-// XK[c * spc + j] = 2^(b-1) * 2^-24 * (sum of the binary16-rounded activations of scale slice j of chunk c).
-template <int BITS, typename LoadX>
-__device__ __forceinline__ void stage_x(LoadX load, int cols, int group, uint32_t* XP, float* XK) {
+// ---------------------------------------------------------------------------------------------
+// Activation staging. Phase 1 (copy_x_to_lds): the activation vector goes to LDS as linear binary16
+// (RAW) with 16-byte accesses. Phase 2 (permute_x): pair register pi of chunk c goes to word
+// ((pi/4) * C + c) * 4 + pi%4 of XP, so a lane's 128-bit reads of consecutive chunks are
+// conflict-free, and XK[c * spc + j] = 2^(b-1) * 2^-24 * (sum of the activations of scale slice j of
+// chunk c). Callers put a barrier between the phases and after phase 2.
+enum XKind { X_F32 = 0, X_BF16 = 1, X_F16 = 2 };
+
+__device__ __forceinline__ void copy_x_to_lds(const void* __restrict__ x, int kind, int cols, int tid, int nthreads,
+                                              uint16_t* RAW) {
+  uint4* RAW4 = (uint4*)RAW;
+  for (int i = tid; i < cols / 8; i += nthreads) {
+    uint4 o;
+    if (kind == X_F16) {
+      o = ((const uint4*)x)[i];
+    } else if (kind == X_BF16) {
+      const uint4 v = ((const uint4*)x)[i];
+      const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+      uint32_t out[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        out[k] = f32_to_f16_bits(bf16_bits_to_f32(in[k] & 0xffffu)) | (f32_to_f16_bits(bf16_bits_to_f32(in[k] >> 16)) << 16);
+      o = make_uint4(out[0], out[1], out[2], out[3]);
+    } else {
+      const float4 a = ((const float4*)x)[2 * i], b = ((const float4*)x)[2 * i + 1];
+      o = make_uint4(f32_to_f16_bits(a.x) | (f32_to_f16_bits(a.y) << 16), f32_to_f16_bits(a.z) | (f32_to_f16_bits(a.w) << 16),
+                     f32_to_f16_bits(b.x) | (f32_to_f16_bits(b.y) << 16), f32_to_f16_bits(b.z) | (f32_to_f16_bits(b.w) << 16));
+    }
+    RAW4[i] = o;
+  }
+}
+
+template <int BITS>
+__device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int group, int tid, int nthreads,
+                                          uint32_t* XP, float* XK) {
   constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
   const int C = cols / WPC;
-  for (int i = threadIdx.x; i < cols / 2; i += blockDim.x) {
+  for (int i = tid; i < cols / 2; i += nthreads) {
     const int c = i / PPC, pi = i % PPC;
     int lo, hi;
     float ps;
     pair_pos<BITS>(pi, lo, hi, ps);
-    const float xl = __half2float(__float2half_rn(load(c * WPC + lo)));
-    const float xh = __half2float(__float2half_rn(load(c * WPC + hi)));
-    const uint32_t bl = __half_as_ushort(__float2half_rn(xl * ps));
-    const uint32_t bh = __half_as_ushort(__float2half_rn(xh * ps));
+    const uint32_t bl = f32_to_f16_bits(f16_bits_to_f32(RAW[c * WPC + lo]) * ps);
+    const uint32_t bh = f32_to_f16_bits(f16_bits_to_f32(RAW[c * WPC + hi]) * ps);
     XP[((pi >> 2) * C + c) * 4 + (pi & 3)] = bl | (bh << 16);
   }
-  const int sub = group < WPC ? group : WPC;
-  const int spc = WPC / sub;  // scale slices per chunk: 1, or 2 for INT2 with group 32
-  for (int s = threadIdx.x; s < C * spc; s += blockDim.x) {
+  const int sub = group < WPC ? group : WPC;   // 16, 32 or 64 weights share a scale inside a chunk
+  const uint4* RAW4 = (const uint4*)RAW;
+  for (int s = tid; s < cols / sub; s += nthreads) {
     float acc = 0.f;
-    for (int i = 0; i < sub; ++i) acc += __half2float(__float2half_rn(load(s * sub + i)));
+    for (int i = 0; i < sub / 8; ++i) {
+      const uint4 v = RAW4[s * (sub / 8) + i];
+      acc += (f16_bits_to_f32(v.x & 0xffffu) + f16_bits_to_f32(v.x >> 16)) + (f16_bits_to_f32(v.y & 0xffffu) + f16_bits_to_f32(v.y >> 16));
+      acc += (f16_bits_to_f32(v.z & 0xffffu) + f16_bits_to_f32(v.z >> 16)) + (f16_bits_to_f32(v.w & 0xffffu) + f16_bits_to_f32(v.w >> 16));
+    }
     XK[s] = acc * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
   }
-  __syncthreads();
 }
 
-struct Tile {
-  uint4 w;
-  uint32_t s;  // one binary16 scale, or two adjacent ones (INT2 with group 32)
-};
+// ---------------------------------------------------------------------------------------------
+// Cross-lane helpers on DPP (data-parallel primitives: one instruction, no LDS round trip).
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kDppRor4 = 0x124;  // row_ror:4  (rotation inside a 16-lane row)
+constexpr int kDppRor8 = 0x128;  // row_ror:8
 
-// Sum over the P lanes of a row group (P a power of two, lanes of a group are contiguous) of NM*NRM row
-// totals per lane; v = m*NRM + i. Needs NRM <= P. Afterwards every lane holds, in v[m*NRM] (m < NM), the
-// group totals of row i = lane & (NRM-1) of matrix m.
+// Sum over the P lanes of a row group (P a power of two, groups are contiguous lanes) of NM*NRM row
+// totals per lane; v = m*NRM + i, NRM <= min(P, 4). Afterwards every lane holds, in v[m*NRM] (m < NM),
+// the group total of row i = lane & (NRM-1) of matrix m.
 template <int NRM, int NM>
 __device__ __forceinline__ void fold_rows(float (&v)[NRM * NM], int P, int lane) {
-  int off = 1;
-#pragma unroll
-  for (int n = NRM; n > 1; n >>= 1) {  // transposing steps: halve the number of live rows per lane
-    const bool upper = (lane & off) != 0;
+  static_assert(NRM == 1 || NRM == 2 || NRM == 4, "transposing steps use the two quad permutes only");
+  if (NRM >= 2) {  // transposing step on lane bit 0
+    const bool upper = (lane & 1) != 0;
 #pragma unroll
     for (int m = 0; m < NM; ++m)
 #pragma unroll
-      for (int i = 0; i < n / 2; ++i) {
+      for (int i = 0; i < NRM / 2; ++i) {
         const float a = v[m * NRM + 2 * i], b = v[m * NRM + 2 * i + 1];
-        const float keep = upper ? b : a, send = upper ? a : b;
-        v[m * NRM + i] = keep + __shfl_xor(send, off, 64);
+        v[m * NRM + i] = (upper ? b : a) + dpp<kDppXor1>(upper ? a : b);
       }
-    off <<= 1;
   }
-  for (; off < P; off <<= 1) {
+  if (NRM >= 4) {  // transposing step on lane bit 1
+    const bool upper = (lane & 2) != 0;
 #pragma unroll
-    for (int m = 0; m < NM; ++m) v[m * NRM] += __shfl_xor(v[m * NRM], off, 64);
+    for (int m = 0; m < NM; ++m) {
+      const float a = v[m * NRM], b = v[m * NRM + 1];
+      v[m * NRM] = (upper ? b : a) + dpp<kDppXor2>(upper ? a : b);
+    }
   }
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    float t = v[m * NRM];
+    if (NRM < 2 && P >= 2) t += dpp<kDppXor1>(t);
+    if (NRM < 4 && P >= 4) t += dpp<kDppXor2>(t);
+    if (P >= 16) {
+      t += dpp<kDppRor4>(t);
+      t += dpp<kDppRor8>(t);
+    } else if (P == 8) {
+      t += __shfl_xor(t, 4, 64);
+    }
+    if (P >= 32) t += __shfl_xor(t, 16, 64);
+    if (P >= 64) t += __shfl_xor(t, 32, 64);
+    v[m * NRM] = t;
+  }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp<kDppXor1>(v));
+  v = fmaxf(v, dpp<kDppXor2>(v));
+  v = fmaxf(v, dpp<kDppRor4>(v));
+  v = fmaxf(v, dpp<kDppRor8>(v));
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp<kDppXor1>(v);
+  v += dpp<kDppXor2>(v);
+  v += dpp<kDppRor4>(v);
+  v += dpp<kDppRor8>(v);
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
 }
 
 // A pointer that is the same in every lane, moved to scalar registers so that loads can use the
@@ -155,94 +244,130 @@ __device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
   return (const T*)(((uint64_t)hi << 32) | lo);
 }
 
-// One wavefront task: NRM rows (per lane group) of each of NM matrices, all chunks of those rows.
-// row0 = first row of this lane's group; rows are row0 + i*RW, clamped to nrows-1 for the loads.
-// Tiles (one 16-byte chunk of one row + its scale) are processed in blocks of kBlock; the loads of the
-// next block are issued before the arithmetic of the current one (double buffering in registers).
-constexpr int kBlock = 4;
+// ---------------------------------------------------------------------------------------------
+struct Tile {
+  uint4 w;
+  uint32_t s;  // one binary16 scale, or two adjacent ones (INT2 with group 32)
+};
+constexpr int kBlock = 4;  // tiles per block; one block is computed while the next is in flight
 
-template <int BITS, int NRM, int NM, bool TWO>
-__device__ __forceinline__ void gemv_task(const uint8_t* const (&q)[NM], const uint16_t* const (&s)[NM], int cols,
-                                          int group, int P, int p, int row0, int RW, int nrows,
-                                          const uint32_t* XP, const float* XK, float (&tot)[NRM * NM]) {
+// All tasks of one wavefront for one expert. A task is NRM rows (per lane group) of each of NM
+// matrices: rows r0 + i*RW + rsub, i < NRM, with r0 = row_begin + (wave + k*nwaves) * RW*NRM.
+// epilogue(row, totals[NM]) is called by one lane per finished row (row < row_end guaranteed).
+template <int BITS, int NRM, int NM, bool TWO, typename Epilogue>
+__device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const uint16_t* const (&s)[NM], int cols,
+                                            int group, int nrows, int row_begin, int row_end, int lane, int wave,
+                                            int nwaves, const uint32_t* XP, const float* XK, Epilogue epilogue) {
   constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
   constexpr int NR = NRM * NM;
   static_assert(NR <= kBlock && kBlock % NR == 0, "rows in flight must divide the block");
-  constexpr int CPB = kBlock / NR;  // chunks per block
+  constexpr int CPB = kBlock / NR;  // chunk steps per block
   const int C = cols / WPC;
+  int P = 1;
+  while (P < 64 && C % (P * 2) == 0) P *= 2;
+  const int RW = 64 / P;
+  const int p = lane % P, rsub = lane / P;
   const int J = C / P;
   const int ng = cols / group;
+  const int task_rows = RW * NRM;
+  const int n_tasks = (row_end - row_begin + task_rows - 1) / task_rows;
+  const int n_my = wave < n_tasks ? (n_tasks - wave + nwaves - 1) / nwaves : 0;
+  const int S = n_my * J;  // chunk steps of this wavefront
+  if (S == 0) return;
   const uint4* XP4 = (const uint4*)XP;
-
-  uint32_t qoff[NR], soff[NR];
-#pragma unroll
-  for (int v = 0; v < NR; ++v) {
-    int row = row0 + (v % NRM) * RW;
-    row = row < nrows ? row : nrows - 1;
-    qoff[v] = (uint32_t)row * (uint32_t)(C * 16) + (uint32_t)p * 16u;
-    soff[v] = ((uint32_t)row * (uint32_t)ng) * 2u;   // bytes
-    tot[v] = 0.f;
-  }
   const uint32_t jstride = (uint32_t)P * 16u;
-  auto load_tile = [&](int j, int v) {
-    Tile t;
-    const int m = v / NRM;
-    t.w = *(const uint4*)(q[m] + (qoff[v] + (uint32_t)j * jstride));
-    const uint32_t g0 = (uint32_t)((p + j * P) * WPC) / (uint32_t)group;
-    const uint8_t* sb = (const uint8_t*)s[m];
-    if (TWO) t.s = *(const uint32_t*)(sb + (soff[v] + g0 * 2u));
-    else t.s = *(const uint16_t*)(sb + (soff[v] + g0 * 2u));
-    return t;
+  const uint32_t row_bytes = (uint32_t)C * 16u;
+
+  // prefetch cursor
+  int pk = 0, pj = 0;
+  uint32_t qoff[NR], soff[NR];
+  auto load_step = [&](Tile (&t)[kBlock], int u0) {
+    if (pj == 0) {
+      const int r0 = row_begin + (wave + pk * nwaves) * task_rows + rsub;
+#pragma unroll
+      for (int v = 0; v < NR; ++v) {
+        int row = r0 + (v % NRM) * RW;
+        row = row < nrows ? row : nrows - 1;
+        qoff[v] = (uint32_t)row * row_bytes + (uint32_t)p * 16u;
+        soff[v] = ((uint32_t)row * (uint32_t)ng) * 2u;
+      }
+    }
+    const uint32_t g0 = ((uint32_t)((p + pj * P) * WPC) / (uint32_t)group) * 2u;
+#pragma unroll
+    for (int v = 0; v < NR; ++v) {
+      const int m = v / NRM;
+      t[u0 + v].w = load_stream16(q[m] + (qoff[v] + (uint32_t)pj * jstride));
+      const uint8_t* sb = (const uint8_t*)s[m];
+      if (TWO) t[u0 + v].s = *(const uint32_t*)(sb + (soff[v] + g0));
+      else t[u0 + v].s = *(const uint16_t*)(sb + (soff[v] + g0));
+    }
+    if (++pj == J) { pj = 0; ++pk; }
   };
   auto load_block = [&](Tile (&t)[kBlock], int blk) {
 #pragma unroll
-    for (int u = 0; u < kBlock; ++u) {
-      const int j = blk * CPB + u / NR;
-      if (j < J) t[u] = load_tile(j, u % NR);
-    }
-  };
-  uint32_t xr[PPC];
-  float k0 = 0.f, k1 = 0.f;
-  auto compute_block = [&](const Tile (&t)[kBlock], int blk) {
-#pragma unroll
-    for (int u = 0; u < kBlock; ++u) {
-      const int j = blk * CPB + u / NR;
-      const int v = u % NR;
-      if (j < J) {
-        if (v == 0) {  // new chunk: fetch its activation pairs and offset terms
-          const int c = p + j * P;
-#pragma unroll
-          for (int qq = 0; qq < PPC / 4; ++qq) {
-            const uint4 t4 = XP4[qq * C + c];
-            xr[4 * qq] = t4.x; xr[4 * qq + 1] = t4.y; xr[4 * qq + 2] = t4.z; xr[4 * qq + 3] = t4.w;
-          }
-          if (TWO) { k0 = XK[2 * c]; k1 = XK[2 * c + 1]; }
-          else k0 = XK[c];
-        }
-        const uint4 w = t[u].w;
-        const uint32_t sraw = t[u].s;
-        if (TWO) {
-          float a0 = dword_dot<BITS>(w.x, &xr[0], 0.f);
-          a0 = dword_dot<BITS>(w.y, &xr[PPC / 4], a0);
-          float a1 = dword_dot<BITS>(w.z, &xr[PPC / 2], 0.f);
-          a1 = dword_dot<BITS>(w.w, &xr[3 * PPC / 4], a1);
-          const float s0 = __half2float(__ushort_as_half((uint16_t)(sraw & 0xffffu))) * 16777216.0f;
-          const float s1 = __half2float(__ushort_as_half((uint16_t)(sraw >> 16))) * 16777216.0f;
-          tot[v] = fmaf(s0, a0 - k0, tot[v]);
-          tot[v] = fmaf(s1, a1 - k1, tot[v]);
-        } else {
-          float a = dword_dot<BITS>(w.x, &xr[0], 0.f);
-          a = dword_dot<BITS>(w.y, &xr[PPC / 4], a);
-          a = dword_dot<BITS>(w.z, &xr[PPC / 2], a);
-          a = dword_dot<BITS>(w.w, &xr[3 * PPC / 4], a);
-          const float s0 = __half2float(__ushort_as_half((uint16_t)(sraw & 0xffffu))) * 16777216.0f;
-          tot[v] = fmaf(s0, a - k0, tot[v]);
-        }
-      }
-    }
+    for (int c = 0; c < CPB; ++c)
+      if (blk * CPB + c < S) load_step(t, c * NR);
   };
 
-  const int nblocks = (J + CPB - 1) / CPB;
+  // compute cursor
+  int ck = 0, cj = 0;
+  float tot[NR];
+  auto compute_step = [&](const Tile (&t)[kBlock], int u0) {
+    if (cj == 0) {
+#pragma unroll
+      for (int v = 0; v < NR; ++v) tot[v] = 0.f;
+    }
+    uint32_t xr[PPC];
+    const int c = p + cj * P;
+#pragma unroll
+    for (int qq = 0; qq < PPC / 4; ++qq) {
+      const uint4 t4 = XP4[qq * C + c];
+      xr[4 * qq] = t4.x; xr[4 * qq + 1] = t4.y; xr[4 * qq + 2] = t4.z; xr[4 * qq + 3] = t4.w;
+    }
+    float k0, k1 = 0.f;
+    if (TWO) { k0 = XK[2 * c]; k1 = XK[2 * c + 1]; }
+    else k0 = XK[c];
+#pragma unroll
+    for (int v = 0; v < NR; ++v) {
+      const uint4 w = t[u0 + v].w;
+      const uint32_t sraw = t[u0 + v].s;
+      if (TWO) {
+        float a0 = dword_dot<BITS>(w.x, &xr[0], 0.f);
+        a0 = dword_dot<BITS>(w.y, &xr[PPC / 4], a0);
+        float a1 = dword_dot<BITS>(w.z, &xr[PPC / 2], 0.f);
+        a1 = dword_dot<BITS>(w.w, &xr[3 * PPC / 4], a1);
+        tot[v] = fmaf(f16_bits_to_f32(sraw & 0xffffu) * 16777216.0f, a0 - k0, tot[v]);
+        tot[v] = fmaf(f16_bits_to_f32(sraw >> 16) * 16777216.0f, a1 - k1, tot[v]);
+      } else {
+        float a = dword_dot<BITS>(w.x, &xr[0], 0.f);
+        a = dword_dot<BITS>(w.y, &xr[PPC / 4], a);
+        a = dword_dot<BITS>(w.z, &xr[PPC / 2], a);
+        a = dword_dot<BITS>(w.w, &xr[3 * PPC / 4], a);
+        tot[v] = fmaf(f16_bits_to_f32(sraw & 0xffffu) * 16777216.0f, a - k0, tot[v]);
+      }
+    }
+    if (++cj == J) {
+      fold_rows<NRM, NM>(tot, P, lane);
+      if (p < NRM) {
+        const int row = row_begin + (wave + ck * nwaves) * task_rows + p * RW + rsub;
+        if (row < row_end) {
+          float r[NM];
+#pragma unroll
+          for (int m = 0; m < NM; ++m) r[m] = tot[m * NRM];
+          epilogue(row, r);
+        }
+      }
+      cj = 0;
+      ++ck;
+    }
+  };
+  auto compute_block = [&](const Tile (&t)[kBlock], int blk) {
+#pragma unroll
+    for (int c = 0; c < CPB; ++c)
+      if (blk * CPB + c < S) compute_step(t, c * NR);
+  };
+
+  const int nblocks = (S + CPB - 1) / CPB;
   Tile bufA[kBlock], bufB[kBlock];
   load_block(bufA, 0);
   for (int blk = 0; blk < nblocks; blk += 2) {
@@ -261,8 +386,8 @@ __host__ __device__ inline int lanes_per_row(int chunks) {
   return P;
 }
 
-// Rows per lane group and matrix in one task: as many (1, 2 or 4) as still leave every wavefront of the
-// workgroup a task, and never more than P (the fold needs NRM <= P).
+// Rows per lane group and matrix in one task: as many (up to nrm_max) as still leave every wavefront of
+// the workgroup a task, and never more than P (the fold needs NRM <= P).
 __host__ __device__ inline int pick_nrm(int rows_in_wg, int RW, int nwaves, int P, int nrm_max) {
   int nrm = nrm_max;
   while (nrm > 1 && (nrm > P || rows_in_wg < RW * nrm * nwaves)) nrm >>= 1;
@@ -270,54 +395,49 @@ __host__ __device__ inline int pick_nrm(int rows_in_wg, int RW, int nwaves, int 
 }
 
 // ---------------------------------------------------------------------------------------------
-// softmax + top-k of one token from its logits, by wavefront 0 of a workgroup. E <= 1024.
-// Writes sel_e[0..k), sel_g[0..k) (LDS or global) from lane 0; probs (global, may be null) from all lanes.
-__device__ __forceinline__ void topk_from_logits(const float* __restrict__ lg, int E, int k, int renorm, int lane,
-                                                 int* sel_e, float* sel_g, float* __restrict__ probs) {
-  constexpr int kMaxPerLane = 16;
-  float v[kMaxPerLane];
+// softmax + top-k of one token from its logits, by ONE wavefront (all 64 lanes call this). E <= 64*MPL.
+// Lane 0 writes sel_e[0..k), sel_g[0..k); all lanes write probs (may be null).
+template <int MPL>
+__device__ __forceinline__ void topk_impl(const float* __restrict__ lg, int E, int k, int renorm, int lane, int* sel_e,
+                                          float* sel_g, float* __restrict__ probs) {
+  float v[MPL];
   float m = -INFINITY;
 #pragma unroll
-  for (int j = 0; j < kMaxPerLane; ++j) {
+  for (int j = 0; j < MPL; ++j) {
     const int e = lane + 64 * j;
     v[j] = e < E ? lg[e] : -INFINITY;
     m = fmaxf(m, v[j]);
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  m = wave_max(m);
   float z = 0.f;
 #pragma unroll
-  for (int j = 0; j < kMaxPerLane; ++j)
+  for (int j = 0; j < MPL; ++j)
     if (lane + 64 * j < E) z += expf(v[j] - m);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) z += __shfl_xor(z, off, 64);
+  z = wave_sum(z);
   const float inv_z = 1.0f / z;
   if (probs) {
 #pragma unroll
-    for (int j = 0; j < kMaxPerLane; ++j)
+    for (int j = 0; j < MPL; ++j)
       if (lane + 64 * j < E) probs[lane + 64 * j] = expf(v[j] - m) * inv_z;
   }
-  // k selection passes on the logits (same order as on the probabilities): largest value, ties to the
-  // lowest expert index.
+  // k selection passes on the logits (same order as on the probabilities): the largest value, ties to
+  // the lowest expert index = the lowest (j, lane) holding that value.
   float sp[8];
   int se[8];
   float sum = 0.f;
   for (int r = 0; r < k; ++r) {
     float bv = -INFINITY;
-    int be = 0x7fffffff;
 #pragma unroll
-    for (int j = 0; j < kMaxPerLane; ++j) {
-      const int e = lane + 64 * j;
-      if (e < E && (v[j] > bv)) { bv = v[j]; be = e; }  // ascending e per lane: '>' keeps the lowest
+    for (int j = 0; j < MPL; ++j) bv = fmaxf(bv, v[j]);
+    bv = wave_max(bv);
+    int be = -1;
+#pragma unroll
+    for (int j = 0; j < MPL; ++j) {
+      const unsigned long long mask = __ballot(v[j] == bv && (lane + 64 * j) < E);
+      if (be < 0 && mask != 0ull) be = 64 * j + (__ffsll((long long)mask) - 1);
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const float ov = __shfl_xor(bv, off, 64);
-      const int oe = __shfl_xor(be, off, 64);
-      if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
-    }
-#pragma unroll
-    for (int j = 0; j < kMaxPerLane; ++j)
+    for (int j = 0; j < MPL; ++j)
       if (lane + 64 * j == be) v[j] = -INFINITY;
     sp[r] = expf(bv - m) * inv_z;
     se[r] = be;
@@ -328,6 +448,13 @@ __device__ __forceinline__ void topk_from_logits(const float* __restrict__ lg, i
       sel_e[r] = se[r];
       sel_g[r] = renorm ? sp[r] / sum : sp[r];
     }
+}
+
+__device__ __forceinline__ void topk_from_logits(const float* __restrict__ lg, int E, int k, int renorm, int lane,
+                                                 int* sel_e, float* sel_g, float* __restrict__ probs) {
+  if (E <= 64) topk_impl<1>(lg, E, k, renorm, lane, sel_e, sel_g, probs);
+  else if (E <= 128) topk_impl<2>(lg, E, k, renorm, lane, sel_e, sel_g, probs);
+  else topk_impl<16>(lg, E, k, renorm, lane, sel_e, sel_g, probs);
 }
 
 __global__ __launch_bounds__(64) void k_topk(LayerDims L, const float* __restrict__ logits, int32_t* __restrict__ idx,
@@ -341,48 +468,35 @@ __global__ __launch_bounds__(64) void k_topk(LayerDims L, const float* __restric
 // ---------------------------------------------------------------------------------------------
 template <int BITS, bool SWIGLU>
 __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int d, int f, int group, int row_begin,
-                                             int row_end, float* __restrict__ h_out, const uint32_t* XP,
+                                             int row_end, uint16_t* __restrict__ h_out, const uint32_t* XP,
                                              const float* XK) {
+  constexpr int NM = SWIGLU ? 2 : 1;
   const int C = d / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
   const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-  const int p = lane % P, rsub = lane / P;
-  constexpr int NM = SWIGLU ? 2 : 1;
   const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock / NM);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* q_in = uniform_ptr(ex.q_in);
   const uint16_t* s_in = uniform_ptr(ex.s_in);
   const uint8_t* q_gate = SWIGLU ? uniform_ptr(ex.q_gate) : nullptr;
   const uint16_t* s_gate = SWIGLU ? uniform_ptr(ex.s_gate) : nullptr;
+  auto epi = [&](int row, const float (&r)[NM]) {
+    float v;
+    if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
+    else v = fmaxf(r[0], 0.f);
+    h_out[row] = (uint16_t)f32_to_f16_bits(v);
+  };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
-    const int task_rows = RW * NRM;
-    for (int r0 = row_begin + wave * task_rows; r0 < row_end; r0 += nwaves * task_rows) {
-      float tot[NRM * NM];
-      if constexpr (SWIGLU) {
-        const uint8_t* const qq[2] = {q_in, q_gate};
-        const uint16_t* const ss[2] = {s_in, s_gate};
-        gemv_task<BITS, NRM, 2, TWO>(qq, ss, d, group, P, p, r0 + rsub, RW, f, XP, XK, tot);
-      } else {
-        const uint8_t* const qq[1] = {q_in};
-        const uint16_t* const ss[1] = {s_in};
-        gemv_task<BITS, NRM, 1, TWO>(qq, ss, d, group, P, p, r0 + rsub, RW, f, XP, XK, tot);
-      }
-      fold_rows<NRM, NM>(tot, P, lane);
-      if (p < NRM) {
-        const int row = r0 + p * RW + rsub;
-        if (row < row_end) {
-          float v;
-          if constexpr (SWIGLU) {
-            const float a = tot[0];
-            v = a / (1.0f + __expf(-a)) * tot[NRM];
-          } else {
-            v = fmaxf(tot[0], 0.f);
-          }
-          h_out[row] = v;
-        }
-      }
+    if constexpr (SWIGLU) {
+      const uint8_t* const qq[2] = {q_in, q_gate};
+      const uint16_t* const ss[2] = {s_in, s_gate};
+      gemv_stream<BITS, NRM, 2, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi);
+    } else {
+      const uint8_t* const qq[1] = {q_in};
+      const uint16_t* const ss[1] = {s_in};
+      gemv_stream<BITS, NRM, 1, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi);
     }
   };
   using T_ = std::true_type;
@@ -401,28 +515,32 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int d
 }
 
 // Phase 1 for one token: (optionally) top-k from the router logits, then for each chosen expert
-// h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]) for the rows r this workgroup owns.
-__global__ __launch_bounds__(768) void k_ffn_in(LayerDims L, const DevExpert* __restrict__ table,
-                                                 const float* __restrict__ logits, int32_t* __restrict__ idx_out,
-                                                 float* __restrict__ gate_out, int32_t fixed_expert,
-                                                 const void* __restrict__ x, float* __restrict__ h,
-                                                 int32_t rows_per_wg) {
+// h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]) for the rows r this workgroup owns; h is kept as
+// binary16 (it is the activation vector of phase 2).
+__global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* __restrict__ table,
+                                                const float* __restrict__ logits, int32_t* __restrict__ idx_out,
+                                                float* __restrict__ gate_out, int32_t fixed_expert,
+                                                const void* __restrict__ x, uint16_t* __restrict__ h,
+                                                int32_t rows_per_wg) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
   const int d = L.d_model, f = L.d_ff;
   const int token = blockIdx.y;
-  uint32_t* XP = smem;                    // d/2 words
-  float* XK = (float*)(smem + d / 2);     // at most d/16 words
+  uint32_t* XP = smem;                          // d/2 words
+  float* XK = (float*)(smem + d / 2);           // d/16 words
+  uint16_t* RAW = (uint16_t*)(XK + d / 16);     // d halfs
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
+  const size_t xbytes = L.x_bf16 ? 2 : 4;
+  copy_x_to_lds((const char*)x + (size_t)token * d * xbytes, L.x_bf16 ? X_BF16 : X_F32, d, threadIdx.x, blockDim.x, RAW);
   if (fixed_expert < 0) {
     if (threadIdx.x < 64) topk_from_logits(logits + (size_t)token * L.n_experts, L.n_experts, k, L.renorm,
                                            threadIdx.x, sel_e, sel_g, nullptr);
-    __syncthreads();
-    if (blockIdx.x == 0 && threadIdx.x < k) {
-      idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
-      gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
-    }
+  }
+  __syncthreads();
+  if (fixed_expert < 0 && blockIdx.x == 0 && threadIdx.x < k) {
+    idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
+    gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
   }
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(f, row_begin + rows_per_wg);
@@ -432,7 +550,7 @@ __global__ __launch_bounds__(768) void k_ffn_in(LayerDims L, const DevExpert* __
     const int slot = fixed_expert >= 0 ? token : token * k + j;
     const int e = fixed_expert >= 0 ? fixed_expert : sel_e[j];
     const DevExpert ex = table[e];
-    float* h_out = h + (size_t)slot * f;
+    uint16_t* h_out = h + (size_t)slot * f;
     // Opaque copy of the thread index: keeps the per-variant lane arithmetic inside this iteration
     // instead of being hoisted (and spilled) ahead of the loop for every bitwidth at once.
     int tid = threadIdx.x;
@@ -441,13 +559,8 @@ __global__ __launch_bounds__(768) void k_ffn_in(LayerDims L, const DevExpert* __
       constexpr int BITS = decltype(bits_tag)::value;
       if (staged_bits != BITS) {   // the activation layout depends on the bitwidth only
         if (staged_bits != 0) __syncthreads();
-        if (L.x_bf16) {
-          const uint16_t* xr = (const uint16_t*)x + (size_t)token * d;
-          stage_x<BITS>([&](int i) { return bf16_bits_to_f32(xr[i]); }, d, L.group, XP, XK);
-        } else {
-          const float* xr = (const float*)x + (size_t)token * d;
-          stage_x<BITS>([&](int i) { return xr[i]; }, d, L.group, XP, XK);
-        }
+        permute_x<BITS>(RAW, d, L.group, tid, blockDim.x, XP, XK);
+        __syncthreads();
         staged_bits = BITS;
       }
       if (sw) ffn_in_tasks<BITS, true>(ex, tid, d, f, L.group, row_begin, row_end, h_out, XP, XK);
@@ -469,24 +582,15 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
   const int C = f / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
   const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-  const int p = lane % P, rsub = lane / P;
   const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* const qq[1] = {uniform_ptr(ex.q_out)};
   const uint16_t* const ss[1] = {uniform_ptr(ex.s_out)};
+  auto epi = [&](int row, const float (&r)[1]) { ybuf[row - row_begin] = fmaf(g, r[0], ybuf[row - row_begin]); };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
-    const int task_rows = RW * NRM;
-    for (int r0 = row_begin + wave * task_rows; r0 < row_end; r0 += nwaves * task_rows) {
-      float tot[NRM];
-      gemv_task<BITS, NRM, 1, TWO>(qq, ss, f, group, P, p, r0 + rsub, RW, d, XP, XK, tot);
-      fold_rows<NRM, 1>(tot, P, lane);
-      if (p < NRM) {
-        const int row = r0 + p * RW + rsub;
-        if (row < row_end) ybuf[row - row_begin] = fmaf(g, tot[0], ybuf[row - row_begin]);
-      }
-    }
+    gemv_stream<BITS, NRM, 1, TWO>(qq, ss, f, group, d, row_begin, row_end, lane, wave, nwaves, XP, XK, epi);
   };
   using T_ = std::true_type;
   using F_ = std::false_type;
@@ -505,17 +609,18 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
 
 // Phase 2 + combine for one token: y[t][r] (+)= sum_j gate_j * W_out_j[r] . h[slot_j], summed in top-k
 // order in LDS for the rows this workgroup owns, each output written once.
-__global__ __launch_bounds__(768) void k_ffn_out(LayerDims L, const DevExpert* __restrict__ table,
-                                                  const int32_t* __restrict__ idx, const float* __restrict__ gate,
-                                                  int32_t fixed_expert, int32_t accumulate,
-                                                  const float* __restrict__ h, float* __restrict__ y,
-                                                  int32_t rows_per_wg) {
+__global__ __launch_bounds__(1024) void k_ffn_out(LayerDims L, const DevExpert* __restrict__ table,
+                                                 const int32_t* __restrict__ idx, const float* __restrict__ gate,
+                                                 int32_t fixed_expert, int32_t accumulate,
+                                                 const uint16_t* __restrict__ h, float* __restrict__ y,
+                                                 int32_t rows_per_wg) {
   extern __shared__ uint32_t smem[];
   const int d = L.d_model, f = L.d_ff;
   const int token = blockIdx.y;
-  uint32_t* XP = smem;                      // f/2 words
-  float* XK = (float*)(smem + f / 2);       // at most f/16 words
-  float* ybuf = XK + f / 16;                // rows_per_wg words
+  uint32_t* XP = smem;                          // f/2 words
+  float* XK = (float*)(smem + f / 2);           // f/16 words
+  uint16_t* RAW = (uint16_t*)(XK + f / 16);     // f halfs
+  float* ybuf = (float*)(RAW + f);              // rows_per_wg words
   float* y_out = y + (size_t)token * d;
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(d, row_begin + rows_per_wg);
@@ -526,13 +631,15 @@ __global__ __launch_bounds__(768) void k_ffn_out(LayerDims L, const DevExpert* _
     const int e = fixed_expert >= 0 ? fixed_expert : idx[slot];
     const float g = gate ? gate[slot] : 1.0f;
     const DevExpert ex = table[e];
-    const float* hr = h + (size_t)slot * f;
     int tid = threadIdx.x;       // opaque copy, see k_ffn_in
     asm volatile("" : "+v"(tid));
-    if (j > 0) __syncthreads();  // everyone is done with the previous choice's activations and sums
+    if (j > 0) __syncthreads();  // everyone is done with the previous choice's activations
+    copy_x_to_lds(h + (size_t)slot * f, X_F16, f, tid, blockDim.x, RAW);
+    __syncthreads();
     auto run = [&](auto bits_tag) {
       constexpr int BITS = decltype(bits_tag)::value;
-      stage_x<BITS>([&](int i) { return hr[i]; }, f, L.group, XP, XK);
+      permute_x<BITS>(RAW, f, L.group, tid, blockDim.x, XP, XK);
+      __syncthreads();
       ffn_out_tasks<BITS>(ex, tid, d, f, L.group, g, row_begin, row_end, ybuf, XP, XK);
     };
     switch (ex.bits) {
@@ -559,16 +666,16 @@ int num_cus() {
 }
 
 inline size_t lds_bytes(int cols) {
-  // activation pairs (2 bytes per weight position) + offset terms (at most one per 16 weights)
-  return (size_t)cols * 2 + (size_t)(cols / 16) * 4;
+  // pair registers (2 bytes per position) + offset terms (one per 16 positions) + linear binary16 copy
+  return (size_t)cols * 2 + (size_t)(cols / 16) * 4 + (size_t)cols * 2;
 }
 
-// Rows per workgroup and wavefronts per workgroup for a GEMV over `rows` output rows whose packed row
-// has at least `min_chunks` 16-byte chunks. About one workgroup per compute unit when there is enough
-// work; row ranges are multiples of 64 rows/P so that tasks never straddle workgroups.
+// Rows per workgroup and wavefronts per workgroup for a GEMV over `rows` output rows. About one
+// workgroup per compute unit when there is enough work; row ranges are multiples of the rows a
+// wavefront covers per step at the widest bitwidth (64/min_P) so that tasks never straddle workgroups.
 struct Split { int rows_per_wg, gx, threads; };
 Split plan_rows(int rows, int min_P, int T, int nrm_max) {
-  const int RWmax = 64 / min_P;                       // rows a wavefront covers per step, worst bitwidth
+  const int RWmax = 64 / min_P;
   const int cus = num_cus();
   int target = cus / (T < 1 ? 1 : (T > cus ? cus : T));  // workgroups per token
   if (target < 1) target = 1;
@@ -578,10 +685,10 @@ Split plan_rows(int rows, int min_P, int T, int nrm_max) {
   Split s;
   s.rows_per_wg = rpw;
   s.gx = (rows + rpw - 1) / rpw;
-  // wavefronts per workgroup: the count in [4, 12] that leaves the fewest idle task slots, more on ties
+  // wavefronts per workgroup: the count in [4, 16] that leaves the fewest idle task slots, more on ties
   int best_w = 4;
   double best_eff = -1.0;
-  for (int w = 12; w >= 4; --w) {
+  for (int w = 16; w >= 4; --w) {
     const int nrm = pick_nrm(rpw, RWmax, w, min_P, nrm_max);
     const int tasks = (rpw + RWmax * nrm - 1) / (RWmax * nrm);
     const int rounds = (tasks + w - 1) / w;
@@ -611,7 +718,8 @@ hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32
 }
 
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits, int32_t* idx_out,
-                         float* gate_out, int32_t fixed_expert, const void* x, int32_t T, float* h, hipStream_t st) {
+                         float* gate_out, int32_t fixed_expert, const void* x, int32_t T, uint16_t* h,
+                         hipStream_t st) {
   const Split sp = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), T, L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
   const size_t lds = lds_bytes(L.d_model);
   static size_t lds_set = 0;
@@ -626,7 +734,7 @@ hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float
 }
 
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx, const float* gate,
-                          int32_t fixed_expert, int32_t accumulate, const float* h, int32_t T, float* y,
+                          int32_t fixed_expert, int32_t accumulate, const uint16_t* h, int32_t T, float* y,
                           hipStream_t st) {
   const Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), T, kBlock);
   const size_t lds = lds_bytes(L.d_ff) + (size_t)sp.rows_per_wg * sizeof(float);
