@@ -20,7 +20,8 @@
  *     between the router and the expert kernels.
  *   - Every entry point validates its arguments before the first HIP call and reports
  *     problems as a status code; nothing throws, nothing aborts.
- *   - Calls that share a workspace must be ordered on one stream (or otherwise serialised).
+ *   - Calls that share a workspace, and all compute calls on one layer handle, must be ordered on
+ *     one stream (or otherwise serialised).
  *
  * Packed weight format (the boundary format; "canonical")
  *   A matrix W[rows][cols] (row = output channel, cols = input dimension) at b bits with group
@@ -93,6 +94,13 @@ size_t moe_layer_table_bytes(int32_t n_experts);
 moeq_status moe_layer_create(const moeq_layer_desc *desc, void *table_dev, size_t table_bytes,
                              moeq_layer **out);
 void moe_layer_destroy(moeq_layer *layer);
+
+/* Synchronous check of the layer's device-side state, for use when no call on the layer is in
+ * flight. The one-launch decode path coordinates its workgroups through a few words behind the
+ * expert table; they are zero between calls. *error_out = 1 if they are not (a bounded wait inside a
+ * kernel gave up, e.g. because calls on this layer overlapped): the outputs of the calls since the
+ * last check are then invalid, and the words are cleared so that the layer can be used again. */
+moeq_status moe_layer_health(const moeq_layer *layer, int32_t *error_out);
 
 /* Workspace bytes needed by any compute call on `layer` with up to max_tokens tokens. */
 size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);

@@ -61,6 +61,8 @@ def lib():
     L.moe_layer_create.argtypes = [C.POINTER(moeq_layer_desc), vp, sz, C.POINTER(vp)]
     L.moe_layer_destroy.restype = None
     L.moe_layer_destroy.argtypes = [vp]
+    L.moe_layer_health.restype = C.c_int
+    L.moe_layer_health.argtypes = [vp, C.POINTER(C.c_int32)]
     L.moe_workspace_bytes.restype = sz
     L.moe_workspace_bytes.argtypes = [vp, i32]
     L.moe_router_topk.restype = C.c_int
@@ -80,7 +82,7 @@ def lib():
 
 
 EXPORTS = ["moe_status_str", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
-           "moe_layer_destroy", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
+           "moe_layer_destroy", "moe_layer_health", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
            "moe_layer_forward", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize"]
 
 
@@ -189,6 +191,12 @@ class Layer:
     @property
     def handle(self):
         return self._h
+
+    def health(self):
+        """0 if the layer's device-side barrier words are clean, 1 if a call on it went wrong (then cleared)."""
+        out = C.c_int32(0)
+        _check(lib().moe_layer_health(self._h, C.byref(out)), "moe_layer_health")
+        return int(out.value)
 
     def workspace_bytes(self, max_tokens):
         return int(lib().moe_workspace_bytes(self._h, max_tokens))

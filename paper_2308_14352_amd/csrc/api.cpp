@@ -14,6 +14,7 @@ struct moeq_layer {
   const float* router_w;
   const float* router_bias;
   const DevExpert* table;          // device
+  uint32_t* barrier;               // device: barrier words of the one-launch path, behind the table
   std::vector<int32_t> bits;       // host copy of the bitwidth table
 };
 
@@ -30,7 +31,7 @@ inline bool group_ok(int32_t g, int32_t bits) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {
-  size_t idx_off, gate_off, logits_off, h_off, total;
+  size_t idx_off, gate_off, logits_off, part_off, h_off, total;
 };
 
 WsLayout ws_layout(const LayerDims& L, int64_t T) {
@@ -39,7 +40,9 @@ WsLayout ws_layout(const LayerDims& L, int64_t T) {
   w.idx_off = 0;
   w.gate_off = align_up(slots * sizeof(int32_t), 256);
   w.logits_off = w.gate_off + align_up(slots * sizeof(float), 256);
-  w.h_off = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
+  w.part_off = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
+  const size_t part_tokens = (size_t)(T < kFusedMaxTokens ? T : kFusedMaxTokens);
+  w.h_off = w.part_off + align_up(part_tokens * kFusedMaxSlices * (size_t)L.n_experts * sizeof(float), 256);
   w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
   return w;
 }
@@ -62,7 +65,7 @@ const char* moe_status_str(moeq_status st) {
 }
 
 size_t moe_layer_table_bytes(int32_t n_experts) {
-  return n_experts > 0 ? (size_t)n_experts * sizeof(DevExpert) : 0;
+  return n_experts > 0 ? (size_t)n_experts * sizeof(DevExpert) + kBarrierBytes : 0;
 }
 
 size_t moe_packed_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group, size_t* scale_bytes_opt) {
@@ -84,7 +87,8 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   if (d % g || f % g) return MOEQ_EINVAL;
   if (((uintptr_t)table_dev & 15u) || table_bytes < moe_layer_table_bytes(E)) return MOEQ_EINVAL;
   if (k > 8 || E > 1024 || d > 32768 || f > 32768 || d % 8 || f % 8) return MOEQ_EUNSUPPORTED;
-  std::vector<DevExpert> tab((size_t)E);
+  std::vector<DevExpert> tab((size_t)E + kBarrierBytes / sizeof(DevExpert));  // trailing zeros: barrier words
+  std::memset(tab.data(), 0, tab.size() * sizeof(DevExpert));
   std::vector<int32_t> bits((size_t)E);
   for (int32_t e = 0; e < E; ++e) {
     const moeq_expert& x = desc->experts[e];
@@ -110,6 +114,7 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   L->router_w = desc->router_w;
   L->router_bias = desc->router_bias;
   L->table = (const DevExpert*)table_dev;
+  L->barrier = (uint32_t*)((char*)table_dev + (size_t)E * sizeof(DevExpert));
   L->bits = std::move(bits);
   if (hipMemcpy(table_dev, tab.data(), tab.size() * sizeof(DevExpert), hipMemcpyHostToDevice) != hipSuccess) {
     delete L;
@@ -120,6 +125,17 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
 }
 
 void moe_layer_destroy(moeq_layer* layer) { delete layer; }
+
+moeq_status moe_layer_health(const moeq_layer* layer, int32_t* error_out) {
+  if (!layer || !error_out) return MOEQ_EINVAL;
+  uint32_t words[kBarrierBytes / 4];
+  if (hipMemcpy(words, layer->barrier, kBarrierBytes, hipMemcpyDeviceToHost) != hipSuccess) return MOEQ_EDEVICE;
+  int32_t bad = 0;
+  for (size_t i = 0; i < kBarrierBytes / 4; ++i) bad |= (words[i] != 0u);
+  *error_out = bad;
+  if (bad && hipMemset(layer->barrier, 0, kBarrierBytes) != hipSuccess) return MOEQ_EDEVICE;
+  return MOEQ_OK;
+}
 
 size_t moe_workspace_bytes(const moeq_layer* layer, int32_t max_tokens) {
   if (!layer || max_tokens <= 0) return 0;
@@ -177,6 +193,16 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   hipStream_t st = (hipStream_t)stream;
   float* logits = (float*)((char*)ws + w.logits_off);
+  // Experimental: the whole layer of a few tokens in one launch with grid barriers. Measured slower than
+  // the three-kernel path on MI355X (a barrier across the 8 XCDs costs more than a kernel boundary), so it
+  // only runs when MOEQ_ONE_LAUNCH=1 is set in the environment.
+  static const bool one_launch = [] { const char* v = std::getenv("MOEQ_ONE_LAUNCH"); return v && v[0] == '1'; }();
+  if (one_launch) {
+    const hipError_t fused = launch_layer_decode(L, layer->table, layer->router_w, layer->router_bias, x, n_tokens, y,
+                                                 idx, gate, (float*)((char*)ws + w.part_off), h, layer->barrier, st);
+    if (fused == hipSuccess) return MOEQ_OK;
+    if (fused != hipErrorNotSupported) return MOEQ_EDEVICE;
+  }
   if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
   if (launch_ffn_in(L, layer->table, logits, idx, gate, -1, x, n_tokens, h, st) != hipSuccess) return MOEQ_EDEVICE;

@@ -467,13 +467,14 @@ __global__ __launch_bounds__(64) void k_topk(LayerDims L, const float* __restric
 
 // ---------------------------------------------------------------------------------------------
 template <int BITS, bool SWIGLU>
-__device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int d, int f, int group, int row_begin,
-                                             int row_end, uint16_t* __restrict__ h_out, const uint32_t* XP,
-                                             const float* XK) {
+__device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
+                                             int row_begin, int row_end, uint16_t* __restrict__ h_out,
+                                             const uint32_t* XP, const float* XK) {
   constexpr int NM = SWIGLU ? 2 : 1;
   const int C = d / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
-  const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int lane = tid & 63, wave = tid >> 6;
+  if (wave >= nwaves) return;
   const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock / NM);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* q_in = uniform_ptr(ex.q_in);
@@ -514,79 +515,110 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int d
   else run(std::integral_constant<int, 1>{}, F_{});
 }
 
-// Phase 1 for one token: (optionally) top-k from the router logits, then for each chosen expert
-// h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]) for the rows r this workgroup owns; h is kept as
-// binary16 (it is the activation vector of phase 2).
+// Phase 1 of one token for the rows [row_begin, row_end) of d_ff: for each chosen expert
+// h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]); h is kept as binary16 (it is the activation vector
+// of phase 2). The activations are already in RAW (LDS, linear binary16). The k experts are handled in
+// passes of `spp`: the activation layouts a pass needs (one per distinct bitwidth) are staged
+// together, then every wavefront streams its tasks of all the pass's experts without a barrier.
+// Called by every thread of the workgroup; the first barrier inside also orders RAW and sel_e.
+__device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert* __restrict__ table, const int* sel_e,
+                                            int fixed_expert, int token, uint16_t* __restrict__ h, int row_begin,
+                                            int row_end, int spp, const uint16_t* RAW, uint32_t* LAY, int nwaves) {
+  const int d = L.d_model, f = L.d_ff;
+  const int lay_words = d / 2 + d / 16;         // one layout: d/2 pair words + d/16 offset terms
+  const int k = fixed_expert >= 0 ? 1 : L.top_k;
+  const bool sw = L.act == MOEQ_ACT_SWIGLU;
+  for (int j0 = 0; j0 < k; j0 += spp) {
+    const int j1 = min(k, j0 + spp);
+    __syncthreads();  // RAW / routing are complete; every wavefront is done with the previous pass's layouts
+    // stage one layout per distinct bitwidth of this pass; layout index = first slot of the pass with it
+    for (int j = j0; j < j1; ++j) {
+      const int bits = table[fixed_expert >= 0 ? fixed_expert : sel_e[j]].bits;
+      bool first = true;
+      for (int i = j0; i < j; ++i) first = first && (table[sel_e[i]].bits != bits);
+      if (!first) continue;
+      uint32_t* XP = LAY + (j - j0) * lay_words;
+      float* XK = (float*)(XP + d / 2);
+      int tid = threadIdx.x;
+      asm volatile("" : "+v"(tid));
+      if (bits == 2) permute_x<2>(RAW, d, L.group, tid, blockDim.x, XP, XK);
+      else if (bits == 4) permute_x<4>(RAW, d, L.group, tid, blockDim.x, XP, XK);
+      else permute_x<8>(RAW, d, L.group, tid, blockDim.x, XP, XK);
+    }
+    __syncthreads();
+    for (int j = j0; j < j1; ++j) {
+      const int slot = fixed_expert >= 0 ? token : token * k + j;
+      const int e = fixed_expert >= 0 ? fixed_expert : sel_e[j];
+      const DevExpert ex = table[e];
+      int li = j;
+      for (int i = j - 1; i >= j0; --i)
+        if (table[sel_e[i]].bits == ex.bits) li = i;
+      const uint32_t* XP = LAY + (li - j0) * lay_words;
+      const float* XK = (const float*)(XP + d / 2);
+      uint16_t* h_out = h + (size_t)slot * f;
+      // Opaque copy of the thread index: keeps the per-variant lane arithmetic inside this iteration
+      // instead of being hoisted (and spilled) ahead of the loop for every bitwidth at once.
+      int tid = threadIdx.x;
+      asm volatile("" : "+v"(tid));
+      auto run = [&](auto bits_tag) {
+        constexpr int BITS = decltype(bits_tag)::value;
+        if (sw) ffn_in_tasks<BITS, true>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, XP, XK);
+        else ffn_in_tasks<BITS, false>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, XP, XK);
+      };
+      switch (ex.bits) {
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        default: run(std::integral_constant<int, 8>{}); break;
+      }
+    }
+  }
+}
+
+// Stand-alone phase 1: (optionally) top-k from the router logits, then phase1_body.
 __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* __restrict__ table,
-                                                const float* __restrict__ logits, int32_t* __restrict__ idx_out,
-                                                float* __restrict__ gate_out, int32_t fixed_expert,
-                                                const void* __restrict__ x, uint16_t* __restrict__ h,
-                                                int32_t rows_per_wg) {
+                                                 const float* __restrict__ logits, int32_t* __restrict__ idx_out,
+                                                 float* __restrict__ gate_out, int32_t fixed_expert,
+                                                 const void* __restrict__ x, uint16_t* __restrict__ h,
+                                                 int32_t rows_per_wg, int32_t slots_per_pass) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
   const int d = L.d_model, f = L.d_ff;
   const int token = blockIdx.y;
-  uint32_t* XP = smem;                          // d/2 words
-  float* XK = (float*)(smem + d / 2);           // d/16 words
-  uint16_t* RAW = (uint16_t*)(XK + d / 16);     // d halfs
+  uint16_t* RAW = (uint16_t*)smem;              // d halfs, then the layouts
+  uint32_t* LAY = smem + d / 2;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
   const size_t xbytes = L.x_bf16 ? 2 : 4;
   copy_x_to_lds((const char*)x + (size_t)token * d * xbytes, L.x_bf16 ? X_BF16 : X_F32, d, threadIdx.x, blockDim.x, RAW);
   if (fixed_expert < 0) {
     if (threadIdx.x < 64) topk_from_logits(logits + (size_t)token * L.n_experts, L.n_experts, k, L.renorm,
                                            threadIdx.x, sel_e, sel_g, nullptr);
-  }
-  __syncthreads();
-  if (fixed_expert < 0 && blockIdx.x == 0 && threadIdx.x < k) {
-    idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
-    gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x < k) {
+      idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
+      gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
+    }
   }
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(f, row_begin + rows_per_wg);
-  const bool sw = L.act == MOEQ_ACT_SWIGLU;
-  int staged_bits = 0;
-  for (int j = 0; j < k; ++j) {
-    const int slot = fixed_expert >= 0 ? token : token * k + j;
-    const int e = fixed_expert >= 0 ? fixed_expert : sel_e[j];
-    const DevExpert ex = table[e];
-    uint16_t* h_out = h + (size_t)slot * f;
-    // Opaque copy of the thread index: keeps the per-variant lane arithmetic inside this iteration
-    // instead of being hoisted (and spilled) ahead of the loop for every bitwidth at once.
-    int tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
-    auto run = [&](auto bits_tag) {
-      constexpr int BITS = decltype(bits_tag)::value;
-      if (staged_bits != BITS) {   // the activation layout depends on the bitwidth only
-        if (staged_bits != 0) __syncthreads();
-        permute_x<BITS>(RAW, d, L.group, tid, blockDim.x, XP, XK);
-        __syncthreads();
-        staged_bits = BITS;
-      }
-      if (sw) ffn_in_tasks<BITS, true>(ex, tid, d, f, L.group, row_begin, row_end, h_out, XP, XK);
-      else ffn_in_tasks<BITS, false>(ex, tid, d, f, L.group, row_begin, row_end, h_out, XP, XK);
-    };
-    switch (ex.bits) {
-      case 2: run(std::integral_constant<int, 2>{}); break;
-      case 4: run(std::integral_constant<int, 4>{}); break;
-      default: run(std::integral_constant<int, 8>{}); break;
-    }
-  }
+  phase1_body(L, table, sel_e, fixed_expert, token, h, row_begin, row_end, slots_per_pass, RAW, LAY,
+              (int)(blockDim.x >> 6));
 }
 
 // ---------------------------------------------------------------------------------------------
 template <int BITS>
-__device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int d, int f, int group, float g,
-                                              int row_begin, int row_end, float* ybuf, const uint32_t* XP,
+__device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
+                                              float g, int row_begin, int row_end, float* ybuf, const uint32_t* XP,
                                               const float* XK) {
   const int C = f / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
-  const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int lane = tid & 63, wave = tid >> 6;
+  if (wave >= nwaves) return;
   const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* const qq[1] = {uniform_ptr(ex.q_out)};
   const uint16_t* const ss[1] = {uniform_ptr(ex.s_out)};
-  auto epi = [&](int row, const float (&r)[1]) { ybuf[row - row_begin] = fmaf(g, r[0], ybuf[row - row_begin]); };
+  auto epi = [&](int row, const float (&r)[1]) { ybuf[row - row_begin] = g * r[0]; };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
@@ -607,50 +639,209 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
   else run(std::integral_constant<int, 1>{}, F_{});
 }
 
-// Phase 2 + combine for one token: y[t][r] (+)= sum_j gate_j * W_out_j[r] . h[slot_j], summed in top-k
-// order in LDS for the rows this workgroup owns, each output written once.
-__global__ __launch_bounds__(1024) void k_ffn_out(LayerDims L, const DevExpert* __restrict__ table,
-                                                 const int32_t* __restrict__ idx, const float* __restrict__ gate,
-                                                 int32_t fixed_expert, int32_t accumulate,
-                                                 const uint16_t* __restrict__ h, float* __restrict__ y,
-                                                 int32_t rows_per_wg) {
-  extern __shared__ uint32_t smem[];
+// Phase 2 + combine of one token for the rows [row_begin, row_end) of d_model:
+// y[t][r] (+)= sum_j gate_j * W_out_j[r] . h[slot_j]. Experts are handled in passes of `spp`: their
+// activation vectors are staged together, every wavefront streams its tasks of all of them without a
+// barrier, each expert's contribution lands in its own LDS row buffer, and the buffers are summed in
+// top-k order at the end: ordered, no atomics, every output written once.
+// idx_tok / gate_tok: this token's k choices (LDS or global); gate_tok may be null (= 1).
+__device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert* __restrict__ table, const int* idx_tok,
+                                            const float* gate_tok, int fixed_expert, int accumulate, int token,
+                                            const uint16_t* __restrict__ h, float* __restrict__ y_out, int row_begin,
+                                            int row_end, int rows_per_wg, int spp, uint32_t* smem, int nwaves) {
   const int d = L.d_model, f = L.d_ff;
-  const int token = blockIdx.y;
-  uint32_t* XP = smem;                          // f/2 words
-  float* XK = (float*)(smem + f / 2);           // f/16 words
-  uint16_t* RAW = (uint16_t*)(XK + f / 16);     // f halfs
-  float* ybuf = (float*)(RAW + f);              // rows_per_wg words
-  float* y_out = y + (size_t)token * d;
-  const int row_begin = blockIdx.x * rows_per_wg;
-  const int row_end = min(d, row_begin + rows_per_wg);
-  for (int i = threadIdx.x; i < rows_per_wg; i += blockDim.x) ybuf[i] = 0.f;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
-  for (int j = 0; j < k; ++j) {
-    const int slot = fixed_expert >= 0 ? token : token * k + j;
-    const int e = fixed_expert >= 0 ? fixed_expert : idx[slot];
-    const float g = gate ? gate[slot] : 1.0f;
-    const DevExpert ex = table[e];
-    int tid = threadIdx.x;       // opaque copy, see k_ffn_in
-    asm volatile("" : "+v"(tid));
-    if (j > 0) __syncthreads();  // everyone is done with the previous choice's activations
-    copy_x_to_lds(h + (size_t)slot * f, X_F16, f, tid, blockDim.x, RAW);
+  const int lay_words = f / 2 + f / 16;          // pair words + offset terms of one activation vector
+  float* ybuf = (float*)smem;                    // [k][rows_per_wg]
+  uint32_t* LAY = smem + k * rows_per_wg;        // [spp][lay_words]
+  uint16_t* RAWS = (uint16_t*)(LAY + spp * lay_words);  // [spp][f]
+  for (int j0 = 0; j0 < k; j0 += spp) {
+    const int j1 = min(k, j0 + spp);
+    if (j0 > 0) __syncthreads();  // every wavefront is done with the previous pass's activations
+    for (int j = j0; j < j1; ++j) {
+      const int slot = fixed_expert >= 0 ? token : token * k + j;
+      copy_x_to_lds(h + (size_t)slot * f, X_F16, f, threadIdx.x, blockDim.x, RAWS + (size_t)(j - j0) * f);
+    }
     __syncthreads();
-    auto run = [&](auto bits_tag) {
-      constexpr int BITS = decltype(bits_tag)::value;
-      permute_x<BITS>(RAW, f, L.group, tid, blockDim.x, XP, XK);
-      __syncthreads();
-      ffn_out_tasks<BITS>(ex, tid, d, f, L.group, g, row_begin, row_end, ybuf, XP, XK);
-    };
-    switch (ex.bits) {
-      case 2: run(std::integral_constant<int, 2>{}); break;
-      case 4: run(std::integral_constant<int, 4>{}); break;
-      default: run(std::integral_constant<int, 8>{}); break;
+    for (int j = j0; j < j1; ++j) {
+      const int bits = table[fixed_expert >= 0 ? fixed_expert : idx_tok[j]].bits;
+      uint32_t* XP = LAY + (j - j0) * lay_words;
+      float* XK = (float*)(XP + f / 2);
+      const uint16_t* RAW = RAWS + (size_t)(j - j0) * f;
+      int tid = threadIdx.x;       // opaque copy: keeps per-variant lane arithmetic out of the prologue
+      asm volatile("" : "+v"(tid));
+      if (bits == 2) permute_x<2>(RAW, f, L.group, tid, blockDim.x, XP, XK);
+      else if (bits == 4) permute_x<4>(RAW, f, L.group, tid, blockDim.x, XP, XK);
+      else permute_x<8>(RAW, f, L.group, tid, blockDim.x, XP, XK);
+    }
+    __syncthreads();
+    for (int j = j0; j < j1; ++j) {
+      const int e = fixed_expert >= 0 ? fixed_expert : idx_tok[j];
+      const float g = gate_tok ? gate_tok[fixed_expert >= 0 ? 0 : j] : 1.0f;
+      const DevExpert ex = table[e];
+      const uint32_t* XP = LAY + (j - j0) * lay_words;
+      const float* XK = (const float*)(XP + f / 2);
+      int tid = threadIdx.x;
+      asm volatile("" : "+v"(tid));
+      auto run = [&](auto bits_tag) {
+        constexpr int BITS = decltype(bits_tag)::value;
+        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, row_begin, row_end, ybuf + j * rows_per_wg, XP, XK);
+      };
+      switch (ex.bits) {
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        default: run(std::integral_constant<int, 8>{}); break;
+      }
     }
   }
   __syncthreads();
-  for (int i = row_begin + (int)threadIdx.x; i < row_end; i += blockDim.x)
-    y_out[i] = accumulate ? y_out[i] + ybuf[i - row_begin] : ybuf[i - row_begin];
+  for (int i = row_begin + (int)threadIdx.x; i < row_end; i += blockDim.x) {
+    float acc = accumulate ? y_out[i] : 0.f;
+    for (int j = 0; j < k; ++j) acc += ybuf[j * rows_per_wg + (i - row_begin)];
+    y_out[i] = acc;
+  }
+}
+
+__global__ __launch_bounds__(1024) void k_ffn_out(LayerDims L, const DevExpert* __restrict__ table,
+                                                  const int32_t* __restrict__ idx, const float* __restrict__ gate,
+                                                  int32_t fixed_expert, int32_t accumulate,
+                                                  const uint16_t* __restrict__ h, float* __restrict__ y,
+                                                  int32_t rows_per_wg, int32_t slots_per_pass) {
+  extern __shared__ uint32_t smem[];
+  const int d = L.d_model;
+  const int token = blockIdx.y;
+  const int k = fixed_expert >= 0 ? 1 : L.top_k;
+  const int row_begin = blockIdx.x * rows_per_wg;
+  const int row_end = min(d, row_begin + rows_per_wg);
+  phase2_body(L, table, idx ? idx + (size_t)token * k : nullptr, gate ? gate + (size_t)token * k : nullptr,
+              fixed_expert, accumulate, token, h, y + (size_t)token * d, row_begin, row_end, rows_per_wg,
+              slots_per_pass, smem, (int)(blockDim.x >> 6));
+}
+
+// ---------------------------------------------------------------------------------------------
+// The whole layer of a few tokens in ONE launch: router partial sums -> grid barrier -> top-k ->
+// phase 1 -> grid barrier -> phase 2 + combine. gridDim.x workgroups per token, all resident at once
+// (the host checks the occupancy), so a counter in device memory can act as a barrier between them.
+//
+// Barrier words (per token: arrive_a, arrive_b, done, unused) live in the layer's device table, are
+// zero between calls, and are reset by the last workgroup to finish. A wait is bounded: a workgroup
+// that does not see its peers in kSpinLimit polls raises the sticky error word and stops waiting, and
+// every later wait returns at once, so the kernel always terminates (with invalid output and the
+// error word set, which moe_layer_forward's caller can read back with moe_layer_health).
+constexpr uint32_t kSpinLimit = 1u << 22;
+
+__device__ __forceinline__ void grid_barrier(uint32_t* counter, uint32_t target, uint32_t* err) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t spins = 0;
+    while (__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+      if (++spins > kSpinLimit) {
+        __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(2);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");  // see what the other workgroups wrote before arriving
+  }
+  __syncthreads();
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(1024) void k_layer_decode(LayerDims L, const DevExpert* __restrict__ table,
+                                                       const float* __restrict__ Wr, const float* __restrict__ bias,
+                                                       const void* __restrict__ x, float* __restrict__ y,
+                                                       int32_t* __restrict__ idx_out, float* __restrict__ gate_out,
+                                                       float* __restrict__ part, uint16_t* __restrict__ h,
+                                                       uint32_t* __restrict__ bar, int32_t n_slices, int32_t slice_cols,
+                                                       int32_t rpw1, int32_t nw1, int32_t spp1, int32_t rpw2,
+                                                       int32_t nw2, int32_t spp2) {
+  extern __shared__ uint32_t smem[];
+  __shared__ int sel_e[8];
+  __shared__ float sel_g[8];
+  __shared__ float red[16];
+  __shared__ float lg[1024];
+  const int d = L.d_model, f = L.d_ff, E = L.n_experts, k = L.top_k;
+  const int G = gridDim.x, b = blockIdx.x, token = blockIdx.y;
+  const int tid0 = threadIdx.x, lane0 = tid0 & 63, wave0 = tid0 >> 6, nwaves = blockDim.x >> 6;
+  uint32_t* bar_t = bar + 4 * token;
+  uint32_t* err = bar + 4 * gridDim.y;
+
+  // ---- phase 0: partial router logits, one (expert, column slice) unit at a time
+  float* part_t = part + (size_t)token * n_slices * E;
+  for (int u = b; u < E * n_slices; u += G) {
+    const int e = u / n_slices, sl = u % n_slices;
+    const int c0 = sl * slice_cols, c1 = min(d, c0 + slice_cols);
+    float acc = 0.f;
+    for (int i = c0 + tid0 * 4; i < c1; i += blockDim.x * 4) {
+      const float4 w = *(const float4*)(Wr + (size_t)e * d + i);
+      float4 v;
+      if (BF16) {
+        const ushort4 q = *(const ushort4*)((const uint16_t*)x + (size_t)token * d + i);
+        v = make_float4(bf16_bits_to_f32(q.x), bf16_bits_to_f32(q.y), bf16_bits_to_f32(q.z), bf16_bits_to_f32(q.w));
+      } else {
+        v = *(const float4*)((const float*)x + (size_t)token * d + i);
+      }
+      acc = fmaf(w.x, v.x, acc); acc = fmaf(w.y, v.y, acc); acc = fmaf(w.z, v.z, acc); acc = fmaf(w.w, v.w, acc);
+    }
+    acc = wave_sum(acc);
+    __syncthreads();                 // red[] from the previous unit has been consumed
+    if (lane0 == 0) red[wave0] = acc;
+    __syncthreads();
+    if (tid0 == 0) {
+      float t = 0.f;
+      for (int w = 0; w < nwaves; ++w) t += red[w];
+      part_t[sl * E + e] = t;
+    }
+  }
+  // the activations of phase 1 travel to LDS while the barrier settles
+  uint16_t* RAW = (uint16_t*)smem;
+  uint32_t* LAY = smem + d / 2;
+  const size_t xbytes = BF16 ? 2 : 4;
+  copy_x_to_lds((const char*)x + (size_t)token * d * xbytes, BF16 ? X_BF16 : X_F32, d, tid0, blockDim.x, RAW);
+  grid_barrier(&bar_t[0], (uint32_t)G, err);
+
+  // ---- logits = ordered sum of the slices (+ bias); softmax + top-k by wavefront 0
+  for (int e = tid0; e < E; e += blockDim.x) {
+    float t = 0.f;
+    for (int sl = 0; sl < n_slices; ++sl) t += part_t[sl * E + e];
+    lg[e] = t + (bias ? bias[e] : 0.f);
+  }
+  __syncthreads();
+  if (tid0 < 64) topk_from_logits(lg, E, k, L.renorm, tid0, sel_e, sel_g, nullptr);
+  __syncthreads();
+  if (b == 0 && tid0 < k) {
+    if (idx_out) idx_out[(size_t)token * k + tid0] = sel_e[tid0];
+    if (gate_out) gate_out[(size_t)token * k + tid0] = sel_g[tid0];
+  }
+
+  // ---- phase 1
+  {
+    const int row_begin = b * rpw1;
+    const int row_end = min(f, row_begin + rpw1);
+    phase1_body(L, table, sel_e, -1, token, h, row_begin, row_end, spp1, RAW, LAY, nw1);
+  }
+  grid_barrier(&bar_t[1], (uint32_t)G, err);
+
+  // ---- phase 2 + combine
+  {
+    const int row_begin = b * rpw2;
+    const int row_end = min(d, row_begin + rpw2);
+    phase2_body(L, table, sel_e, sel_g, -1, 0, token, h, y + (size_t)token * d, row_begin, row_end, rpw2, spp2, smem,
+                nw2);
+  }
+
+  // ---- the last workgroup to get here re-arms the barrier words for the next call
+  __syncthreads();
+  if (tid0 == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(&bar_t[2], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == (uint32_t)G - 1u) {
+      __hip_atomic_store(&bar_t[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&bar_t[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&bar_t[2], 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 }
 
 int num_cus() {
@@ -665,19 +856,14 @@ int num_cus() {
   return cus;
 }
 
-inline size_t lds_bytes(int cols) {
-  // pair registers (2 bytes per position) + offset terms (one per 16 positions) + linear binary16 copy
-  return (size_t)cols * 2 + (size_t)(cols / 16) * 4 + (size_t)cols * 2;
-}
+constexpr size_t kLdsBudget = 150 * 1024;  // of the 160 KB per compute unit; the rest covers static LDS
 
-// Rows per workgroup and wavefronts per workgroup for a GEMV over `rows` output rows. About one
-// workgroup per compute unit when there is enough work; row ranges are multiples of the rows a
-// wavefront covers per step at the widest bitwidth (64/min_P) so that tasks never straddle workgroups.
+// Rows per workgroup and wavefronts per workgroup for a GEMV over `rows` output rows split over
+// `target` workgroups. Row ranges are multiples of the rows a wavefront covers per step at the widest
+// bitwidth (64/min_P) so that tasks never straddle workgroups.
 struct Split { int rows_per_wg, gx, threads; };
-Split plan_rows(int rows, int min_P, int T, int nrm_max) {
+Split plan_rows(int rows, int min_P, int target, int nrm_max) {
   const int RWmax = 64 / min_P;
-  const int cus = num_cus();
-  int target = cus / (T < 1 ? 1 : (T > cus ? cus : T));  // workgroups per token
   if (target < 1) target = 1;
   int rpw = (rows + target - 1) / target;
   rpw = (rpw + RWmax - 1) / RWmax * RWmax;
@@ -699,6 +885,12 @@ Split plan_rows(int rows, int min_P, int T, int nrm_max) {
   return s;
 }
 
+int wgs_per_token(int T) {
+  const int cus = num_cus();
+  int target = cus / (T < 1 ? 1 : (T > cus ? cus : T));
+  return target < 1 ? 1 : target;
+}
+
 int min_lanes_per_row(int cols) {
   int P = 64;
   for (int b = 2; b <= 8; b *= 2) {
@@ -707,6 +899,36 @@ int min_lanes_per_row(int cols) {
     if (p < P) P = p;
   }
   return P;
+}
+
+// LDS bytes and slots per pass of the two phases.
+struct PhaseLds { size_t bytes; int spp; };
+PhaseLds phase1_lds(const LayerDims& L, int k) {
+  const size_t raw = (size_t)L.d_model * 2;
+  const size_t lay = ((size_t)L.d_model / 2 + (size_t)L.d_model / 16) * 4;
+  int spp = (int)((kLdsBudget - raw) / lay);   // layouts that fit: at most one per slot of a pass, 3 distinct
+  if (spp > k) spp = k;
+  if (spp > 3) spp = 3;
+  if (spp < 1) spp = 1;
+  return {raw + (size_t)spp * lay, spp};
+}
+PhaseLds phase2_lds(const LayerDims& L, int k, int rows_per_wg) {
+  const size_t ybuf = (size_t)k * rows_per_wg * 4;
+  const size_t per_slot = ((size_t)L.d_ff / 2 + (size_t)L.d_ff / 16) * 4 + (size_t)L.d_ff * 2;
+  int spp = (int)((kLdsBudget - ybuf) / per_slot);
+  if (spp > k) spp = k;
+  if (spp < 1) spp = 1;
+  return {ybuf + (size_t)spp * per_slot, spp};
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, size_t lds, size_t& granted) {
+  if (lds > 48 * 1024 && lds > granted) {
+    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    granted = lds;
+  }
+  return hipSuccess;
 }
 
 }  // namespace
@@ -720,32 +942,67 @@ hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits, int32_t* idx_out,
                          float* gate_out, int32_t fixed_expert, const void* x, int32_t T, uint16_t* h,
                          hipStream_t st) {
-  const Split sp = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), T, L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
-  const size_t lds = lds_bytes(L.d_model);
-  static size_t lds_set = 0;
-  if (lds > 48 * 1024 && lds > lds_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_ffn_in, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    lds_set = lds;
-  }
-  hipLaunchKernelGGL(k_ffn_in, dim3(sp.gx, T), dim3(sp.threads), lds, st, L, table, logits, idx_out, gate_out,
-                     fixed_expert, x, h, sp.rows_per_wg);
+  const Split sp = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), wgs_per_token(T),
+                             L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
+  const PhaseLds pl = phase1_lds(L, fixed_expert >= 0 ? 1 : L.top_k);
+  static size_t granted = 0;
+  if (hipError_t e = allow_lds(k_ffn_in, pl.bytes, granted); e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_ffn_in, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, logits, idx_out, gate_out,
+                     fixed_expert, x, h, sp.rows_per_wg, pl.spp);
   return hipGetLastError();
 }
 
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx, const float* gate,
                           int32_t fixed_expert, int32_t accumulate, const uint16_t* h, int32_t T, float* y,
                           hipStream_t st) {
-  const Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), T, kBlock);
-  const size_t lds = lds_bytes(L.d_ff) + (size_t)sp.rows_per_wg * sizeof(float);
-  static size_t lds_set = 0;
-  if (lds > 48 * 1024 && lds > lds_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_ffn_out, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    lds_set = lds;
+  const Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), wgs_per_token(T), kBlock);
+  const PhaseLds pl = phase2_lds(L, fixed_expert >= 0 ? 1 : L.top_k, sp.rows_per_wg);
+  static size_t granted = 0;
+  if (hipError_t e = allow_lds(k_ffn_out, pl.bytes, granted); e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_ffn_out, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, idx, gate, fixed_expert,
+                     accumulate, h, y, sp.rows_per_wg, pl.spp);
+  return hipGetLastError();
+}
+
+// One-launch layer. Returns hipErrorNotSupported (and launches nothing) when the shape does not fit
+// the resident-grid scheme; the caller then uses the three-kernel path.
+hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const float* router_w,
+                               const float* router_bias, const void* x, int32_t T, float* y, int32_t* idx_out,
+                               float* gate_out, float* part, uint16_t* h, uint32_t* bar, hipStream_t st) {
+  if (T < 1 || T > kFusedMaxTokens) return hipErrorNotSupported;
+  const int G = wgs_per_token(T);
+  if (G < 8) return hipErrorNotSupported;
+  const Split s1 = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), G, L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
+  const Split s2 = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), G, kBlock);
+  const PhaseLds p1 = phase1_lds(L, L.top_k), p2 = phase2_lds(L, L.top_k, s2.rows_per_wg);
+  const size_t lds = p1.bytes > p2.bytes ? p1.bytes : p2.bytes;
+  if (lds > kLdsBudget) return hipErrorNotSupported;
+  // column slices of the router GEMV: enough (expert, slice) units to give every workgroup one
+  int n_slices = G / L.n_experts;
+  if (n_slices < 1) n_slices = 1;
+  if (n_slices > kFusedMaxSlices) n_slices = kFusedMaxSlices;
+  int slice_cols = (L.d_model + n_slices - 1) / n_slices;
+  slice_cols = (slice_cols + 63) / 64 * 64;
+  n_slices = (L.d_model + slice_cols - 1) / slice_cols;
+  const int threads = 1024;
+  auto kernel = L.x_bf16 ? k_layer_decode<true> : k_layer_decode<false>;
+  static size_t granted[2] = {0, 0};
+  if (hipError_t e = allow_lds(kernel, lds, granted[L.x_bf16 ? 1 : 0]); e != hipSuccess) return e;
+  // every workgroup must be resident at once: the barrier between them is a spin on a counter
+  static int resident[2] = {-1, -1};
+  static size_t resident_lds[2] = {0, 0};
+  int& res = resident[L.x_bf16 ? 1 : 0];
+  if (res < 0 || resident_lds[L.x_bf16 ? 1 : 0] != lds) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kernel, threads, lds) != hipSuccess)
+      return hipErrorNotSupported;
+    res = per_cu * num_cus();
+    resident_lds[L.x_bf16 ? 1 : 0] = lds;
   }
-  hipLaunchKernelGGL(k_ffn_out, dim3(sp.gx, T), dim3(sp.threads), lds, st, L, table, idx, gate, fixed_expert,
-                     accumulate, h, y, sp.rows_per_wg);
+  if (G * T > res) return hipErrorNotSupported;
+  hipLaunchKernelGGL(kernel, dim3(G, T), dim3(threads), lds, st, L, table, router_w, router_bias, x, y, idx_out,
+                     gate_out, part, h, bar, n_slices, slice_cols, s1.rows_per_wg, s1.threads / 64, p1.spp,
+                     s2.rows_per_wg, s2.threads / 64, p2.spp);
   return hipGetLastError();
 }
 

@@ -20,6 +20,13 @@ struct alignas(64) DevExpert {
 };
 static_assert(sizeof(DevExpert) == 64, "expert table entry is 64 bytes");
 
+// One-launch decode path: at most this many tokens per call, and this many column slices of the router
+// GEMV; the barrier words (4 per token + 1 error word) sit behind the expert table in device memory.
+constexpr int kFusedMaxTokens = 16;
+constexpr int kFusedMaxSlices = 32;
+constexpr size_t kBarrierBytes = 512;
+static_assert((4 * kFusedMaxTokens + 1) * 4 <= kBarrierBytes, "barrier words fit");
+
 struct LayerDims {
   int32_t d_model, d_ff, n_experts, top_k, group, act, renorm, x_bf16;
 };
@@ -45,6 +52,14 @@ hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx,
                           const float* gate, int32_t fixed_expert, int32_t accumulate,
                           const uint16_t* h, int32_t T, float* y, hipStream_t st);
+
+// The whole layer in one launch (router partials, grid barrier, top-k, phase 1, grid barrier, phase 2).
+// part: [T][kFusedMaxSlices][E] fp32 scratch; bar: the layer's barrier words. Returns
+// hipErrorNotSupported without launching when the shape does not fit the scheme.
+hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const float* router_w,
+                               const float* router_bias, const void* x, int32_t T, float* y,
+                               int32_t* idx_out, float* gate_out, float* part, uint16_t* h,
+                               uint32_t* bar, hipStream_t st);
 
 hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
                                 uint8_t* q, uint16_t* s, hipStream_t st);

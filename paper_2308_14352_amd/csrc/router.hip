@@ -1,7 +1,7 @@
 // Router GEMV (Section 1; Section 2.1: a small router scores the experts for every token).
 // logits[t][e] = router_w[e] . x[t] (+ bias[e]) in fp32. One workgroup per (expert, group of up to 8
 // tokens): the expert's row is read once with 128-bit loads and dotted with each token of the group;
-// partial sums are folded with cross-lane shuffles, then across the wavefronts through LDS.
+// partial sums are folded with DPP inside each wavefront, then across the wavefronts through LDS.
 // The softmax and the top-k selection run where the result is needed (see the FFN kernels).
 #include "moeq_internal.h"
 
@@ -12,6 +12,24 @@ constexpr int kThreads = 256;
 constexpr int kTokensPerWg = 8;
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Sum over the 64 lanes: DPP inside the 16-lane rows, then the four row totals through scalar reads.
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp<0x124>(v);   // row_ror:4
+  v += dpp<0x128>(v);   // row_ror:8
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
+}
 
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void k_router_logits(LayerDims L, const float* __restrict__ Wr,
@@ -47,10 +65,10 @@ __global__ __launch_bounds__(kThreads) void k_router_logits(LayerDims L, const f
   }
 #pragma unroll
   for (int tt = 0; tt < kTokensPerWg; ++tt) {
-    float v = acc[tt];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    if (lane == 0) part[wave][tt] = v;
+    if (tt < nt) {   // uniform over the workgroup
+      const float v = wave_sum(acc[tt]);
+      if (lane == 0) part[wave][tt] = v;
+    }
   }
   __syncthreads();
   if (tid < nt) {

@@ -115,4 +115,4 @@ def test_compute_entry_points_reject_null_handles_and_shapes():
     assert L.moe_unpack_codes(C.c_void_p(256), 1, 64, 3, C.c_void_p(256), None) == B.MOEQ_EINVAL
     assert L.moe_dequantize(C.c_void_p(256), C.c_void_p(256), 1, 64, 4, 48, C.c_void_p(256), None) == B.MOEQ_EINVAL
     assert L.moe_workspace_bytes(None, 4) == 0
-    assert B.moe_layer_table_bytes(8) == 8 * 64 and B.moe_layer_table_bytes(0) == 0
+    assert B.moe_layer_table_bytes(8) == 8 * 64 + 512 and B.moe_layer_table_bytes(0) == 0

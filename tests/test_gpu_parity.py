@@ -168,6 +168,7 @@ def test_layer_forward_small(base, d, f, E, T):
     assert torch.equal(y, y_b)
     # zero tokens: a no-op
     moeq.moe_layer_forward(layer, x[:0])
+    assert layer.health() == 0
 
 
 def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
@@ -202,6 +203,7 @@ def test_layer_forward_full_size(cfg_id, layer_id, T):
     e = int(idx_ref[0, 0])
     assert np.array_equal(layer.experts[e].q_in.cpu().numpy(), experts[e].q_in)
     assert np.array_equal(s16(layer.experts[e].s_out), experts[e].s_out)
+    assert layer.health() == 0
 
 
 def test_layer_forward_batch8_switch_large_and_workspace_errors():
