@@ -151,6 +151,15 @@ moeq_status moe_unpack_codes(const void *q, int64_t rows, int64_t cols, int32_t 
 moeq_status moe_dequantize(const void *q, const void *s, int64_t rows, int64_t cols, int32_t bits,
                            int32_t group, float *w_out, void *stream);
 
+/* Measurement aid. While `which` is MOEQ_KERNEL_FFN_IN or MOEQ_KERNEL_FFN_OUT, every moe_layer_forward
+ * call records start_event just before and stop_event just after that kernel on the call's stream
+ * (hipEvent_t handles created by the caller with timing enabled), so a benchmark can time the
+ * dominant kernel alone. which = 0 turns it off. Process-wide, not thread-safe; do not use under
+ * stream capture. */
+#define MOEQ_KERNEL_FFN_IN 1  /* phase 1: top-k + W_in / W_gate GEMVs (Section 3.2, dequantize-fused) */
+#define MOEQ_KERNEL_FFN_OUT 2 /* phase 2: W_out GEMVs + gate-weighted combine                          */
+moeq_status moe_profile_kernel(int32_t which, void *start_event, void *stop_event);
+
 const char *moe_status_str(moeq_status st);
 
 #ifdef __cplusplus

@@ -63,6 +63,8 @@ def lib():
     L.moe_layer_destroy.argtypes = [vp]
     L.moe_layer_health.restype = C.c_int
     L.moe_layer_health.argtypes = [vp, C.POINTER(C.c_int32)]
+    L.moe_profile_kernel.restype = C.c_int
+    L.moe_profile_kernel.argtypes = [i32, vp, vp]
     L.moe_workspace_bytes.restype = sz
     L.moe_workspace_bytes.argtypes = [vp, i32]
     L.moe_router_topk.restype = C.c_int
@@ -81,7 +83,7 @@ def lib():
     return L
 
 
-EXPORTS = ["moe_status_str", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
+EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
            "moe_layer_destroy", "moe_layer_health", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
            "moe_layer_forward", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize"]
 
@@ -103,6 +105,14 @@ def _stream(stream):
     if stream is None:
         stream = torch.cuda.current_stream()
     return C.c_void_p(stream.cuda_stream)
+
+
+MOEQ_KERNEL_FFN_IN, MOEQ_KERNEL_FFN_OUT = 1, 2
+
+
+def moe_profile_kernel(which, start_event=None, stop_event=None):
+    """which: 0 (off), MOEQ_KERNEL_FFN_IN or MOEQ_KERNEL_FFN_OUT; events are raw hipEvent_t handles (ints)."""
+    _check(lib().moe_profile_kernel(int(which), C.c_void_p(start_event), C.c_void_p(stop_event)), "moe_profile_kernel")
 
 
 def moe_packed_bytes(rows, cols, bits, group):

@@ -31,7 +31,7 @@ inline bool group_ok(int32_t g, int32_t bits) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {
-  size_t idx_off, gate_off, logits_off, part_off, h_off, total;
+  size_t idx_off, gate_off, logits_off, part_off, sel_off, h_off, hp_off, total;
 };
 
 WsLayout ws_layout(const LayerDims& L, int64_t T) {
@@ -42,12 +42,26 @@ WsLayout ws_layout(const LayerDims& L, int64_t T) {
   w.logits_off = w.gate_off + align_up(slots * sizeof(float), 256);
   w.part_off = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
   const size_t part_tokens = (size_t)(T < kFusedMaxTokens ? T : kFusedMaxTokens);
-  w.h_off = w.part_off + align_up(part_tokens * kFusedMaxSlices * (size_t)L.n_experts * sizeof(float), 256);
-  w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
+  w.sel_off = w.part_off + align_up(part_tokens * kFusedMaxSlices * (size_t)L.n_experts * sizeof(float), 256);
+  w.h_off = w.sel_off + align_up(slots * sizeof(DevExpert), 256);
+  w.hp_off = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
+  w.total = w.hp_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
   return w;
 }
 
 inline moeq_status dev(hipError_t e) { return e == hipSuccess ? MOEQ_OK : MOEQ_EDEVICE; }
+
+// Measurement aid (moe_profile_kernel): events to record around one kernel of moe_layer_forward.
+struct ProfileHook { int32_t which; hipEvent_t start, stop; };
+ProfileHook g_profile = {0, nullptr, nullptr};
+
+struct ScopedEvents {
+  bool on; hipStream_t st;
+  ScopedEvents(int32_t which, hipStream_t s) : on(g_profile.which == which && g_profile.start && g_profile.stop), st(s) {
+    if (on) (void)hipEventRecord(g_profile.start, st);
+  }
+  ~ScopedEvents() { if (on) (void)hipEventRecord(g_profile.stop, st); }
+};
 
 }  // namespace
 
@@ -170,10 +184,12 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
+  uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, nullptr, nullptr, expert, x, n_tokens, h, st);
+  hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, nullptr, nullptr, nullptr, expert, x, n_tokens, h,
+                               hp, st);
   if (e != hipSuccess) return MOEQ_EDEVICE;
-  return dev(launch_ffn_out(layer->dims, layer->table, nullptr, gate_opt, expert, accumulate ? 1 : 0, h,
+  return dev(launch_ffn_out(layer->dims, layer->table, nullptr, gate_opt, expert, accumulate ? 1 : 0, h, hp,
                             n_tokens, y, st));
 }
 
@@ -191,6 +207,8 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   int32_t* idx = topk_idx_opt ? topk_idx_opt : (int32_t*)((char*)ws + w.idx_off);
   float* gate = topk_gate_opt ? topk_gate_opt : (float*)((char*)ws + w.gate_off);
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
+  uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
+  DevExpert* sel_tab = (DevExpert*)((char*)ws + w.sel_off);
   hipStream_t st = (hipStream_t)stream;
   float* logits = (float*)((char*)ws + w.logits_off);
   // Experimental: the whole layer of a few tokens in one launch with grid barriers. Measured slower than
@@ -199,14 +217,26 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   static const bool one_launch = [] { const char* v = std::getenv("MOEQ_ONE_LAUNCH"); return v && v[0] == '1'; }();
   if (one_launch) {
     const hipError_t fused = launch_layer_decode(L, layer->table, layer->router_w, layer->router_bias, x, n_tokens, y,
-                                                 idx, gate, (float*)((char*)ws + w.part_off), h, layer->barrier, st);
+                                                 idx, gate, (float*)((char*)ws + w.part_off), h, hp, layer->barrier, st);
     if (fused == hipSuccess) return MOEQ_OK;
     if (fused != hipErrorNotSupported) return MOEQ_EDEVICE;
   }
   if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
-  if (launch_ffn_in(L, layer->table, logits, idx, gate, -1, x, n_tokens, h, st) != hipSuccess) return MOEQ_EDEVICE;
-  return dev(launch_ffn_out(L, layer->table, idx, gate, -1, 0, h, n_tokens, y, st));
+  {
+    ScopedEvents ev(MOEQ_KERNEL_FFN_IN, st);
+    if (launch_ffn_in(L, layer->table, logits, idx, gate, sel_tab, -1, x, n_tokens, h, hp, st) != hipSuccess)
+      return MOEQ_EDEVICE;
+  }
+  ScopedEvents ev(MOEQ_KERNEL_FFN_OUT, st);
+  return dev(launch_ffn_out(L, layer->table, sel_tab, gate, -1, 0, h, hp, n_tokens, y, st));
+}
+
+moeq_status moe_profile_kernel(int32_t which, void* start_event, void* stop_event) {
+  if (which != 0 && which != MOEQ_KERNEL_FFN_IN && which != MOEQ_KERNEL_FFN_OUT) return MOEQ_EINVAL;
+  if (which != 0 && (!start_event || !stop_event)) return MOEQ_EINVAL;
+  g_profile = ProfileHook{which, (hipEvent_t)start_event, (hipEvent_t)stop_event};
+  return MOEQ_OK;
 }
 
 moeq_status moe_quantize_pack(const float* w, int64_t rows, int64_t cols, int32_t bits, int32_t group,

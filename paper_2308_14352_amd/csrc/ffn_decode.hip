@@ -68,6 +68,28 @@ __device__ __forceinline__ void pair_pos(int pi, int& lo, int& hi, float& presca
   }
 }
 
+// Inverse of pair_pos: where activation number `col` of a vector of C chunks lives in the staged
+// layout (index in units of binary16 values) and its pre-division.
+template <int BITS>
+__device__ __forceinline__ int staged_index(int col, int C, float& prescale) {
+  constexpr int WPC = Fmt<BITS>::WPC;
+  const int c = col / WPC, pos = col % WPC;
+  int pi, half;
+  if (BITS == 8) {
+    const int d = pos >> 2, b = pos & 3;
+    pi = 2 * d + (b & 1); half = b >> 1; prescale = 1.0f;
+  } else if (BITS == 4) {
+    const int d = pos >> 3, n = pos & 7, k = n & 3;
+    pi = 4 * d + k; half = n >> 2; prescale = (k & 1) ? 0.0625f : 1.0f;
+  } else {
+    const int d = pos >> 4, jj = pos & 15, j = jj & 7;
+    pi = 8 * d + j; half = jj >> 3;
+    const int e = j < 5 ? j : j - 5;
+    prescale = 1.0f / (float)(1 << (2 * e));
+  }
+  return (((pi >> 2) * C + c) * 4 + (pi & 3)) * 2 + half;
+}
+
 __device__ __forceinline__ float dot2(uint32_t codes, uint32_t xpair, float acc) {
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, codes), __builtin_bit_cast(half2_t, xpair), acc, false);
 }
@@ -130,6 +152,24 @@ __device__ __forceinline__ void copy_x_to_lds(const void* __restrict__ x, int ki
   }
 }
 
+// XK from a linear binary16 vector (LDS or global memory).
+template <int BITS>
+__device__ __forceinline__ void offset_terms(const uint16_t* lin, int cols, int group, int tid, int nthreads,
+                                             float* XK) {
+  constexpr int WPC = Fmt<BITS>::WPC;
+  const int sub = group < WPC ? group : WPC;   // 16, 32 or 64 weights share a scale inside a chunk
+  const uint4* lin4 = (const uint4*)lin;
+  for (int s = tid; s < cols / sub; s += nthreads) {
+    float acc = 0.f;
+    for (int i = 0; i < sub / 8; ++i) {
+      const uint4 v = lin4[s * (sub / 8) + i];
+      acc += (f16_bits_to_f32(v.x & 0xffffu) + f16_bits_to_f32(v.x >> 16)) + (f16_bits_to_f32(v.y & 0xffffu) + f16_bits_to_f32(v.y >> 16));
+      acc += (f16_bits_to_f32(v.z & 0xffffu) + f16_bits_to_f32(v.z >> 16)) + (f16_bits_to_f32(v.w & 0xffffu) + f16_bits_to_f32(v.w >> 16));
+    }
+    XK[s] = acc * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+  }
+}
+
 template <int BITS>
 __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int group, int tid, int nthreads,
                                           uint32_t* XP, float* XK) {
@@ -144,17 +184,7 @@ __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int gro
     const uint32_t bh = f32_to_f16_bits(f16_bits_to_f32(RAW[c * WPC + hi]) * ps);
     XP[((pi >> 2) * C + c) * 4 + (pi & 3)] = bl | (bh << 16);
   }
-  const int sub = group < WPC ? group : WPC;   // 16, 32 or 64 weights share a scale inside a chunk
-  const uint4* RAW4 = (const uint4*)RAW;
-  for (int s = tid; s < cols / sub; s += nthreads) {
-    float acc = 0.f;
-    for (int i = 0; i < sub / 8; ++i) {
-      const uint4 v = RAW4[s * (sub / 8) + i];
-      acc += (f16_bits_to_f32(v.x & 0xffffu) + f16_bits_to_f32(v.x >> 16)) + (f16_bits_to_f32(v.y & 0xffffu) + f16_bits_to_f32(v.y >> 16));
-      acc += (f16_bits_to_f32(v.z & 0xffffu) + f16_bits_to_f32(v.z >> 16)) + (f16_bits_to_f32(v.w & 0xffffu) + f16_bits_to_f32(v.w >> 16));
-    }
-    XK[s] = acc * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
-  }
+  offset_terms<BITS>(RAW, cols, group, tid, nthreads, XK);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -254,10 +284,14 @@ constexpr int kBlock = 4;  // tiles per block; one block is computed while the n
 // All tasks of one wavefront for one expert. A task is NRM rows (per lane group) of each of NM
 // matrices: rows r0 + i*RW + rsub, i < NRM, with r0 = row_begin + (wave + k*nwaves) * RW*NRM.
 // epilogue(row, totals[NM]) is called by one lane per finished row (row < row_end guaranteed).
-template <int BITS, int NRM, int NM, bool TWO, typename Epilogue>
+// stage() is called exactly once by EVERY thread of the workgroup (it may contain barriers), after the
+// wavefront's first block of weight loads has been issued and before any activation is read from
+// XP/XK: whatever it takes to get the activations into LDS overlaps with the first loads' latency.
+template <int BITS, int NRM, int NM, bool TWO, typename Epilogue, typename Stage>
 __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const uint16_t* const (&s)[NM], int cols,
                                             int group, int nrows, int row_begin, int row_end, int lane, int wave,
-                                            int nwaves, const uint32_t* XP, const float* XK, Epilogue epilogue) {
+                                            int nwaves, const uint32_t* XP, const float* XK, Epilogue epilogue,
+                                            Stage stage) {
   constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
   constexpr int NR = NRM * NM;
   static_assert(NR <= kBlock && kBlock % NR == 0, "rows in flight must divide the block");
@@ -271,9 +305,8 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
   const int ng = cols / group;
   const int task_rows = RW * NRM;
   const int n_tasks = (row_end - row_begin + task_rows - 1) / task_rows;
-  const int n_my = wave < n_tasks ? (n_tasks - wave + nwaves - 1) / nwaves : 0;
-  const int S = n_my * J;  // chunk steps of this wavefront
-  if (S == 0) return;
+  const int n_my = (wave < nwaves && wave < n_tasks) ? (n_tasks - wave + nwaves - 1) / nwaves : 0;
+  const int S = n_my * J;  // chunk steps of this wavefront (0: it only takes part in stage())
   const uint4* XP4 = (const uint4*)XP;
   const uint32_t jstride = (uint32_t)P * 16u;
   const uint32_t row_bytes = (uint32_t)C * 16u;
@@ -370,6 +403,7 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
   const int nblocks = (S + CPB - 1) / CPB;
   Tile bufA[kBlock], bufB[kBlock];
   load_block(bufA, 0);
+  stage();
   for (int blk = 0; blk < nblocks; blk += 2) {
     if (blk + 1 < nblocks) load_block(bufB, blk + 1);
     compute_block(bufA, blk);
@@ -466,15 +500,15 @@ __global__ __launch_bounds__(64) void k_topk(LayerDims L, const float* __restric
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int BITS, bool SWIGLU>
+template <int BITS, bool SWIGLU, typename Stage>
 __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
                                              int row_begin, int row_end, uint16_t* __restrict__ h_out,
-                                             const uint32_t* XP, const float* XK) {
+                                             uint16_t* __restrict__ hp_out, const uint32_t* XP, const float* XK,
+                                             Stage stage) {
   constexpr int NM = SWIGLU ? 2 : 1;
   const int C = d / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
   const int lane = tid & 63, wave = tid >> 6;
-  if (wave >= nwaves) return;
   const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock / NM);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* q_in = uniform_ptr(ex.q_in);
@@ -485,7 +519,12 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
     float v;
     if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
     else v = fmaxf(r[0], 0.f);
-    h_out[row] = (uint16_t)f32_to_f16_bits(v);
+    // linear copy (for the offset terms of phase 2) and the copy already in phase 2's staged order
+    const uint32_t hb = f32_to_f16_bits(v);
+    h_out[row] = (uint16_t)hb;
+    float ps;
+    const int si = staged_index<BITS>(row, f / Fmt<BITS>::WPC, ps);
+    hp_out[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
   };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
@@ -493,11 +532,11 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
     if constexpr (SWIGLU) {
       const uint8_t* const qq[2] = {q_in, q_gate};
       const uint16_t* const ss[2] = {s_in, s_gate};
-      gemv_stream<BITS, NRM, 2, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi);
+      gemv_stream<BITS, NRM, 2, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi, stage);
     } else {
       const uint8_t* const qq[1] = {q_in};
       const uint16_t* const ss[1] = {s_in};
-      gemv_stream<BITS, NRM, 1, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi);
+      gemv_stream<BITS, NRM, 1, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi, stage);
     }
   };
   using T_ = std::true_type;
@@ -515,55 +554,71 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
   else run(std::integral_constant<int, 1>{}, F_{});
 }
 
+// Copies the table records of the k chosen experts into LDS (sel_x), so that nothing later in the
+// kernel waits on a chain of dependent global loads. src_idx == nullptr: the single expert `fixed`.
+__device__ __forceinline__ void load_selected(DevExpert* sel_x, const DevExpert* __restrict__ table,
+                                              const int* src_idx, int fixed, int k) {
+  const int t = threadIdx.x;
+  if (t < k * 4) {
+    const int j = t >> 2, part = t & 3;
+    const int e = src_idx ? src_idx[j] : fixed;
+    ((uint4*)&sel_x[j])[part] = ((const uint4*)&table[e])[part];
+  }
+}
+
 // Phase 1 of one token for the rows [row_begin, row_end) of d_ff: for each chosen expert
 // h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]); h is kept as binary16 (it is the activation vector
-// of phase 2). The activations are already in RAW (LDS, linear binary16). The k experts are handled in
-// passes of `spp`: the activation layouts a pass needs (one per distinct bitwidth) are staged
-// together, then every wavefront streams its tasks of all the pass's experts without a barrier.
-// Called by every thread of the workgroup; the first barrier inside also orders RAW and sel_e.
-__device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert* __restrict__ table, const int* sel_e,
-                                            int fixed_expert, int token, uint16_t* __restrict__ h, int row_begin,
+// of phase 2), once in linear order and once in the staged order phase 2 reads (hp). The activations
+// are already in RAW (LDS, linear binary16) and the chosen experts' records in sel_x (LDS). The k
+// experts are handled in passes of `spp`: the activation layouts a pass needs (one per distinct
+// bitwidth) are staged together, then every wavefront streams its tasks of all the pass's experts
+// without a barrier. Called by every thread of the workgroup; the first barrier inside also orders
+// RAW and sel_x.
+__device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert* sel_x, int k, size_t slot0,
+                                            uint16_t* __restrict__ h, uint16_t* __restrict__ hp, int row_begin,
                                             int row_end, int spp, const uint16_t* RAW, uint32_t* LAY, int nwaves) {
   const int d = L.d_model, f = L.d_ff;
   const int lay_words = d / 2 + d / 16;         // one layout: d/2 pair words + d/16 offset terms
-  const int k = fixed_expert >= 0 ? 1 : L.top_k;
   const bool sw = L.act == MOEQ_ACT_SWIGLU;
+  __syncthreads();  // RAW and sel_x are complete
   for (int j0 = 0; j0 < k; j0 += spp) {
     const int j1 = min(k, j0 + spp);
-    __syncthreads();  // RAW / routing are complete; every wavefront is done with the previous pass's layouts
-    // stage one layout per distinct bitwidth of this pass; layout index = first slot of the pass with it
+    if (j0 > 0) __syncthreads();  // every wavefront is done with the previous pass's layouts
     for (int j = j0; j < j1; ++j) {
-      const int bits = table[fixed_expert >= 0 ? fixed_expert : sel_e[j]].bits;
-      bool first = true;
-      for (int i = j0; i < j; ++i) first = first && (table[sel_e[i]].bits != bits);
-      if (!first) continue;
-      uint32_t* XP = LAY + (j - j0) * lay_words;
-      float* XK = (float*)(XP + d / 2);
-      int tid = threadIdx.x;
-      asm volatile("" : "+v"(tid));
-      if (bits == 2) permute_x<2>(RAW, d, L.group, tid, blockDim.x, XP, XK);
-      else if (bits == 4) permute_x<4>(RAW, d, L.group, tid, blockDim.x, XP, XK);
-      else permute_x<8>(RAW, d, L.group, tid, blockDim.x, XP, XK);
-    }
-    __syncthreads();
-    for (int j = j0; j < j1; ++j) {
-      const int slot = fixed_expert >= 0 ? token : token * k + j;
-      const int e = fixed_expert >= 0 ? fixed_expert : sel_e[j];
-      const DevExpert ex = table[e];
+      const DevExpert ex = sel_x[j];
       int li = j;
       for (int i = j - 1; i >= j0; --i)
-        if (table[sel_e[i]].bits == ex.bits) li = i;
+        if (sel_x[i].bits == ex.bits) li = i;
       const uint32_t* XP = LAY + (li - j0) * lay_words;
       const float* XK = (const float*)(XP + d / 2);
-      uint16_t* h_out = h + (size_t)slot * f;
+      uint16_t* h_out = h + (slot0 + j) * f;
+      uint16_t* hp_out = hp + (slot0 + j) * f;
       // Opaque copy of the thread index: keeps the per-variant lane arithmetic inside this iteration
       // instead of being hoisted (and spilled) ahead of the loop for every bitwidth at once.
       int tid = threadIdx.x;
       asm volatile("" : "+v"(tid));
+      // The first expert of a pass stages, behind its first weight loads, one activation layout per
+      // distinct bitwidth of the pass (layout index = first slot of the pass with that bitwidth).
+      const bool do_stage = (j == j0);
+      auto stage = [&]() {
+        if (!do_stage) return;
+        for (int jj = j0; jj < j1; ++jj) {
+          const int bits = sel_x[jj].bits;
+          bool first = true;
+          for (int i = j0; i < jj; ++i) first = first && (sel_x[i].bits != bits);
+          if (!first) continue;
+          uint32_t* XPs = LAY + (jj - j0) * lay_words;
+          float* XKs = (float*)(XPs + d / 2);
+          if (bits == 2) permute_x<2>(RAW, d, L.group, tid, blockDim.x, XPs, XKs);
+          else if (bits == 4) permute_x<4>(RAW, d, L.group, tid, blockDim.x, XPs, XKs);
+          else permute_x<8>(RAW, d, L.group, tid, blockDim.x, XPs, XKs);
+        }
+        __syncthreads();
+      };
       auto run = [&](auto bits_tag) {
         constexpr int BITS = decltype(bits_tag)::value;
-        if (sw) ffn_in_tasks<BITS, true>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, XP, XK);
-        else ffn_in_tasks<BITS, false>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, XP, XK);
+        if (sw) ffn_in_tasks<BITS, true>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, hp_out, XP, XK, stage);
+        else ffn_in_tasks<BITS, false>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, hp_out, XP, XK, stage);
       };
       switch (ex.bits) {
         case 2: run(std::integral_constant<int, 2>{}); break;
@@ -574,15 +629,18 @@ __device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert*
   }
 }
 
-// Stand-alone phase 1: (optionally) top-k from the router logits, then phase1_body.
+// Stand-alone phase 1: (optionally) top-k from the router logits, then phase1_body. Workgroup 0 of a
+// token also publishes the routing (idx, gate) and the chosen experts' records (sel_tab) for phase 2.
 __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* __restrict__ table,
                                                  const float* __restrict__ logits, int32_t* __restrict__ idx_out,
-                                                 float* __restrict__ gate_out, int32_t fixed_expert,
-                                                 const void* __restrict__ x, uint16_t* __restrict__ h,
+                                                 float* __restrict__ gate_out, DevExpert* __restrict__ sel_tab,
+                                                 int32_t fixed_expert, const void* __restrict__ x,
+                                                 uint16_t* __restrict__ h, uint16_t* __restrict__ hp,
                                                  int32_t rows_per_wg, int32_t slots_per_pass) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
+  __shared__ DevExpert sel_x[8];
   const int d = L.d_model, f = L.d_ff;
   const int token = blockIdx.y;
   uint16_t* RAW = (uint16_t*)smem;              // d halfs, then the layouts
@@ -594,26 +652,33 @@ __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* _
     if (threadIdx.x < 64) topk_from_logits(logits + (size_t)token * L.n_experts, L.n_experts, k, L.renorm,
                                            threadIdx.x, sel_e, sel_g, nullptr);
     __syncthreads();
+    load_selected(sel_x, table, sel_e, -1, k);
     if (blockIdx.x == 0 && threadIdx.x < k) {
       idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
       gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
     }
+    if (blockIdx.x == 0) {
+      __syncthreads();
+      if (threadIdx.x < k * 4)
+        ((uint4*)&sel_tab[(size_t)token * k])[threadIdx.x] = ((const uint4*)sel_x)[threadIdx.x];
+    }
+  } else {
+    load_selected(sel_x, table, nullptr, fixed_expert, 1);
   }
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(f, row_begin + rows_per_wg);
-  phase1_body(L, table, sel_e, fixed_expert, token, h, row_begin, row_end, slots_per_pass, RAW, LAY,
-              (int)(blockDim.x >> 6));
+  phase1_body(L, sel_x, k, fixed_expert >= 0 ? (size_t)token : (size_t)token * k, h, hp, row_begin, row_end,
+              slots_per_pass, RAW, LAY, (int)(blockDim.x >> 6));
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int BITS>
+template <int BITS, typename Stage>
 __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
                                               float g, int row_begin, int row_end, float* ybuf, const uint32_t* XP,
-                                              const float* XK) {
+                                              const float* XK, Stage stage) {
   const int C = f / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
   const int lane = tid & 63, wave = tid >> 6;
-  if (wave >= nwaves) return;
   const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* const qq[1] = {uniform_ptr(ex.q_out)};
@@ -622,7 +687,7 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
-    gemv_stream<BITS, NRM, 1, TWO>(qq, ss, f, group, d, row_begin, row_end, lane, wave, nwaves, XP, XK, epi);
+    gemv_stream<BITS, NRM, 1, TWO>(qq, ss, f, group, d, row_begin, row_end, lane, wave, nwaves, XP, XK, epi, stage);
   };
   using T_ = std::true_type;
   using F_ = std::false_type;
@@ -641,51 +706,54 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
 
 // Phase 2 + combine of one token for the rows [row_begin, row_end) of d_model:
 // y[t][r] (+)= sum_j gate_j * W_out_j[r] . h[slot_j]. Experts are handled in passes of `spp`: their
-// activation vectors are staged together, every wavefront streams its tasks of all of them without a
-// barrier, each expert's contribution lands in its own LDS row buffer, and the buffers are summed in
-// top-k order at the end: ordered, no atomics, every output written once.
-// idx_tok / gate_tok: this token's k choices (LDS or global); gate_tok may be null (= 1).
-__device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert* __restrict__ table, const int* idx_tok,
-                                            const float* gate_tok, int fixed_expert, int accumulate, int token,
-                                            const uint16_t* __restrict__ h, float* __restrict__ y_out, int row_begin,
-                                            int row_end, int rows_per_wg, int spp, uint32_t* smem, int nwaves) {
+// activation vectors (already in staged order in hp) are copied to LDS together, the offset terms are
+// summed from the linear copy h, every wavefront streams its tasks of all of them without a barrier,
+// each expert's contribution lands in its own LDS row buffer, and the buffers are summed in top-k order
+// at the end: ordered, no atomics, every output written once.
+// sel_x: the k chosen experts' records (LDS); gate_tok: their gates (LDS or global), may be null (= 1).
+__device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert* sel_x, const float* gate_tok, int k,
+                                            int accumulate, size_t slot0, const uint16_t* __restrict__ h,
+                                            const uint16_t* __restrict__ hp, float* __restrict__ y_out,
+                                            int row_begin, int row_end, int rows_per_wg, int spp, uint32_t* smem,
+                                            int nwaves) {
   const int d = L.d_model, f = L.d_ff;
-  const int k = fixed_expert >= 0 ? 1 : L.top_k;
   const int lay_words = f / 2 + f / 16;          // pair words + offset terms of one activation vector
   float* ybuf = (float*)smem;                    // [k][rows_per_wg]
   uint32_t* LAY = smem + k * rows_per_wg;        // [spp][lay_words]
-  uint16_t* RAWS = (uint16_t*)(LAY + spp * lay_words);  // [spp][f]
+  __syncthreads();  // sel_x / gates are complete
   for (int j0 = 0; j0 < k; j0 += spp) {
     const int j1 = min(k, j0 + spp);
     if (j0 > 0) __syncthreads();  // every wavefront is done with the previous pass's activations
     for (int j = j0; j < j1; ++j) {
-      const int slot = fixed_expert >= 0 ? token : token * k + j;
-      copy_x_to_lds(h + (size_t)slot * f, X_F16, f, threadIdx.x, blockDim.x, RAWS + (size_t)(j - j0) * f);
-    }
-    __syncthreads();
-    for (int j = j0; j < j1; ++j) {
-      const int bits = table[fixed_expert >= 0 ? fixed_expert : idx_tok[j]].bits;
-      uint32_t* XP = LAY + (j - j0) * lay_words;
-      float* XK = (float*)(XP + f / 2);
-      const uint16_t* RAW = RAWS + (size_t)(j - j0) * f;
-      int tid = threadIdx.x;       // opaque copy: keeps per-variant lane arithmetic out of the prologue
-      asm volatile("" : "+v"(tid));
-      if (bits == 2) permute_x<2>(RAW, f, L.group, tid, blockDim.x, XP, XK);
-      else if (bits == 4) permute_x<4>(RAW, f, L.group, tid, blockDim.x, XP, XK);
-      else permute_x<8>(RAW, f, L.group, tid, blockDim.x, XP, XK);
-    }
-    __syncthreads();
-    for (int j = j0; j < j1; ++j) {
-      const int e = fixed_expert >= 0 ? fixed_expert : idx_tok[j];
-      const float g = gate_tok ? gate_tok[fixed_expert >= 0 ? 0 : j] : 1.0f;
-      const DevExpert ex = table[e];
+      const float g = gate_tok ? gate_tok[j] : 1.0f;
+      const DevExpert ex = sel_x[j];
       const uint32_t* XP = LAY + (j - j0) * lay_words;
       const float* XK = (const float*)(XP + f / 2);
-      int tid = threadIdx.x;
+      int tid = threadIdx.x;       // opaque copy: keeps per-variant lane arithmetic out of the prologue
       asm volatile("" : "+v"(tid));
+      // The first expert of a pass brings, behind its first weight loads, the activation vectors of all
+      // the pass's experts into LDS (already in staged order) and sums their offset terms.
+      const bool do_stage = (j == j0);
+      auto stage = [&]() {
+        if (!do_stage) return;
+        const int per = f / 8, n = (j1 - j0) * per;
+        for (int i = tid; i < n; i += blockDim.x) {
+          const int jj = i / per, r = i - jj * per;
+          ((uint4*)(LAY + jj * lay_words))[r] = ((const uint4*)(hp + (slot0 + j0 + jj) * f))[r];
+        }
+        for (int jj = j0; jj < j1; ++jj) {
+          float* XKs = (float*)(LAY + (jj - j0) * lay_words + f / 2);
+          const uint16_t* lin = h + (slot0 + jj) * f;
+          const int bits = sel_x[jj].bits;
+          if (bits == 2) offset_terms<2>(lin, f, L.group, tid, blockDim.x, XKs);
+          else if (bits == 4) offset_terms<4>(lin, f, L.group, tid, blockDim.x, XKs);
+          else offset_terms<8>(lin, f, L.group, tid, blockDim.x, XKs);
+        }
+        __syncthreads();
+      };
       auto run = [&](auto bits_tag) {
         constexpr int BITS = decltype(bits_tag)::value;
-        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, row_begin, row_end, ybuf + j * rows_per_wg, XP, XK);
+        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, row_begin, row_end, ybuf + j * rows_per_wg, XP, XK, stage);
       };
       switch (ex.bits) {
         case 2: run(std::integral_constant<int, 2>{}); break;
@@ -702,19 +770,28 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
   }
 }
 
+// Stand-alone phase 2. sel_tab: the chosen experts' records written by phase 1 (fixed_expert < 0).
 __global__ __launch_bounds__(1024) void k_ffn_out(LayerDims L, const DevExpert* __restrict__ table,
-                                                  const int32_t* __restrict__ idx, const float* __restrict__ gate,
+                                                  const DevExpert* __restrict__ sel_tab, const float* __restrict__ gate,
                                                   int32_t fixed_expert, int32_t accumulate,
-                                                  const uint16_t* __restrict__ h, float* __restrict__ y,
-                                                  int32_t rows_per_wg, int32_t slots_per_pass) {
+                                                  const uint16_t* __restrict__ h, const uint16_t* __restrict__ hp,
+                                                  float* __restrict__ y, int32_t rows_per_wg, int32_t slots_per_pass) {
   extern __shared__ uint32_t smem[];
+  __shared__ DevExpert sel_x[8];
+  __shared__ float sel_g[8];
   const int d = L.d_model;
   const int token = blockIdx.y;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
+  const size_t slot0 = fixed_expert >= 0 ? (size_t)token : (size_t)token * k;
+  if (fixed_expert >= 0) {
+    load_selected(sel_x, table, nullptr, fixed_expert, 1);
+  } else if (threadIdx.x < k * 4) {
+    ((uint4*)sel_x)[threadIdx.x] = ((const uint4*)&sel_tab[slot0])[threadIdx.x];
+  }
+  if (threadIdx.x < k) sel_g[threadIdx.x] = gate ? gate[slot0 + threadIdx.x] : 1.0f;
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(d, row_begin + rows_per_wg);
-  phase2_body(L, table, idx ? idx + (size_t)token * k : nullptr, gate ? gate + (size_t)token * k : nullptr,
-              fixed_expert, accumulate, token, h, y + (size_t)token * d, row_begin, row_end, rows_per_wg,
+  phase2_body(L, sel_x, sel_g, k, accumulate, slot0, h, hp, y + (size_t)token * d, row_begin, row_end, rows_per_wg,
               slots_per_pass, smem, (int)(blockDim.x >> 6));
 }
 
@@ -754,12 +831,14 @@ __global__ __launch_bounds__(1024) void k_layer_decode(LayerDims L, const DevExp
                                                        const void* __restrict__ x, float* __restrict__ y,
                                                        int32_t* __restrict__ idx_out, float* __restrict__ gate_out,
                                                        float* __restrict__ part, uint16_t* __restrict__ h,
-                                                       uint32_t* __restrict__ bar, int32_t n_slices, int32_t slice_cols,
+                                                       uint16_t* __restrict__ hp, uint32_t* __restrict__ bar,
+                                                       int32_t n_slices, int32_t slice_cols,
                                                        int32_t rpw1, int32_t nw1, int32_t spp1, int32_t rpw2,
                                                        int32_t nw2, int32_t spp2) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
+  __shared__ DevExpert sel_x[8];
   __shared__ float red[16];
   __shared__ float lg[1024];
   const int d = L.d_model, f = L.d_ff, E = L.n_experts, k = L.top_k;
@@ -811,6 +890,7 @@ __global__ __launch_bounds__(1024) void k_layer_decode(LayerDims L, const DevExp
   __syncthreads();
   if (tid0 < 64) topk_from_logits(lg, E, k, L.renorm, tid0, sel_e, sel_g, nullptr);
   __syncthreads();
+  load_selected(sel_x, table, sel_e, -1, k);
   if (b == 0 && tid0 < k) {
     if (idx_out) idx_out[(size_t)token * k + tid0] = sel_e[tid0];
     if (gate_out) gate_out[(size_t)token * k + tid0] = sel_g[tid0];
@@ -820,7 +900,7 @@ __global__ __launch_bounds__(1024) void k_layer_decode(LayerDims L, const DevExp
   {
     const int row_begin = b * rpw1;
     const int row_end = min(f, row_begin + rpw1);
-    phase1_body(L, table, sel_e, -1, token, h, row_begin, row_end, spp1, RAW, LAY, nw1);
+    phase1_body(L, sel_x, k, (size_t)token * k, h, hp, row_begin, row_end, spp1, RAW, LAY, nw1);
   }
   grid_barrier(&bar_t[1], (uint32_t)G, err);
 
@@ -828,8 +908,8 @@ __global__ __launch_bounds__(1024) void k_layer_decode(LayerDims L, const DevExp
   {
     const int row_begin = b * rpw2;
     const int row_end = min(d, row_begin + rpw2);
-    phase2_body(L, table, sel_e, sel_g, -1, 0, token, h, y + (size_t)token * d, row_begin, row_end, rpw2, spp2, smem,
-                nw2);
+    phase2_body(L, sel_x, sel_g, k, 0, (size_t)token * k, h, hp, y + (size_t)token * d, row_begin, row_end, rpw2,
+                spp2, smem, nw2);
   }
 
   // ---- the last workgroup to get here re-arms the barrier words for the next call
@@ -914,7 +994,7 @@ PhaseLds phase1_lds(const LayerDims& L, int k) {
 }
 PhaseLds phase2_lds(const LayerDims& L, int k, int rows_per_wg) {
   const size_t ybuf = (size_t)k * rows_per_wg * 4;
-  const size_t per_slot = ((size_t)L.d_ff / 2 + (size_t)L.d_ff / 16) * 4 + (size_t)L.d_ff * 2;
+  const size_t per_slot = ((size_t)L.d_ff / 2 + (size_t)L.d_ff / 16) * 4;
   int spp = (int)((kLdsBudget - ybuf) / per_slot);
   if (spp > k) spp = k;
   if (spp < 1) spp = 1;
@@ -940,27 +1020,27 @@ hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32
 }
 
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits, int32_t* idx_out,
-                         float* gate_out, int32_t fixed_expert, const void* x, int32_t T, uint16_t* h,
-                         hipStream_t st) {
+                         float* gate_out, DevExpert* sel_tab, int32_t fixed_expert, const void* x, int32_t T,
+                         uint16_t* h, uint16_t* hp, hipStream_t st) {
   const Split sp = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), wgs_per_token(T),
                              L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
   const PhaseLds pl = phase1_lds(L, fixed_expert >= 0 ? 1 : L.top_k);
   static size_t granted = 0;
   if (hipError_t e = allow_lds(k_ffn_in, pl.bytes, granted); e != hipSuccess) return e;
   hipLaunchKernelGGL(k_ffn_in, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, logits, idx_out, gate_out,
-                     fixed_expert, x, h, sp.rows_per_wg, pl.spp);
+                     sel_tab, fixed_expert, x, h, hp, sp.rows_per_wg, pl.spp);
   return hipGetLastError();
 }
 
-hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx, const float* gate,
-                          int32_t fixed_expert, int32_t accumulate, const uint16_t* h, int32_t T, float* y,
-                          hipStream_t st) {
+hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevExpert* sel_tab, const float* gate,
+                          int32_t fixed_expert, int32_t accumulate, const uint16_t* h, const uint16_t* hp, int32_t T,
+                          float* y, hipStream_t st) {
   const Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), wgs_per_token(T), kBlock);
   const PhaseLds pl = phase2_lds(L, fixed_expert >= 0 ? 1 : L.top_k, sp.rows_per_wg);
   static size_t granted = 0;
   if (hipError_t e = allow_lds(k_ffn_out, pl.bytes, granted); e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_ffn_out, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, idx, gate, fixed_expert,
-                     accumulate, h, y, sp.rows_per_wg, pl.spp);
+  hipLaunchKernelGGL(k_ffn_out, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, sel_tab, gate, fixed_expert,
+                     accumulate, h, hp, y, sp.rows_per_wg, pl.spp);
   return hipGetLastError();
 }
 
@@ -968,7 +1048,8 @@ hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int3
 // the resident-grid scheme; the caller then uses the three-kernel path.
 hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const float* router_w,
                                const float* router_bias, const void* x, int32_t T, float* y, int32_t* idx_out,
-                               float* gate_out, float* part, uint16_t* h, uint32_t* bar, hipStream_t st) {
+                               float* gate_out, float* part, uint16_t* h, uint16_t* hp, uint32_t* bar,
+                               hipStream_t st) {
   if (T < 1 || T > kFusedMaxTokens) return hipErrorNotSupported;
   const int G = wgs_per_token(T);
   if (G < 8) return hipErrorNotSupported;
@@ -1001,7 +1082,7 @@ hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const
   }
   if (G * T > res) return hipErrorNotSupported;
   hipLaunchKernelGGL(kernel, dim3(G, T), dim3(threads), lds, st, L, table, router_w, router_bias, x, y, idx_out,
-                     gate_out, part, h, bar, n_slices, slice_cols, s1.rows_per_wg, s1.threads / 64, p1.spp,
+                     gate_out, part, h, hp, bar, n_slices, slice_cols, s1.rows_per_wg, s1.threads / 64, p1.spp,
                      s2.rows_per_wg, s2.threads / 64, p2.spp);
   return hipGetLastError();
 }

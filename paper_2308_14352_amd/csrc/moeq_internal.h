@@ -40,18 +40,19 @@ hipError_t launch_router_logits(const LayerDims& L, const float* router_w, const
 hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32_t* idx, float* gate,
                        float* probs, hipStream_t st);
 
-// Phase 1 of the expert FFN: h[slot][f] = act(W_in x [, W_gate x]), stored as binary16.
+// Phase 1 of the expert FFN: h[slot][f] = act(W_in x [, W_gate x]), stored as binary16 twice: linear
+// (h) and in the staged order phase 2 reads (hp).
 // fixed_expert >= 0: every token uses that expert (slot == token). Otherwise each workgroup derives
-// the token's top-k from `logits`, the routing is also written to idx_out/gate_out, and
-// slot = token * top_k + j.
+// the token's top-k from `logits`, the routing is written to idx_out/gate_out, the chosen experts'
+// table records to sel_tab[slot], and slot = token * top_k + j.
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits,
-                         int32_t* idx_out, float* gate_out, int32_t fixed_expert, const void* x,
-                         int32_t T, uint16_t* h, hipStream_t st);
+                         int32_t* idx_out, float* gate_out, DevExpert* sel_tab, int32_t fixed_expert,
+                         const void* x, int32_t T, uint16_t* h, uint16_t* hp, hipStream_t st);
 
 // Phase 2 + combine: y[t] (+)= sum_j gate * W_out h[slot].
-hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int32_t* idx,
+hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevExpert* sel_tab,
                           const float* gate, int32_t fixed_expert, int32_t accumulate,
-                          const uint16_t* h, int32_t T, float* y, hipStream_t st);
+                          const uint16_t* h, const uint16_t* hp, int32_t T, float* y, hipStream_t st);
 
 // The whole layer in one launch (router partials, grid barrier, top-k, phase 1, grid barrier, phase 2).
 // part: [T][kFusedMaxSlices][E] fp32 scratch; bar: the layer's barrier words. Returns
@@ -59,7 +60,7 @@ hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const int3
 hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const float* router_w,
                                const float* router_bias, const void* x, int32_t T, float* y,
                                int32_t* idx_out, float* gate_out, float* part, uint16_t* h,
-                               uint32_t* bar, hipStream_t st);
+                               uint16_t* hp, uint32_t* bar, hipStream_t st);
 
 hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
                                 uint8_t* q, uint16_t* s, hipStream_t st);
