@@ -280,6 +280,7 @@ struct Tile {
   uint32_t s;  // one binary16 scale, or two adjacent ones (INT2 with group 32)
 };
 constexpr int kBlock = 4;  // tiles per block; one block is computed while the next is in flight
+constexpr int kMaxKs = 4;  // at most this many wavefront teams split a row along its length
 
 // All tasks of one wavefront for one expert. A task is NRM rows (per lane group) of each of NM
 // matrices: rows r0 + i*RW + rsub, i < NRM, with r0 = row_begin + (wave + k*nwaves) * RW*NRM.
@@ -290,8 +291,8 @@ constexpr int kBlock = 4;  // tiles per block; one block is computed while the n
 template <int BITS, int NRM, int NM, bool TWO, typename Epilogue, typename Stage>
 __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const uint16_t* const (&s)[NM], int cols,
                                             int group, int nrows, int row_begin, int row_end, int lane, int wave,
-                                            int nwaves, const uint32_t* XP, const float* XK, Epilogue epilogue,
-                                            Stage stage) {
+                                            int nwaves, int ks_parts, const uint32_t* XP, const float* XK,
+                                            Epilogue epilogue, Stage stage) {
   constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
   constexpr int NR = NRM * NM;
   static_assert(NR <= kBlock && kBlock % NR == 0, "rows in flight must divide the block");
@@ -301,11 +302,17 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
   while (P < 64 && C % (P * 2) == 0) P *= 2;
   const int RW = 64 / P;
   const int p = lane % P, rsub = lane / P;
-  const int J = C / P;
+  // The nwaves wavefronts form ks_parts teams; team `part` covers the chunk steps
+  // [jb, jb + J) of every row, and its wavefronts share the tasks. epilogue gets partial sums then.
+  const int wpp = nwaves / ks_parts;            // wavefronts per team
+  const int part = wave / wpp, tw = wave - part * wpp;
+  const int Jfull = C / P;
+  const int jb = (part * Jfull) / ks_parts;
+  const int J = (wave < nwaves) ? ((part + 1) * Jfull) / ks_parts - jb : 0;
   const int ng = cols / group;
   const int task_rows = RW * NRM;
   const int n_tasks = (row_end - row_begin + task_rows - 1) / task_rows;
-  const int n_my = (wave < nwaves && wave < n_tasks) ? (n_tasks - wave + nwaves - 1) / nwaves : 0;
+  const int n_my = (wave < nwaves && tw < n_tasks) ? (n_tasks - tw + wpp - 1) / wpp : 0;
   const int S = n_my * J;  // chunk steps of this wavefront (0: it only takes part in stage())
   const uint4* XP4 = (const uint4*)XP;
   const uint32_t jstride = (uint32_t)P * 16u;
@@ -316,7 +323,7 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
   uint32_t qoff[NR], soff[NR];
   auto load_step = [&](Tile (&t)[kBlock], int u0) {
     if (pj == 0) {
-      const int r0 = row_begin + (wave + pk * nwaves) * task_rows + rsub;
+      const int r0 = row_begin + (tw + pk * wpp) * task_rows + rsub;
 #pragma unroll
       for (int v = 0; v < NR; ++v) {
         int row = r0 + (v % NRM) * RW;
@@ -325,11 +332,11 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
         soff[v] = ((uint32_t)row * (uint32_t)ng) * 2u;
       }
     }
-    const uint32_t g0 = ((uint32_t)((p + pj * P) * WPC) / (uint32_t)group) * 2u;
+    const uint32_t g0 = ((uint32_t)((p + (jb + pj) * P) * WPC) / (uint32_t)group) * 2u;
 #pragma unroll
     for (int v = 0; v < NR; ++v) {
       const int m = v / NRM;
-      t[u0 + v].w = load_stream16(q[m] + (qoff[v] + (uint32_t)pj * jstride));
+      t[u0 + v].w = load_stream16(q[m] + (qoff[v] + (uint32_t)(jb + pj) * jstride));
       const uint8_t* sb = (const uint8_t*)s[m];
       if (TWO) t[u0 + v].s = *(const uint32_t*)(sb + (soff[v] + g0));
       else t[u0 + v].s = *(const uint16_t*)(sb + (soff[v] + g0));
@@ -351,7 +358,7 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
       for (int v = 0; v < NR; ++v) tot[v] = 0.f;
     }
     uint32_t xr[PPC];
-    const int c = p + cj * P;
+    const int c = p + (jb + cj) * P;
 #pragma unroll
     for (int qq = 0; qq < PPC / 4; ++qq) {
       const uint4 t4 = XP4[qq * C + c];
@@ -382,12 +389,12 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
     if (++cj == J) {
       fold_rows<NRM, NM>(tot, P, lane);
       if (p < NRM) {
-        const int row = row_begin + (wave + ck * nwaves) * task_rows + p * RW + rsub;
+        const int row = row_begin + (tw + ck * wpp) * task_rows + p * RW + rsub;
         if (row < row_end) {
           float r[NM];
 #pragma unroll
           for (int m = 0; m < NM; ++m) r[m] = tot[m * NRM];
-          epilogue(row, r);
+          epilogue(row, r, part);
         }
       }
       cj = 0;
@@ -515,7 +522,7 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
   const uint16_t* s_in = uniform_ptr(ex.s_in);
   const uint8_t* q_gate = SWIGLU ? uniform_ptr(ex.q_gate) : nullptr;
   const uint16_t* s_gate = SWIGLU ? uniform_ptr(ex.s_gate) : nullptr;
-  auto epi = [&](int row, const float (&r)[NM]) {
+  auto epi = [&](int row, const float (&r)[NM], int) {
     float v;
     if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
     else v = fmaxf(r[0], 0.f);
@@ -532,11 +539,11 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
     if constexpr (SWIGLU) {
       const uint8_t* const qq[2] = {q_in, q_gate};
       const uint16_t* const ss[2] = {s_in, s_gate};
-      gemv_stream<BITS, NRM, 2, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi, stage);
+      gemv_stream<BITS, NRM, 2, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, 1, XP, XK, epi, stage);
     } else {
       const uint8_t* const qq[1] = {q_in};
       const uint16_t* const ss[1] = {s_in};
-      gemv_stream<BITS, NRM, 1, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, XP, XK, epi, stage);
+      gemv_stream<BITS, NRM, 1, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, 1, XP, XK, epi, stage);
     }
   };
   using T_ = std::true_type;
@@ -672,22 +679,33 @@ __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* _
 }
 
 // ---------------------------------------------------------------------------------------------
+// Number of wavefront teams that split every row of a phase-2 GEMV along its length: the rows a
+// workgroup owns are few and long, so without the split most wavefronts would have no task.
+__host__ __device__ inline int pick_ks(int rows_in_wg, int RW, int nwaves, int Jfull) {
+  const int tasks1 = (rows_in_wg + RW - 1) / RW;   // tasks at one row per lane group
+  int ks = 1;
+  while (ks < kMaxKs && tasks1 * ks * 2 <= nwaves && ks * 2 <= Jfull && nwaves % (ks * 2) == 0) ks *= 2;
+  return ks;
+}
+
 template <int BITS, typename Stage>
 __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
-                                              float g, int row_begin, int row_end, float* ybuf, const uint32_t* XP,
-                                              const float* XK, Stage stage) {
+                                              float g, int row_begin, int row_end, int rows_per_wg, float* ybuf,
+                                              const uint32_t* XP, const float* XK, Stage stage) {
   const int C = f / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
   const int lane = tid & 63, wave = tid >> 6;
-  const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock);
+  const int ks = pick_ks(row_end - row_begin, RW, nwaves, C / P);
+  const int nrm = pick_nrm(row_end - row_begin, RW, nwaves / ks, P, kBlock);
   const bool two = (BITS == 2) && (group == 32);
   const uint8_t* const qq[1] = {uniform_ptr(ex.q_out)};
   const uint16_t* const ss[1] = {uniform_ptr(ex.s_out)};
-  auto epi = [&](int row, const float (&r)[1]) { ybuf[row - row_begin] = g * r[0]; };
+  // ybuf: [kMaxKs][rows_per_wg] partial sums of this expert; teams beyond ks are zeroed by the caller
+  auto epi = [&](int row, const float (&r)[1], int part) { ybuf[part * rows_per_wg + (row - row_begin)] = g * r[0]; };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
-    gemv_stream<BITS, NRM, 1, TWO>(qq, ss, f, group, d, row_begin, row_end, lane, wave, nwaves, XP, XK, epi, stage);
+    gemv_stream<BITS, NRM, 1, TWO>(qq, ss, f, group, d, row_begin, row_end, lane, wave, nwaves, ks, XP, XK, epi, stage);
   };
   using T_ = std::true_type;
   using F_ = std::false_type;
@@ -718,8 +736,9 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
                                             int nwaves) {
   const int d = L.d_model, f = L.d_ff;
   const int lay_words = f / 2 + f / 16;          // pair words + offset terms of one activation vector
-  float* ybuf = (float*)smem;                    // [k][rows_per_wg]
-  uint32_t* LAY = smem + k * rows_per_wg;        // [spp][lay_words]
+  float* ybuf = (float*)smem;                    // [k][kMaxKs][rows_per_wg]
+  uint32_t* LAY = smem + k * kMaxKs * rows_per_wg;   // [spp][lay_words]
+  for (int i = threadIdx.x; i < k * kMaxKs * rows_per_wg; i += blockDim.x) ybuf[i] = 0.f;
   __syncthreads();  // sel_x / gates are complete
   for (int j0 = 0; j0 < k; j0 += spp) {
     const int j1 = min(k, j0 + spp);
@@ -753,7 +772,8 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
       };
       auto run = [&](auto bits_tag) {
         constexpr int BITS = decltype(bits_tag)::value;
-        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, row_begin, row_end, ybuf + j * rows_per_wg, XP, XK, stage);
+        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, row_begin, row_end, rows_per_wg,
+                            ybuf + j * kMaxKs * rows_per_wg, XP, XK, stage);
       };
       switch (ex.bits) {
         case 2: run(std::integral_constant<int, 2>{}); break;
@@ -765,7 +785,11 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
   __syncthreads();
   for (int i = row_begin + (int)threadIdx.x; i < row_end; i += blockDim.x) {
     float acc = accumulate ? y_out[i] : 0.f;
-    for (int j = 0; j < k; ++j) acc += ybuf[j * rows_per_wg + (i - row_begin)];
+    for (int j = 0; j < k; ++j) {      // experts in top-k order, teams in order: a fixed summation order
+      float e_sum = 0.f;
+      for (int pt = 0; pt < kMaxKs; ++pt) e_sum += ybuf[(j * kMaxKs + pt) * rows_per_wg + (i - row_begin)];
+      acc += e_sum;
+    }
     y_out[i] = acc;
   }
 }
@@ -965,6 +989,14 @@ Split plan_rows(int rows, int min_P, int target, int nrm_max) {
   return s;
 }
 
+// Phase 2 rows are few and long: wavefronts beyond one per task team up along the row (pick_ks), so the
+// workgroup is widened to the largest power-of-two multiple of the planned size that still fits.
+int phase2_threads(int threads) {
+  int w = threads / 64;
+  while (w * 2 <= 16) w *= 2;
+  return w * 64;
+}
+
 int wgs_per_token(int T) {
   const int cus = num_cus();
   int target = cus / (T < 1 ? 1 : (T > cus ? cus : T));
@@ -993,7 +1025,7 @@ PhaseLds phase1_lds(const LayerDims& L, int k) {
   return {raw + (size_t)spp * lay, spp};
 }
 PhaseLds phase2_lds(const LayerDims& L, int k, int rows_per_wg) {
-  const size_t ybuf = (size_t)k * rows_per_wg * 4;
+  const size_t ybuf = (size_t)k * kMaxKs * rows_per_wg * 4;
   const size_t per_slot = ((size_t)L.d_ff / 2 + (size_t)L.d_ff / 16) * 4;
   int spp = (int)((kLdsBudget - ybuf) / per_slot);
   if (spp > k) spp = k;
@@ -1035,7 +1067,8 @@ hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevExpert* sel_tab, const float* gate,
                           int32_t fixed_expert, int32_t accumulate, const uint16_t* h, const uint16_t* hp, int32_t T,
                           float* y, hipStream_t st) {
-  const Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), wgs_per_token(T), kBlock);
+  Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), wgs_per_token(T), kBlock);
+  sp.threads = phase2_threads(sp.threads);
   const PhaseLds pl = phase2_lds(L, fixed_expert >= 0 ? 1 : L.top_k, sp.rows_per_wg);
   static size_t granted = 0;
   if (hipError_t e = allow_lds(k_ffn_out, pl.bytes, granted); e != hipSuccess) return e;
@@ -1054,7 +1087,8 @@ hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const
   const int G = wgs_per_token(T);
   if (G < 8) return hipErrorNotSupported;
   const Split s1 = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), G, L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
-  const Split s2 = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), G, kBlock);
+  Split s2 = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), G, kBlock);
+  s2.threads = phase2_threads(s2.threads);
   const PhaseLds p1 = phase1_lds(L, L.top_k), p2 = phase2_lds(L, L.top_k, s2.rows_per_wg);
   const size_t lds = p1.bytes > p2.bytes ? p1.bytes : p2.bytes;
   if (lds > kLdsBudget) return hipErrorNotSupported;
