@@ -30,17 +30,20 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every layer from Python instead of a HIP graph")
     ap.add_argument("--layers", type=int, default=None, help="debug: truncate the stack")
+    ap.add_argument("--layout", default="columns", choices=["columns", "canonical"],
+                    help="W_out layout: columns = one streaming kernel per layer call (default), "
+                         "canonical = the two-kernel path on the boundary format")
     return ap.parse_args()
 
 
 class Stack:
     """All layers of one workload, packed in HBM, plus the hidden states of every (step, layer)."""
 
-    def __init__(self, cfg, batch, steps, dev, n_layers=None):
+    def __init__(self, cfg, batch, steps, dev, n_layers=None, columns=True):
         import torch
         import gen
         import paper_2308_14352_amd as moeq
-        self.cfg, self.batch, self.steps = cfg, batch, steps
+        self.cfg, self.batch, self.steps, self.columns = cfg, batch, steps, columns
         self.L = n_layers or cfg.n_layers
         self.layers, self.bits = [], []
         act = moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU
@@ -55,11 +58,13 @@ class Stack:
                 q_g = s_g = None
                 if cfg.swiglu:
                     q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], bits[e], cfg.group)
-                experts.append(moeq.PackedExpert(bits[e], q_in, s_in, q_out, s_out, q_g, s_g))
-                del w
+                ex = moeq.PackedExpert(bits[e], q_in, s_in, q_out, s_out, q_g, s_g)
+                experts.append(ex.with_out_columns(cfg.d_ff, cfg.group) if columns else ex)
+                del w, ex, q_out, s_out
             Wr, bias = gen.router_weights(cfg, l, dev)
             self.layers.append(moeq.Layer(cfg.d_model, cfg.d_ff, cfg.top_k, cfg.group, act, cfg.renorm, xdt, Wr,
-                                          bias, experts))
+                                          bias, experts,
+                                          moeq.MOEQ_OUT_COLUMNS if columns else moeq.MOEQ_OUT_CANONICAL))
             self.bits.append(bits)
         torch.cuda.synchronize()
         # hidden states of every (step, layer): [steps][L][batch][d]
@@ -167,8 +172,9 @@ class HipEvents:
 
 def dominant_kernel_events(stack, steps, idx):
     """Eager pass over `steps` steps with a HIP event pair recorded by the library around the
-    dominant kernel (k_ffn_in, phase 1: about two thirds of the bytes) of every layer call, on the
-    stream the kernel runs on. Returns (mean duration in ms, mean algorithmic bytes of that kernel)."""
+    dominant kernel of every layer call, on the stream the kernel runs on: k_moe_decode (the whole layer
+    but the final sum of partial vectors) with W_out in columns, else k_ffn_in (phase 1, about two thirds
+    of the bytes). Returns (mean duration in ms, mean algorithmic bytes of that kernel)."""
     import numpy as np
     import torch
     import paper_2308_14352_amd as moeq
@@ -182,15 +188,22 @@ def dominant_kernel_events(stack, steps, idx):
         stack.xs.copy_(stack.x_all[sd])
         for l in range(stack.L):
             a, b = evs.new(), evs.new()
-            binding.moe_profile_kernel(binding.MOEQ_KERNEL_FFN_IN, a.value, b.value)
+            binding.moe_profile_kernel(binding.MOEQ_KERNEL_FUSED if stack.columns else binding.MOEQ_KERNEL_FFN_IN,
+                                       a.value, b.value)
             moeq.moe_layer_forward(stack.layers[l], stack.xs[l], y=stack.y[l], ws=stack.ws)
             pairs.append((a, b))
-            tot = stack.batch * cfg.d_model * xb + stack.batch * cfg.top_k * cfg.d_ff * 2 \
-                + stack.batch * cfg.n_experts * 4
+            layer = stack.layers[l]
+            if stack.columns:       # router weights (+bias), x, every (token, choice) slot's whole expert
+                tot = stack.batch * cfg.d_model * xb + layer.router_w.numel() * 4 \
+                    + (0 if layer.router_bias is None else cfg.n_experts * 4)
+            else:                   # x, logits, the h vectors out
+                tot = stack.batch * cfg.d_model * xb + stack.batch * cfg.top_k * cfg.d_ff * 2 \
+                    + stack.batch * cfg.n_experts * 4
             for t in range(stack.batch):                 # the kernel streams every (token, choice) slot
                 for e in idx[sd, l, t]:
-                    ex = stack.layers[l].experts[int(e)]
-                    for tns in (ex.q_in, ex.s_in, ex.q_gate, ex.s_gate):
+                    ex = layer.experts[int(e)]
+                    tensors = (ex.q_in, ex.s_in, ex.q_gate, ex.s_gate) + ((ex.q_out, ex.s_out) if stack.columns else ())
+                    for tns in tensors:
                         if tns is not None:
                             tot += tns.numel() * tns.element_size()
             nbytes.append(tot)
@@ -243,12 +256,12 @@ WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8
 DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
 
 
-def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True):
+def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True, columns=True):
     import gen
     cfg_id, batch = WORKLOADS[name]
     cfg = gen.CONFIGS[cfg_id]
     n_distinct = min(steps, cfg.steps)
-    stack = Stack(cfg, batch, n_distinct, dev, n_layers)
+    stack = Stack(cfg, batch, n_distinct, dev, n_layers, columns)
     idx = stack.routing()
     bytes_sl = stack.algorithmic_bytes(idx)
     elapsed, _ = time_steps(stack, steps, warmup, use_graph)
@@ -294,7 +307,8 @@ def main():
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]
     use_graph = not args.no_graph
-    stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers)
+    columns = args.layout == "columns"
+    stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers, columns=columns)
     cfg = stack.cfg
     achieved = res["kernel_bytes"] / (res["kernel_ms"] * 1e-3) / 1e9
     out = {
@@ -305,11 +319,14 @@ def main():
         "config": {"workload": f"{name}: {cfg.name}", "layers": stack.L, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "act": cfg.act, "group": cfg.group,
                    "batch": stack.batch, "x_dtype": cfg.x_dtype, "bitwidths": cfg.bit_rule,
-                   "packed_GB": round(res["packed_GB"], 3), "launch": "hip-graph" if use_graph else "eager"},
+                   "packed_GB": round(res["packed_GB"], 3), "launch": "hip-graph" if use_graph else "eager",
+                   "w_out_layout": args.layout},
         "layer_tokens_per_s": res["layer_tokens_per_s"],
         "algorithmic_GBps": res["algorithmic_GBps"],
         "pct_hbm_peak": 100.0 * res["algorithmic_GBps"] / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "k_ffn_in (phase 1: top-k + dequantize-fused W_in/W_gate GEMVs)",
+        "roofline": {"bound": "hbm",
+                     "kernel": ("k_moe_decode (router + top-k + dequantize-fused FFN of every d_ff slice)" if columns
+                                else "k_ffn_in (phase 1: top-k + dequantize-fused W_in/W_gate GEMVs)"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": res["kernel_bytes"], "avg_launch_ms": res["kernel_ms"],
                      "traffic": None},
@@ -323,7 +340,7 @@ def main():
         for other, k in (("c1", 64), ("c2", 256), ("c3", 128), ("c3b8", 128)):
             if other == name:
                 continue
-            st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False)
+            st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False, columns=columns)
             extras[other] = {kk: r[kk] for kk in ("tokens_per_s", "layer_tokens_per_s", "ms_per_step",
                                                   "algorithmic_GBps", "layers", "batch", "steps", "packed_GB")
                              if kk in r}

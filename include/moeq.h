@@ -31,6 +31,12 @@
  *             u = q + 2^(b-1) (q in [-(2^(b-1)-1), 2^(b-1)-1]) at bits [i*b mod 8, +b) of byte
  *             floor(i*b/8). cols*b must be a multiple of 128 (16-byte rows).
  *     scales: rows * cols/g IEEE binary16 values, row-major. W^[o][i] = scale[o][i/g] * q[o][i].
+ *
+ * Dword-column-major layout of W_out (optional, made from the canonical one by moe_prepare_out)
+ *   The same bits, transposed in units of 32-bit words: codes[w][r] = word w (little-endian) of canonical
+ *   row r, for w < cols*b/32; scales[g][r] = canonical scale[r][g]. rows must be a multiple of 4. With
+ *   W_out in this layout a layer's decode calls run as one streaming kernel per call (each workgroup
+ *   takes a slice of d_ff through both FFN matrices) plus a small ordered reduction.
  */
 #ifndef MOEQ_H
 #define MOEQ_H
@@ -52,12 +58,14 @@ typedef enum {
 
 typedef enum { MOEQ_ACT_RELU = 0, MOEQ_ACT_SWIGLU = 1 } moeq_act;
 typedef enum { MOEQ_F32 = 0, MOEQ_BF16 = 1 } moeq_dtype;
+typedef enum { MOEQ_OUT_CANONICAL = 0, MOEQ_OUT_COLUMNS = 1 } moeq_out_layout;
 
 /* One expert's packed weights: dev pointers, read-only, in the canonical format.
  * ReLU   (Switch-style): h = relu(W_in x),            y = W_out h;   q_gate/s_gate = NULL
  * SwiGLU (Mixtral-style): h = silu(W_in x) * (W_gate x), y = W_out h
- * W_in, W_gate: [d_ff][d_model]; W_out: [d_model][d_ff]. `bits` is this expert's entry of the
- * per-expert bitwidth table (Section 3.2, "Selecting expert-wise bitwidths").               */
+ * W_in, W_gate: [d_ff][d_model]; W_out: [d_model][d_ff] (q_out/s_out in the layout the layer's
+ * out_layout names). `bits` is this expert's entry of the per-expert bitwidth table (Section 3.2,
+ * "Selecting expert-wise bitwidths").                                                        */
 typedef struct moeq_expert {
   int32_t bits; /* 2, 4 or 8 */
   const void *q_in, *s_in;
@@ -75,6 +83,7 @@ typedef struct moeq_layer_desc {
   const float *router_w;    /* dev [n_experts][d_model] fp32                                   */
   const float *router_bias; /* dev [n_experts] fp32 or NULL                                    */
   const moeq_expert *experts; /* host array [n_experts] of dev pointers                        */
+  int32_t out_layout;       /* moeq_out_layout of every expert's q_out / s_out                 */
 } moeq_layer_desc;
 
 typedef struct moeq_layer moeq_layer; /* opaque, host-side handle */
@@ -89,18 +98,12 @@ size_t moe_layer_table_bytes(int32_t n_experts);
  * pointer in `desc` must stay valid until moe_layer_destroy. Limits: d_model, d_ff multiples of
  * `group`; group a multiple of 32 (a multiple of 64 or exactly 32 for 2-bit experts);
  * d_model*bits and d_ff*bits multiples of 128 for every expert; 1 <= top_k <= min(8, n_experts);
- * n_experts <= 1024; d_model, d_ff <= 32768.
+ * n_experts <= 1024; d_model, d_ff <= 32768. With out_layout = MOEQ_OUT_COLUMNS also: group and d_ff
+ * multiples of 16, d_model <= 8192 (else MOEQ_EUNSUPPORTED).
  * Errors: MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EDEVICE (copy failed). */
 moeq_status moe_layer_create(const moeq_layer_desc *desc, void *table_dev, size_t table_bytes,
                              moeq_layer **out);
 void moe_layer_destroy(moeq_layer *layer);
-
-/* Synchronous check of the layer's device-side state, for use when no call on the layer is in
- * flight. The one-launch decode path coordinates its workgroups through a few words behind the
- * expert table; they are zero between calls. *error_out = 1 if they are not (a bounded wait inside a
- * kernel gave up, e.g. because calls on this layer overlapped): the outputs of the calls since the
- * last check are then invalid, and the words are cleared so that the layer can be used again. */
-moeq_status moe_layer_health(const moeq_layer *layer, int32_t *error_out);
 
 /* Workspace bytes needed by any compute call on `layer` with up to max_tokens tokens. */
 size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);
@@ -151,13 +154,23 @@ moeq_status moe_unpack_codes(const void *q, int64_t rows, int64_t cols, int32_t 
 moeq_status moe_dequantize(const void *q, const void *s, int64_t rows, int64_t cols, int32_t bits,
                            int32_t group, float *w_out, void *stream);
 
-/* Measurement aid. While `which` is MOEQ_KERNEL_FFN_IN or MOEQ_KERNEL_FFN_OUT, every moe_layer_forward
+/* W_out of one expert, canonical -> dword-column-major (see the top of this file) and back: device to
+ * device, out of place (source and destination must not overlap). rows = d_model (a multiple of 4), cols =
+ * d_ff; q buffers are rows*cols*bits/8 bytes (16-byte aligned), s buffers rows*cols/group binary16 values.
+ * Both are pure permutations: moe_unprepare_out(moe_prepare_out(q, s)) returns q and s bit for bit. */
+moeq_status moe_prepare_out(const void *q, const void *s, int64_t rows, int64_t cols, int32_t bits,
+                            int32_t group, void *q_cols, void *s_cols, void *stream);
+moeq_status moe_unprepare_out(const void *q_cols, const void *s_cols, int64_t rows, int64_t cols,
+                              int32_t bits, int32_t group, void *q, void *s, void *stream);
+
+/* Measurement aid. While `which` names a kernel, every moe_layer_forward
  * call records start_event just before and stop_event just after that kernel on the call's stream
  * (hipEvent_t handles created by the caller with timing enabled), so a benchmark can time the
  * dominant kernel alone. which = 0 turns it off. Process-wide, not thread-safe; do not use under
  * stream capture. */
 #define MOEQ_KERNEL_FFN_IN 1  /* phase 1: top-k + W_in / W_gate GEMVs (Section 3.2, dequantize-fused) */
 #define MOEQ_KERNEL_FFN_OUT 2 /* phase 2: W_out GEMVs + gate-weighted combine                          */
+#define MOEQ_KERNEL_FUSED 3   /* the one-kernel path: router, top-k and both phases of every d_ff slice */
 moeq_status moe_profile_kernel(int32_t which, void *start_event, void *stop_event);
 
 const char *moe_status_str(moeq_status st);

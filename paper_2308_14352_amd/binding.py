@@ -15,6 +15,7 @@ LIB_PATH = os.environ.get("MOEQ_LIB") or os.path.join(_HERE, "libmoeq.so")
 MOEQ_OK, MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EWORKSPACE, MOEQ_EDEVICE = range(5)
 MOEQ_ACT_RELU, MOEQ_ACT_SWIGLU = 0, 1
 MOEQ_F32, MOEQ_BF16 = 0, 1
+MOEQ_OUT_CANONICAL, MOEQ_OUT_COLUMNS = 0, 1
 
 
 class MoeqError(RuntimeError):
@@ -35,7 +36,7 @@ class moeq_layer_desc(C.Structure):
                 ("top_k", C.c_int32), ("group", C.c_int32), ("act", C.c_int32),
                 ("renorm", C.c_int32), ("x_dtype", C.c_int32),
                 ("router_w", C.c_void_p), ("router_bias", C.c_void_p),
-                ("experts", C.POINTER(moeq_expert))]
+                ("experts", C.POINTER(moeq_expert)), ("out_layout", C.c_int32)]
 
 
 _lib = None
@@ -61,8 +62,6 @@ def lib():
     L.moe_layer_create.argtypes = [C.POINTER(moeq_layer_desc), vp, sz, C.POINTER(vp)]
     L.moe_layer_destroy.restype = None
     L.moe_layer_destroy.argtypes = [vp]
-    L.moe_layer_health.restype = C.c_int
-    L.moe_layer_health.argtypes = [vp, C.POINTER(C.c_int32)]
     L.moe_profile_kernel.restype = C.c_int
     L.moe_profile_kernel.argtypes = [i32, vp, vp]
     L.moe_workspace_bytes.restype = sz
@@ -79,13 +78,17 @@ def lib():
     L.moe_unpack_codes.argtypes = [vp, i64, i64, i32, vp, vp]
     L.moe_dequantize.restype = C.c_int
     L.moe_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp]
+    for fn in (L.moe_prepare_out, L.moe_unprepare_out):
+        fn.restype = C.c_int
+        fn.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp]
     _lib = L
     return L
 
 
 EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
-           "moe_layer_destroy", "moe_layer_health", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
-           "moe_layer_forward", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize"]
+           "moe_layer_destroy", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
+           "moe_layer_forward", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
+           "moe_unprepare_out"]
 
 
 def status_str(st):
@@ -107,11 +110,11 @@ def _stream(stream):
     return C.c_void_p(stream.cuda_stream)
 
 
-MOEQ_KERNEL_FFN_IN, MOEQ_KERNEL_FFN_OUT = 1, 2
+MOEQ_KERNEL_FFN_IN, MOEQ_KERNEL_FFN_OUT, MOEQ_KERNEL_FUSED = 1, 2, 3
 
 
 def moe_profile_kernel(which, start_event=None, stop_event=None):
-    """which: 0 (off), MOEQ_KERNEL_FFN_IN or MOEQ_KERNEL_FFN_OUT; events are raw hipEvent_t handles (ints)."""
+    """which: 0 (off) or one of the MOEQ_KERNEL_* ids; events are raw hipEvent_t handles (ints)."""
     _check(lib().moe_profile_kernel(int(which), C.c_void_p(start_event), C.c_void_p(stop_event)), "moe_profile_kernel")
 
 
@@ -155,13 +158,40 @@ def moe_dequantize(q, s, cols, bits, group, stream=None):
     return out
 
 
+def moe_prepare_out(q, s, cols, bits, group, stream=None):
+    """Canonical W_out (codes [rows][cols*bits/8], scales [rows][cols/group]) -> dword-column-major copies
+    (codes uint8 [cols*bits/32][rows*4], scales [cols/group][rows])."""
+    rows = q.shape[0]
+    qc = torch.empty((cols * bits // 32, rows * 4), dtype=torch.uint8, device=q.device)
+    sc = torch.empty((cols // group, rows), dtype=torch.float16, device=q.device)
+    _check(lib().moe_prepare_out(_ptr(q), _ptr(s), rows, cols, bits, group, _ptr(qc), _ptr(sc), _stream(stream)),
+           "moe_prepare_out")
+    return qc, sc
+
+
+def moe_unprepare_out(qc, sc, cols, bits, group, stream=None):
+    """Inverse of moe_prepare_out."""
+    rows = sc.shape[1]
+    q = torch.empty((rows, cols * bits // 8), dtype=torch.uint8, device=qc.device)
+    s = torch.empty((rows, cols // group), dtype=torch.float16, device=qc.device)
+    _check(lib().moe_unprepare_out(_ptr(qc), _ptr(sc), rows, cols, bits, group, _ptr(q), _ptr(s), _stream(stream)),
+           "moe_unprepare_out")
+    return q, s
+
+
 class PackedExpert:
-    """Device tensors of one expert in the boundary format (keeps them alive)."""
+    """Device tensors of one expert in the boundary format (keeps them alive). q_out/s_out are in the
+    layout the owning Layer is created with."""
 
     def __init__(self, bits, q_in, s_in, q_out, s_out, q_gate=None, s_gate=None):
         self.bits = int(bits)
         self.q_in, self.s_in, self.q_out, self.s_out = q_in, s_in, q_out, s_out
         self.q_gate, self.s_gate = q_gate, s_gate
+
+    def with_out_columns(self, d_ff, group):
+        """A copy of this expert (canonical W_out) whose W_out is in the dword-column-major layout."""
+        qc, sc = moe_prepare_out(self.q_out, self.s_out, d_ff, self.bits, group)
+        return PackedExpert(self.bits, self.q_in, self.s_in, qc, sc, self.q_gate, self.s_gate)
 
     def nbytes(self):
         ts = [self.q_in, self.s_in, self.q_out, self.s_out, self.q_gate, self.s_gate]
@@ -175,7 +205,9 @@ class PackedExpert:
 class Layer:
     """Owner of a moeq_layer handle and of the device tensors it borrows."""
 
-    def __init__(self, d_model, d_ff, top_k, group, act, renorm, x_dtype, router_w, router_bias, experts):
+    def __init__(self, d_model, d_ff, top_k, group, act, renorm, x_dtype, router_w, router_bias, experts,
+                 out_layout=MOEQ_OUT_CANONICAL):
+        self.out_layout = out_layout
         self.d_model, self.d_ff, self.top_k, self.group = d_model, d_ff, top_k, group
         self.n_experts = len(experts)
         self.experts = list(experts)
@@ -185,7 +217,7 @@ class Layer:
         self._table = torch.empty(max(moe_layer_table_bytes(self.n_experts), 16), dtype=torch.uint8, device=dev)
         arr = (moeq_expert * self.n_experts)(*[e.c_struct() for e in self.experts])
         desc = moeq_layer_desc(d_model, d_ff, self.n_experts, top_k, group, act, int(bool(renorm)), x_dtype,
-                               _ptr(router_w), _ptr(router_bias), arr)
+                               _ptr(router_w), _ptr(router_bias), arr, out_layout)
         h = C.c_void_p()
         _check(lib().moe_layer_create(C.byref(desc), _ptr(self._table), self._table.numel(), C.byref(h)),
                "moe_layer_create")
@@ -201,12 +233,6 @@ class Layer:
     @property
     def handle(self):
         return self._h
-
-    def health(self):
-        """0 if the layer's device-side barrier words are clean, 1 if a call on it went wrong (then cleared)."""
-        out = C.c_int32(0)
-        _check(lib().moe_layer_health(self._h, C.byref(out)), "moe_layer_health")
-        return int(out.value)
 
     def workspace_bytes(self, max_tokens):
         return int(lib().moe_workspace_bytes(self._h, max_tokens))

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoeq.so")
-SOURCES = ["api.cpp", "router.hip", "ffn_decode.hip", "quant.hip"]
+SOURCES = ["api.cpp", "router.hip", "ffn_decode.hip", "decode_fused.hip", "quant.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed-fp32 instructions are kept off on this target (see the design notes)
@@ -24,7 +24,8 @@ def stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "moeq_internal.h"), os.path.join(ROOT, "include", "moeq.h")]
+    deps = sources() + [os.path.join(CSRC, "moeq_internal.h"), os.path.join(CSRC, "decode_core.h"),
+                        os.path.join(ROOT, "include", "moeq.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -14,8 +14,9 @@ struct moeq_layer {
   const float* router_w;
   const float* router_bias;
   const DevExpert* table;          // device
-  uint32_t* barrier;               // device: barrier words of the one-launch path, behind the table
   std::vector<int32_t> bits;       // host copy of the bitwidth table
+  int32_t out_layout;              // layout of W_out (MOEQ_OUT_CANONICAL or MOEQ_OUT_COLUMNS)
+  FusedPlan plan;                  // split of the one-kernel path (out_layout == MOEQ_OUT_COLUMNS)
 };
 
 namespace {
@@ -30,23 +31,37 @@ inline bool group_ok(int32_t g, int32_t bits) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Workspace carving. Both paths keep idx, gate and logits; the two-kernel path adds the chosen experts'
+// records and the two copies of h, the one-kernel path the partial output vectors.
 struct WsLayout {
-  size_t idx_off, gate_off, logits_off, part_off, sel_off, h_off, hp_off, total;
+  size_t idx_off, gate_off, logits_off, sel_off, h_off, hp_off, part_off, total;
 };
 
-WsLayout ws_layout(const LayerDims& L, int64_t T) {
-  WsLayout w;
+WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
+  const LayerDims& L = layer->dims;
+  WsLayout w{};
   const size_t slots = (size_t)T * L.top_k;
   w.idx_off = 0;
   w.gate_off = align_up(slots * sizeof(int32_t), 256);
   w.logits_off = w.gate_off + align_up(slots * sizeof(float), 256);
-  w.part_off = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
-  const size_t part_tokens = (size_t)(T < kFusedMaxTokens ? T : kFusedMaxTokens);
-  w.sel_off = w.part_off + align_up(part_tokens * kFusedMaxSlices * (size_t)L.n_experts * sizeof(float), 256);
-  w.h_off = w.sel_off + align_up(slots * sizeof(DevExpert), 256);
-  w.hp_off = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
-  w.total = w.hp_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
+  const size_t tail = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
+  if (layer->out_layout == MOEQ_OUT_COLUMNS) {
+    w.part_off = tail;
+    w.total = w.part_off + align_up((size_t)T * (size_t)layer->plan.n_slices * (size_t)L.d_model * sizeof(float), 256);
+  } else {
+    w.sel_off = tail;
+    w.h_off = w.sel_off + align_up(slots * sizeof(DevExpert), 256);
+    w.hp_off = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
+    w.total = w.hp_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
+  }
   return w;
+}
+
+// Routers with at most this many experts are evaluated inside the one-kernel path by every workgroup;
+// larger ones by the router kernel first (MOEQ_INLINE_ROUTER overrides, for experiments).
+int inline_router_max() {
+  static const int v = [] { const char* e = std::getenv("MOEQ_INLINE_ROUTER"); return e ? std::atoi(e) : 16; }();
+  return v;
 }
 
 inline moeq_status dev(hipError_t e) { return e == hipSuccess ? MOEQ_OK : MOEQ_EDEVICE; }
@@ -79,7 +94,7 @@ const char* moe_status_str(moeq_status st) {
 }
 
 size_t moe_layer_table_bytes(int32_t n_experts) {
-  return n_experts > 0 ? (size_t)n_experts * sizeof(DevExpert) + kBarrierBytes : 0;
+  return n_experts > 0 ? (size_t)n_experts * sizeof(DevExpert) : 0;
 }
 
 size_t moe_packed_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group, size_t* scale_bytes_opt) {
@@ -98,10 +113,17 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   if (k > E) return MOEQ_EINVAL;
   if (desc->act != MOEQ_ACT_RELU && desc->act != MOEQ_ACT_SWIGLU) return MOEQ_EINVAL;
   if (desc->x_dtype != MOEQ_F32 && desc->x_dtype != MOEQ_BF16) return MOEQ_EINVAL;
+  if (desc->out_layout != MOEQ_OUT_CANONICAL && desc->out_layout != MOEQ_OUT_COLUMNS) return MOEQ_EINVAL;
   if (d % g || f % g) return MOEQ_EINVAL;
   if (((uintptr_t)table_dev & 15u) || table_bytes < moe_layer_table_bytes(E)) return MOEQ_EINVAL;
   if (k > 8 || E > 1024 || d > 32768 || f > 32768 || d % 8 || f % 8) return MOEQ_EUNSUPPORTED;
-  std::vector<DevExpert> tab((size_t)E + kBarrierBytes / sizeof(DevExpert));  // trailing zeros: barrier words
+  const LayerDims dims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0};
+  FusedPlan plan{0, 0, 0};
+  if (desc->out_layout == MOEQ_OUT_COLUMNS) {
+    plan = plan_fused(dims);
+    if (!plan.SW) return MOEQ_EUNSUPPORTED;
+  }
+  std::vector<DevExpert> tab((size_t)E);
   std::memset(tab.data(), 0, tab.size() * sizeof(DevExpert));
   std::vector<int32_t> bits((size_t)E);
   for (int32_t e = 0; e < E; ++e) {
@@ -124,12 +146,13 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   }
   moeq_layer* L = new (std::nothrow) moeq_layer();
   if (!L) return MOEQ_EDEVICE;
-  L->dims = LayerDims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0};
+  L->dims = dims;
   L->router_w = desc->router_w;
   L->router_bias = desc->router_bias;
   L->table = (const DevExpert*)table_dev;
-  L->barrier = (uint32_t*)((char*)table_dev + (size_t)E * sizeof(DevExpert));
   L->bits = std::move(bits);
+  L->out_layout = desc->out_layout;
+  L->plan = plan;
   if (hipMemcpy(table_dev, tab.data(), tab.size() * sizeof(DevExpert), hipMemcpyHostToDevice) != hipSuccess) {
     delete L;
     return MOEQ_EDEVICE;
@@ -140,20 +163,9 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
 
 void moe_layer_destroy(moeq_layer* layer) { delete layer; }
 
-moeq_status moe_layer_health(const moeq_layer* layer, int32_t* error_out) {
-  if (!layer || !error_out) return MOEQ_EINVAL;
-  uint32_t words[kBarrierBytes / 4];
-  if (hipMemcpy(words, layer->barrier, kBarrierBytes, hipMemcpyDeviceToHost) != hipSuccess) return MOEQ_EDEVICE;
-  int32_t bad = 0;
-  for (size_t i = 0; i < kBarrierBytes / 4; ++i) bad |= (words[i] != 0u);
-  *error_out = bad;
-  if (bad && hipMemset(layer->barrier, 0, kBarrierBytes) != hipSuccess) return MOEQ_EDEVICE;
-  return MOEQ_OK;
-}
-
 size_t moe_workspace_bytes(const moeq_layer* layer, int32_t max_tokens) {
   if (!layer || max_tokens <= 0) return 0;
-  return ws_layout(layer->dims, max_tokens).total;
+  return ws_layout(layer, max_tokens).total;
 }
 
 moeq_status moe_router_topk(const moeq_layer* layer, const void* x, int32_t n_tokens, int32_t* topk_idx,
@@ -162,7 +174,7 @@ moeq_status moe_router_topk(const moeq_layer* layer, const void* x, int32_t n_to
   if (n_tokens == 0) return MOEQ_OK;
   if (!x || !topk_idx || !topk_gate || ((uintptr_t)x & 15u)) return MOEQ_EINVAL;
   if (n_tokens > 65535) return MOEQ_EUNSUPPORTED;
-  const WsLayout w = ws_layout(layer->dims, n_tokens);
+  const WsLayout w = ws_layout(layer, n_tokens);
   if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
   float* logits = (float*)((char*)ws + w.logits_off);
@@ -180,12 +192,20 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   if (n_tokens == 0) return MOEQ_OK;
   if (!x || !y || ((uintptr_t)x & 15u) || ((uintptr_t)y & 3u)) return MOEQ_EINVAL;
   if (n_tokens > 65535) return MOEQ_EUNSUPPORTED;
-  const WsLayout w = ws_layout(layer->dims, n_tokens);
+  const WsLayout w = ws_layout(layer, n_tokens);
   if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  if (layer->out_layout == MOEQ_OUT_COLUMNS) {
+    float* part = (float*)((char*)ws + w.part_off);
+    if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert, gate_opt, x,
+                          n_tokens, part, nullptr, nullptr, st) != hipSuccess)
+      return MOEQ_EDEVICE;
+    return dev(launch_reduce_partials(part, layer->plan.n_slices, layer->dims.d_model, n_tokens, accumulate ? 1 : 0,
+                                      y, st));
+  }
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
-  hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, nullptr, nullptr, nullptr, expert, x, n_tokens, h,
                                hp, st);
   if (e != hipSuccess) return MOEQ_EDEVICE;
@@ -201,26 +221,33 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   if (!x || !y || ((uintptr_t)x & 15u) || ((uintptr_t)y & 3u)) return MOEQ_EINVAL;
   if ((int64_t)n_tokens * layer->dims.top_k > 65535) return MOEQ_EUNSUPPORTED;
   const LayerDims& L = layer->dims;
-  const WsLayout w = ws_layout(L, n_tokens);
+  const WsLayout w = ws_layout(layer, n_tokens);
   if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
   int32_t* idx = topk_idx_opt ? topk_idx_opt : (int32_t*)((char*)ws + w.idx_off);
   float* gate = topk_gate_opt ? topk_gate_opt : (float*)((char*)ws + w.gate_off);
+  hipStream_t st = (hipStream_t)stream;
+  float* logits = (float*)((char*)ws + w.logits_off);
+  if (layer->out_layout == MOEQ_OUT_COLUMNS) {
+    // one streaming kernel for the whole layer, then the ordered sum of its partial output vectors
+    const float* lg = nullptr;
+    if (L.n_experts > inline_router_max()) {
+      if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
+        return MOEQ_EDEVICE;
+      lg = logits;
+    }
+    float* part = (float*)((char*)ws + w.part_off);
+    {
+      ScopedEvents ev(MOEQ_KERNEL_FUSED, st);
+      if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias, lg, -1, nullptr, x,
+                            n_tokens, part, idx, gate, st) != hipSuccess)
+        return MOEQ_EDEVICE;
+    }
+    return dev(launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n_tokens, 0, y, st));
+  }
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
   DevExpert* sel_tab = (DevExpert*)((char*)ws + w.sel_off);
-  hipStream_t st = (hipStream_t)stream;
-  float* logits = (float*)((char*)ws + w.logits_off);
-  // Experimental: the whole layer of a few tokens in one launch with grid barriers. Measured slower than
-  // the three-kernel path on MI355X (a barrier across the 8 XCDs costs more than a kernel boundary), so it
-  // only runs when MOEQ_ONE_LAUNCH=1 is set in the environment.
-  static const bool one_launch = [] { const char* v = std::getenv("MOEQ_ONE_LAUNCH"); return v && v[0] == '1'; }();
-  if (one_launch) {
-    const hipError_t fused = launch_layer_decode(L, layer->table, layer->router_w, layer->router_bias, x, n_tokens, y,
-                                                 idx, gate, (float*)((char*)ws + w.part_off), h, hp, layer->barrier, st);
-    if (fused == hipSuccess) return MOEQ_OK;
-    if (fused != hipErrorNotSupported) return MOEQ_EDEVICE;
-  }
   if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
   {
@@ -233,7 +260,7 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
 }
 
 moeq_status moe_profile_kernel(int32_t which, void* start_event, void* stop_event) {
-  if (which != 0 && which != MOEQ_KERNEL_FFN_IN && which != MOEQ_KERNEL_FFN_OUT) return MOEQ_EINVAL;
+  if (which < 0 || which > MOEQ_KERNEL_FUSED) return MOEQ_EINVAL;
   if (which != 0 && (!start_event || !stop_event)) return MOEQ_EINVAL;
   g_profile = ProfileHook{which, (hipEvent_t)start_event, (hipEvent_t)stop_event};
   return MOEQ_OK;
@@ -248,6 +275,34 @@ moeq_status moe_quantize_pack(const float* w, int64_t rows, int64_t cols, int32_
   if (rows * (cols / group) > (int64_t)1 << 40) return MOEQ_EUNSUPPORTED;
   return dev(launch_quantize_pack(w, rows, cols, bits, group, (uint8_t*)q_out, (uint16_t*)s_out,
                                   (hipStream_t)stream));
+}
+
+// Canonical <-> dword-column-major: a transposition of the 32-bit words of the code rows and of the scales.
+static moeq_status relayout_out(const void* q_src, const void* s_src, int64_t rows, int64_t cols, int32_t bits,
+                                int32_t group, void* q_dst, void* s_dst, bool to_columns, void* stream) {
+  if (!q_src || !s_src || !q_dst || !s_dst || rows <= 0 || cols <= 0) return MOEQ_EINVAL;
+  if (!bits_ok(bits) || group <= 0 || cols % group || (cols * bits) % 32 || rows % 4) return MOEQ_EINVAL;
+  if (q_src == q_dst || s_src == s_dst) return MOEQ_EINVAL;
+  if (((uintptr_t)q_src | (uintptr_t)q_dst) & 15u) return MOEQ_EINVAL;
+  if (((uintptr_t)s_src | (uintptr_t)s_dst) & 1u) return MOEQ_EINVAL;
+  const int64_t words = cols * bits / 32, groups = cols / group;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = to_columns ? launch_transpose(q_src, rows, words, 4, q_dst, st)
+                            : launch_transpose(q_src, words, rows, 4, q_dst, st);
+  if (e != hipSuccess) return MOEQ_EDEVICE;
+  e = to_columns ? launch_transpose(s_src, rows, groups, 2, s_dst, st)
+                 : launch_transpose(s_src, groups, rows, 2, s_dst, st);
+  return dev(e);
+}
+
+moeq_status moe_prepare_out(const void* q, const void* s, int64_t rows, int64_t cols, int32_t bits, int32_t group,
+                            void* q_cols, void* s_cols, void* stream) {
+  return relayout_out(q, s, rows, cols, bits, group, q_cols, s_cols, true, stream);
+}
+
+moeq_status moe_unprepare_out(const void* q_cols, const void* s_cols, int64_t rows, int64_t cols, int32_t bits,
+                              int32_t group, void* q, void* s, void* stream) {
+  return relayout_out(q_cols, s_cols, rows, cols, bits, group, q, s, false, stream);
 }
 
 moeq_status moe_unpack_codes(const void* q, int64_t rows, int64_t cols, int32_t bits, int8_t* codes_out,

@@ -20,13 +20,6 @@ struct alignas(64) DevExpert {
 };
 static_assert(sizeof(DevExpert) == 64, "expert table entry is 64 bytes");
 
-// One-launch decode path: at most this many tokens per call, and this many column slices of the router
-// GEMV; the barrier words (4 per token + 1 error word) sit behind the expert table in device memory.
-constexpr int kFusedMaxTokens = 16;
-constexpr int kFusedMaxSlices = 32;
-constexpr size_t kBarrierBytes = 512;
-static_assert((4 * kFusedMaxTokens + 1) * 4 <= kBarrierBytes, "barrier words fit");
-
 struct LayerDims {
   int32_t d_model, d_ff, n_experts, top_k, group, act, renorm, x_bf16;
 };
@@ -54,13 +47,24 @@ hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevE
                           const float* gate, int32_t fixed_expert, int32_t accumulate,
                           const uint16_t* h, const uint16_t* hp, int32_t T, float* y, hipStream_t st);
 
-// The whole layer in one launch (router partials, grid barrier, top-k, phase 1, grid barrier, phase 2).
-// part: [T][kFusedMaxSlices][E] fp32 scratch; bar: the layer's barrier words. Returns
-// hipErrorNotSupported without launching when the shape does not fit the scheme.
-hipError_t launch_layer_decode(const LayerDims& L, const DevExpert* table, const float* router_w,
-                               const float* router_bias, const void* x, int32_t T, float* y,
-                               int32_t* idx_out, float* gate_out, float* part, uint16_t* h,
-                               uint16_t* hp, uint32_t* bar, hipStream_t st);
+// ---- one-kernel decode path (W_out in the dword-column-major layout) -------------------------------
+// Split of a layer for the fused kernel: slices of SW columns of d_ff, one workgroup of `threads` per
+// (slice, token). SW == 0: the shape does not fit the scheme.
+struct FusedPlan { int32_t SW, n_slices, threads; };
+FusedPlan plan_fused(const LayerDims& L);
+
+// Router (inline when logits == nullptr) + top-k + both FFN phases of every (slice, token); writes the
+// partial outputs part[T][n_slices][d]. fixed_expert >= 0: that expert for every token, gate_in[T] or 1.
+hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const DevExpert* table,
+                             const float* router_w, const float* router_bias, const float* logits,
+                             int32_t fixed_expert, const float* gate_in, const void* x, int32_t T,
+                             float* part, int32_t* idx_out, float* gate_out, hipStream_t st);
+// y[t] (+)= sum_s part[t][s], fixed order.
+hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_t T, int accumulate,
+                                  float* y, hipStream_t st);
+// out[c][r] = in[r][c], elements of 2 or 4 bytes.
+hipError_t launch_transpose(const void* in, int64_t rows, int64_t cols, int elem_bytes, void* out,
+                            hipStream_t st);
 
 hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
                                 uint8_t* q, uint16_t* s, hipStream_t st);

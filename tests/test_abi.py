@@ -66,7 +66,7 @@ def test_packed_bytes(rows, cols, bits, group, expect):
 def _desc(**kw):
     ex = (B.moeq_expert * 2)(B.moeq_expert(4, 16, 16, None, None, 16, 16), B.moeq_expert(4, 16, 16, None, None, 16, 16))
     d = dict(d_model=64, d_ff=128, n_experts=2, top_k=1, group=32, act=0, renorm=0, x_dtype=0,
-             router_w=16, router_bias=None, experts=ex)
+             router_w=16, router_bias=None, experts=ex, out_layout=0)
     d.update(kw)
     return B.moeq_layer_desc(**d), ex
 
@@ -78,6 +78,9 @@ def _desc(**kw):
     (dict(act=7), B.MOEQ_EINVAL),
     (dict(x_dtype=5), B.MOEQ_EINVAL),
     (dict(router_w=None), B.MOEQ_EINVAL),
+    (dict(out_layout=2), B.MOEQ_EINVAL),
+    (dict(out_layout=1, d_model=64, d_ff=136, group=8), B.MOEQ_EUNSUPPORTED),   # d_ff is not a multiple of 16
+    (dict(out_layout=1, d_model=16384, d_ff=16384, group=32), B.MOEQ_EUNSUPPORTED),  # beyond the one-kernel path
     (dict(group=16, d_model=64, d_ff=128), B.MOEQ_EUNSUPPORTED),
 ])
 def test_layer_create_rejects_bad_descriptions_before_any_device_call(kw, status):
@@ -115,4 +118,10 @@ def test_compute_entry_points_reject_null_handles_and_shapes():
     assert L.moe_unpack_codes(C.c_void_p(256), 1, 64, 3, C.c_void_p(256), None) == B.MOEQ_EINVAL
     assert L.moe_dequantize(C.c_void_p(256), C.c_void_p(256), 1, 64, 4, 48, C.c_void_p(256), None) == B.MOEQ_EINVAL
     assert L.moe_workspace_bytes(None, 4) == 0
-    assert B.moe_layer_table_bytes(8) == 8 * 64 + 512 and B.moe_layer_table_bytes(0) == 0
+    assert B.moe_layer_table_bytes(8) == 8 * 64 and B.moe_layer_table_bytes(0) == 0
+    p = C.c_void_p(256)
+    q = C.c_void_p(4096)
+    assert L.moe_prepare_out(None, p, 4, 64, 4, 32, q, q, None) == B.MOEQ_EINVAL
+    assert L.moe_prepare_out(p, p, 6, 64, 4, 32, q, q, None) == B.MOEQ_EINVAL        # rows not a multiple of 4
+    assert L.moe_prepare_out(p, p, 4, 64, 4, 32, p, q, None) == B.MOEQ_EINVAL        # in place
+    assert L.moe_unprepare_out(p, p, 4, 64, 3, 32, q, q, None) == B.MOEQ_EINVAL

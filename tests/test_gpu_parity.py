@@ -65,6 +65,22 @@ def test_quantize_pack_ties_and_bump_cases_bit_exact():
         assert np.array_equal(s16(s), s_ref) and np.array_equal(q.cpu().numpy(), q_ref)
 
 
+@pytest.mark.parametrize("bits", (2, 4, 8))
+@pytest.mark.parametrize("rows,cols,group", [(8, 64, 32), (36, 320, 64), (768, 3072, 32), (4096, 14336, 128)])
+def test_prepare_out_is_the_word_transposition_and_round_trips(bits, rows, cols, group):
+    """The dword-column-major layout against its definition, built with numpy from the ORACLE's packed bytes."""
+    w = gen.normal((rows, cols), 0.02, gen.seed_for("prep", bits, rows, cols), DEV)
+    q, s = moeq.moe_quantize_pack(w, bits, group)
+    qc, sc = moeq.moe_prepare_out(q, s, cols, bits, group)
+    q2, s2 = moeq.moe_unprepare_out(qc, sc, cols, bits, group)
+    torch.cuda.synchronize()
+    q_ref, s_ref = oracle.quantize_pack(w.cpu().numpy(), bits, group)
+    words = np.ascontiguousarray(q_ref).view("<u4")                     # [rows][cols*bits/32]
+    assert np.array_equal(qc.cpu().numpy().view("<u4"), words.T)
+    assert np.array_equal(s16(sc), s_ref.T)
+    assert torch.equal(q2, q) and torch.equal(s2.view(torch.int16), s.view(torch.int16))
+
+
 # ------------------------------------------------------------------ router
 @pytest.mark.parametrize("cfg_id,T", [("c1", 64), ("c2", 33), ("c3", 8), ("c4", 5), ("c5", 257)])
 def test_router_topk_matches_oracle(cfg_id, T):
@@ -119,7 +135,8 @@ def test_router_exact_ties_go_to_lowest_index():
     ("c4", 512, 1792, 128, 2),     # SwiGLU, Mixtral-like 7 * 2^k row length
     ("c4", 4096, 14336, 128, 1),   # Mixtral expert, full size
 ])
-def test_expert_ffn_q_matches_oracle(bits, base, d, f, g, T):
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_expert_ffn_q_matches_oracle(bits, base, d, f, g, T, columns):
     if bits == 2 and (d % 64 or f % 64):
         pytest.skip("2-bit rows must be whole 16-byte chunks")
     cfg = gen.tiny_config(base, d, f, n_experts=2, group=g)
@@ -127,9 +144,12 @@ def test_expert_ffn_q_matches_oracle(bits, base, d, f, g, T):
     ex_gpu = pack_expert_gpu(w, bits, g)
     ex_orc = pack_expert_oracle(w, bits, g)
     del w
+    if columns:
+        ex_gpu = ex_gpu.with_out_columns(f, g)
     Wr, _ = gen.router_weights(cfg, 0, DEV)
     layer = moeq.Layer(d, f, cfg.top_k, g, moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU, cfg.renorm,
-                       moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32, Wr, None, [ex_gpu, ex_gpu])
+                       moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32, Wr, None, [ex_gpu, ex_gpu],
+                       moeq.MOEQ_OUT_COLUMNS if columns else moeq.MOEQ_OUT_CANONICAL)
     x = gen.hidden(cfg, 0, 0, T, DEV)
     y_ref = oracle.expert_ffn(ex_orc, d, f, g, int(cfg.swiglu), x.float().cpu().numpy())
     y = moeq.moe_expert_ffn_q(layer, 1, x)
@@ -149,9 +169,10 @@ def test_expert_ffn_q_matches_oracle(bits, base, d, f, g, T):
     ("c1", 256, 512, 8, 5), ("c2", 384, 768, 16, 4), ("c3", 512, 1024, 32, 8), ("c4", 512, 1792, 8, 3),
     ("c5", 512, 1024, 8, 40),
 ])
-def test_layer_forward_small(base, d, f, E, T):
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_layer_forward_small(base, d, f, E, T, columns):
     cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1)
-    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns)
     x = gen.hidden(cfg, 0, 0, T, DEV)
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
     torch.cuda.synchronize()
@@ -168,7 +189,6 @@ def test_layer_forward_small(base, d, f, E, T):
     assert torch.equal(y, y_b)
     # zero tokens: a no-op
     moeq.moe_layer_forward(layer, x[:0])
-    assert layer.health() == 0
 
 
 def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
@@ -182,11 +202,12 @@ def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
 
 
 @pytest.mark.parametrize("cfg_id,layer_id,T", [("c1", 0, 8), ("c2", 3, 6), ("c3", 7, 8), ("c4", 5, 2)])
-def test_layer_forward_full_size(cfg_id, layer_id, T):
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_layer_forward_full_size(cfg_id, layer_id, T, columns):
     """One layer of each decode configuration at its real shape; the oracle runs the activated experts."""
     cfg = gen.CONFIGS[cfg_id]
     bits_table = gen.bitwidth_table(cfg, layer_id)
-    layer, _, Wr, bias = build_layer_pair(cfg, layer_id, DEV, bits_table, want_oracle=False)
+    layer, _, Wr, bias = build_layer_pair(cfg, layer_id, DEV, bits_table, want_oracle=False, columns=columns)
     x = gen.hidden(cfg, layer_id, 0, T, DEV)
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
     torch.cuda.synchronize()
@@ -201,14 +222,14 @@ def test_layer_forward_full_size(cfg_id, layer_id, T):
     assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
     # the library's packed copy of one activated expert equals the oracle's, bit for bit
     e = int(idx_ref[0, 0])
-    assert np.array_equal(layer.experts[e].q_in.cpu().numpy(), experts[e].q_in)
-    assert np.array_equal(s16(layer.experts[e].s_out), experts[e].s_out)
-    assert layer.health() == 0
+    assert np.array_equal(layer.canonical[e].q_in.cpu().numpy(), experts[e].q_in)
+    assert np.array_equal(s16(layer.canonical[e].s_out), experts[e].s_out)
 
 
-def test_layer_forward_batch8_switch_large_and_workspace_errors():
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_layer_forward_batch8_switch_large_and_workspace_errors(columns):
     cfg = gen.tiny_config("c3", 1024, 4096, n_experts=16, n_layers=1)
-    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns)
     x = gen.hidden(cfg, 0, 1, 8, DEV)
     y = moeq.moe_layer_forward(layer, x)
     torch.cuda.synchronize()
