@@ -15,6 +15,7 @@ struct moeq_layer {
   const float* router_bias;
   const DevExpert* table;          // device
   std::vector<int32_t> bits;       // host copy of the bitwidth table
+  int32_t bits_mask;               // or of the bitwidths in the table (2 | 4 | 8)
   int32_t out_layout;              // layout of W_out (MOEQ_OUT_CANONICAL or MOEQ_OUT_COLUMNS)
   FusedPlan plan;                  // split of the one-kernel path (out_layout == MOEQ_OUT_COLUMNS)
 };
@@ -60,7 +61,11 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
 // Routers with at most this many experts are evaluated inside the one-kernel path by every workgroup;
 // larger ones by the router kernel first (MOEQ_INLINE_ROUTER overrides, for experiments).
 int inline_router_max() {
-  static const int v = [] { const char* e = std::getenv("MOEQ_INLINE_ROUTER"); return e ? std::atoi(e) : 16; }();
+  static const int v = [] {
+    const char* e = std::getenv("MOEQ_INLINE_ROUTER");
+    const int want = e ? std::atoi(e) : 16, cap = fused_inline_router_max();
+    return want < cap ? want : cap;
+  }();
   return v;
 }
 
@@ -150,6 +155,8 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   L->router_w = desc->router_w;
   L->router_bias = desc->router_bias;
   L->table = (const DevExpert*)table_dev;
+  L->bits_mask = 0;
+  for (int32_t b : bits) L->bits_mask |= b;
   L->bits = std::move(bits);
   L->out_layout = desc->out_layout;
   L->plan = plan;
@@ -198,8 +205,8 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   hipStream_t st = (hipStream_t)stream;
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     float* part = (float*)((char*)ws + w.part_off);
-    if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert, gate_opt, x,
-                          n_tokens, part, nullptr, nullptr, st) != hipSuccess)
+    if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert, gate_opt,
+                          layer->bits[(size_t)expert], x, n_tokens, part, nullptr, nullptr, st) != hipSuccess)
       return MOEQ_EDEVICE;
     return dev(launch_reduce_partials(part, layer->plan.n_slices, layer->dims.d_model, n_tokens, accumulate ? 1 : 0,
                                       y, st));
@@ -239,8 +246,8 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
     float* part = (float*)((char*)ws + w.part_off);
     {
       ScopedEvents ev(MOEQ_KERNEL_FUSED, st);
-      if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias, lg, -1, nullptr, x,
-                            n_tokens, part, idx, gate, st) != hipSuccess)
+      if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias, lg, -1, nullptr,
+                            layer->bits_mask, x, n_tokens, part, idx, gate, st) != hipSuccess)
         return MOEQ_EDEVICE;
     }
     return dev(launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n_tokens, 0, y, st));

@@ -32,11 +32,23 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
+// Loads through pointers that are known to point to device memory. A pointer that was itself read from
+// memory (an expert record) has no address space the compiler can see; without the cast it would emit
+// FLAT loads, which count on the LDS counter as well, so that every wait for an LDS read would also wait
+// for all weight loads in flight.
+#define MOEQ_GLOBAL __attribute__((address_space(1)))
 // 16-byte load with the non-temporal hint: packed weights are read once per call and should not
 // displace the activations and scales that are reused from the caches.
 __device__ __forceinline__ uint4 load_stream16(const uint8_t* ptr) {
-  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)ptr);
+  const u32x4_t v = __builtin_nontemporal_load((const MOEQ_GLOBAL u32x4_t*)ptr);
   return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t gload_u16(const uint8_t* ptr) { return *(const MOEQ_GLOBAL uint16_t*)ptr; }
+__device__ __forceinline__ uint32_t gload_u32(const uint8_t* ptr) { return *(const MOEQ_GLOBAL uint32_t*)ptr; }
+__device__ __forceinline__ uint2 gload_u32x2(const uint8_t* ptr) {
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+  const u32x2_t v = *(const MOEQ_GLOBAL u32x2_t*)ptr;
+  return make_uint2(v.x, v.y);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -338,8 +350,8 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
       const int m = v / NRM;
       t[u0 + v].w = load_stream16(q[m] + (qoff[v] + (uint32_t)(jb + pj) * jstride));
       const uint8_t* sb = (const uint8_t*)s[m];
-      if (TWO) t[u0 + v].s = *(const uint32_t*)(sb + (soff[v] + g0));
-      else t[u0 + v].s = *(const uint16_t*)(sb + (soff[v] + g0));
+      if (TWO) t[u0 + v].s = gload_u32(sb + (soff[v] + g0));
+      else t[u0 + v].s = gload_u16(sb + (soff[v] + g0));
     }
     if (++pj == J) { pj = 0; ++pk; }
   };

@@ -23,9 +23,11 @@
 namespace moeq {
 namespace {
 
-constexpr int kRbMax = 2;          // output row blocks (of 4 rows) per thread in phase 2
-constexpr int kP2Unroll = 8;       // 128-bit loads in flight per thread in phase 2
-constexpr int kInlineMaxE = 1024;  // size of the in-kernel logits buffer
+constexpr int kRbMax = 4;          // output row blocks (of 4 rows) per thread in phase 2
+constexpr int kBurst = 8;          // 128-bit loads a thread issues back to back before it consumes them
+constexpr int kInlineMaxE = 64;    // the router is evaluated in the kernel for at most this many experts
+constexpr int kMaxSegs = 8;        // router work units per expert: d_model <= 2048 * kMaxSegs on the one-kernel path
+constexpr int kTabLds = 64;        // expert records kept in LDS when the layer has at most this many experts
 
 // Position (in binary16 units) of column `col` of a slice in the pair layout phase 2 reads, and the
 // power of two its activation is pre-divided by. Word w of a row holds CPD = 32/b codes; its PPD = CPD/2
@@ -60,25 +62,159 @@ struct FusedParams {
   int32_t* idx_out;       // [T][k] or null
   float* gate_out;        // [T][k] or null
   int32_t SW;             // slice width (columns of d_ff): a multiple of 16 that divides the group size
+  int32_t bits_mask;      // bitwidths present among the experts this call can pick (bit 1: INT2, 2: INT4, 3: INT8)
 };
 
-// Phase 1 of one expert on the rows [row_begin, row_end) of W_in (and W_gate): h values go to LDS as
-// binary16, once linear (HL) and once in the pair layout of this expert's bitwidth (HP).
+// Layout slot of a bitwidth: its rank among the bitwidths present in the layer.
+__device__ __forceinline__ int layout_slot(int bits_mask, int bits) {
+  const int bit = bits == 2 ? 1 : bits == 4 ? 2 : 3;
+  return __popc((unsigned)bits_mask & ((1u << bit) - 1u));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Phase 1 of one expert: the rows [row_begin, row_begin + n_rows) of W_in (and W_gate) against the
+// staged activations. P lanes share a row (RW = 64/P rows per wavefront load), J = chunks per lane
+// and row. The tiles (one 128-bit load per lane, plus its scale) of a wavefront are grouped in bursts
+// of RGB row groups x JC chunk steps x NM matrices (four tiles); a wavefront walks the bursts of its
+// row-group sets (J/JC bursts per set) with two register sets: the loads of
+// burst b+1 are issued before the arithmetic of burst b, so 4 to 8 loads per lane are always in flight.
+template <int BITS, int NM, int JC, int RGB>
+struct P1Burst {
+  uint4 t[RGB][JC][NM];
+  uint32_t sc[RGB][JC][NM];
+};
+
+template <int BITS, int NM, int JC, int RGB, typename Epilogue>
+__device__ __forceinline__ void p1_stream(const uint8_t* const (&q)[NM], const uint8_t* const (&s)[NM], int d,
+                                          int group, int row_begin, int n_rows, int P, int J, int lane, int wave,
+                                          int nwaves, const uint32_t* XP, const float* XK, Epilogue epilogue) {
+  constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
+  using Burst = P1Burst<BITS, NM, JC, RGB>;
+  const int C = d / WPC;
+  const int RW = 64 / P;
+  const int n_rg = (n_rows + RW - 1) / RW;
+  const int n_sets = (n_rg + RGB - 1) / RGB;
+  const int JB = J / JC;                                                     // bursts per row-group set
+  // Wavefront w owns the contiguous run of sets [w*spw, (w+1)*spw) and starts at a position that depends
+  // on the workgroup: at any moment the loads of a workgroup are spread over its whole block of rows, and
+  // those of different workgroups over different parts of theirs, which keeps all memory channels busy
+  // (workgroups walking their blocks in lockstep would otherwise hit the same few channels together).
+  const int spw = (n_sets + nwaves - 1) / nwaves;
+  const int set_begin = wave * spw;
+  const int my_sets = max(0, min(spw, n_sets - set_begin));
+  const int rot = my_sets > 0 ? (int)blockIdx.x % my_sets : 0;
+  const int nb = my_sets * JB;
+  const int p = lane & (P - 1), rsub = lane / P;
+  const uint32_t row_bytes = (uint32_t)C * 16u;
+  const uint32_t ng2 = (uint32_t)(d / group) * 2u;
+  const bool two = (BITS == 2) && (group == 32);
+  const uint4* XP4 = (const uint4*)XP;
+
+  auto issue = [&](Burst& B, int b) __attribute__((always_inline)) {
+    const int si = b / JB, j0 = (b - si * JB) * JC;
+    const int sr = si + rot < my_sets ? si + rot : si + rot - my_sets;
+    const int rg0 = (set_begin + sr) * RGB;
+#pragma unroll
+    for (int i = 0; i < RGB; ++i) {
+      // rows past the slice are clamped: computed and dropped
+      const uint32_t row = (uint32_t)(row_begin + min((rg0 + i) * RW + rsub, n_rows - 1));
+      const uint32_t qoff = row * row_bytes + (uint32_t)p * 16u;
+      const uint32_t soff = row * ng2;
+#pragma unroll
+      for (int jj = 0; jj < JC; ++jj) {
+        const uint32_t c = (uint32_t)(p + (j0 + jj) * P);
+        const uint32_t g0 = (c * (uint32_t)WPC / (uint32_t)group) * 2u;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          B.t[i][jj][m] = load_stream16(q[m] + (qoff + (uint32_t)(j0 + jj) * (uint32_t)P * 16u));
+          if (two) B.sc[i][jj][m] = gload_u32(s[m] + (soff + g0));
+          else B.sc[i][jj][m] = gload_u16(s[m] + (soff + g0));
+        }
+      }
+    }
+  };
+
+  float tot[NM * RGB];
+  auto compute = [&](const Burst& B, int b) __attribute__((always_inline)) {
+    const int si = b / JB, j0 = (b - si * JB) * JC;
+    const int sr = si + rot < my_sets ? si + rot : si + rot - my_sets;
+    const int rg0 = (set_begin + sr) * RGB;
+    if (j0 == 0) {
+#pragma unroll
+      for (int v = 0; v < NM * RGB; ++v) tot[v] = 0.f;
+    }
+    // Per chunk step, the two halves of the chunk one after the other, so that only half of the chunk's
+    // activation pairs are in registers at a time. The offset term enters as the start value of the
+    // dot-product chain; the factor 2^24 of the subnormal trick is applied once per row.
+#pragma unroll
+    for (int jj = 0; jj < JC; ++jj) {
+      const int c = p + (j0 + jj) * P;
+      float k0, k1 = 0.f;
+      if (two) { k0 = XK[2 * c]; k1 = XK[2 * c + 1]; }
+      else k0 = XK[c];
+      float a[RGB][NM];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        uint32_t xr[PPC / 2];
+#pragma unroll
+        for (int qq = 0; qq < PPC / 8; ++qq) {
+          const uint4 t4 = XP4[(h * (PPC / 8) + qq) * C + c];
+          xr[4 * qq] = t4.x; xr[4 * qq + 1] = t4.y; xr[4 * qq + 2] = t4.z; xr[4 * qq + 3] = t4.w;
+        }
+#pragma unroll
+        for (int i = 0; i < RGB; ++i)
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
+            const uint4 w = B.t[i][jj][m];
+            const float start = h == 0 ? -k0 : (two ? -k1 : a[i][m]);
+            float v = dword_dot<BITS>(h ? w.z : w.x, &xr[0], start);
+            v = dword_dot<BITS>(h ? w.w : w.y, &xr[PPC / 4], v);
+            a[i][m] = v;
+            if (two) {
+              const uint32_t sraw = B.sc[i][jj][m];
+              tot[m * RGB + i] = fmaf(f16_bits_to_f32(h ? (sraw >> 16) : (sraw & 0xffffu)), v, tot[m * RGB + i]);
+            }
+          }
+      }
+      if (!two) {
+#pragma unroll
+        for (int i = 0; i < RGB; ++i)
+#pragma unroll
+          for (int m = 0; m < NM; ++m)
+            tot[m * RGB + i] = fmaf(f16_bits_to_f32(B.sc[i][jj][m]), a[i][m], tot[m * RGB + i]);
+      }
+    }
+    if (j0 + JC == J) {
+      fold_rows<RGB, NM>(tot, P, lane);
+      if (p < RGB && (rg0 + p) * RW + rsub < n_rows) {
+        float r[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m) r[m] = tot[m * RGB] * 16777216.0f;
+        epilogue(row_begin + (rg0 + p) * RW + rsub, r);
+      }
+    }
+  };
+
+  Burst A, Bb;
+  if (nb > 0) issue(A, 0);
+  for (int b = 0; b < nb; b += 2) {
+    if (b + 1 < nb) issue(Bb, b + 1);
+    compute(A, b);
+    if (b + 2 < nb) issue(A, b + 2);
+    if (b + 1 < nb) compute(Bb, b + 1);
+  }
+}
+
+// Phase 1 of one expert on the SW rows of its slice: h values go to LDS as binary16, once linear (HL)
+// and once in the pair layout of this expert's bitwidth (HP).
 template <int BITS, bool SWIGLU>
-__device__ __forceinline__ void fused_in_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
-                                               int row_begin, int row_end, uint16_t* HL, uint16_t* HP,
-                                               const uint32_t* XP, const float* XK) {
+__device__ __forceinline__ void fused_in(const DevExpert* ex, int tid, int nwaves, int d, int group, int row_begin,
+                                         int SW, uint16_t* HL, uint16_t* HP, const uint32_t* XP, const float* XK) {
   constexpr int NM = SWIGLU ? 2 : 1;
   const int C = d / Fmt<BITS>::WPC;
-  const int P = lanes_per_row(C), RW = 64 / P;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int nrm = pick_nrm(row_end - row_begin, RW, nwaves, P, kBlock / NM);
-  const bool two = (BITS == 2) && (group == 32);
-  const uint8_t* q_in = uniform_ptr(ex.q_in);
-  const uint16_t* s_in = uniform_ptr(ex.s_in);
-  const uint8_t* q_gate = SWIGLU ? uniform_ptr(ex.q_gate) : nullptr;
-  const uint16_t* s_gate = SWIGLU ? uniform_ptr(ex.s_gate) : nullptr;
-  auto epi = [&](int row, const float (&r)[NM], int) {
+  const int P = lanes_per_row(C), J = C / P;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  auto epi = [&](int row, const float (&r)[NM]) __attribute__((always_inline)) {
     float v;
     if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
     else v = fmaxf(r[0], 0.f);
@@ -89,211 +225,307 @@ __device__ __forceinline__ void fused_in_tasks(const DevExpert& ex, int tid, int
     const int si = slice_pair_index<BITS>(c, ps);
     HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
   };
-  auto no_stage = []() {};
-  auto run = [&](auto nrm_tag, auto two_tag) {
-    constexpr int NRM = decltype(nrm_tag)::value;
-    constexpr bool TWO = decltype(two_tag)::value;
+  const uint8_t* q0 = uniform_ptr(ex->q_in);
+  const uint8_t* s0 = (const uint8_t*)uniform_ptr(ex->s_in);
+  const uint8_t* q1 = SWIGLU ? uniform_ptr(ex->q_gate) : nullptr;
+  const uint8_t* s1 = SWIGLU ? (const uint8_t*)uniform_ptr(ex->s_gate) : nullptr;
+  auto run = [&](auto jc_tag, auto rgb_tag) __attribute__((always_inline)) {
+    constexpr int JC = decltype(jc_tag)::value, RGB = decltype(rgb_tag)::value;
     if constexpr (SWIGLU) {
-      const uint8_t* const qq[2] = {q_in, q_gate};
-      const uint16_t* const ss[2] = {s_in, s_gate};
-      gemv_stream<BITS, NRM, 2, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, 1, XP, XK, epi, no_stage);
+      const uint8_t* const qq[2] = {q0, q1};
+      const uint8_t* const ss[2] = {s0, s1};
+      p1_stream<BITS, 2, JC, RGB>(qq, ss, d, group, row_begin, SW, P, J, lane, wave, nwaves, XP, XK, epi);
     } else {
-      const uint8_t* const qq[1] = {q_in};
-      const uint16_t* const ss[1] = {s_in};
-      gemv_stream<BITS, NRM, 1, TWO>(qq, ss, d, group, f, row_begin, row_end, lane, wave, nwaves, 1, XP, XK, epi, no_stage);
+      const uint8_t* const qq[1] = {q0};
+      const uint8_t* const ss[1] = {s0};
+      p1_stream<BITS, 1, JC, RGB>(qq, ss, d, group, row_begin, SW, P, J, lane, wave, nwaves, XP, XK, epi);
     }
   };
-  using T_ = std::true_type;
-  using F_ = std::false_type;
-  if constexpr (BITS == 2) {
-    if (two) {
-      if (!SWIGLU && nrm == 4) run(std::integral_constant<int, SWIGLU ? 2 : 4>{}, T_{});
-      else if (nrm >= 2) run(std::integral_constant<int, 2>{}, T_{});
-      else run(std::integral_constant<int, 1>{}, T_{});
-      return;
-    }
+  // A burst is four tiles: two chunk steps when a row has an even number of them, and as many row groups
+  // as that leaves room for - one only when the fold could not take more (it needs RGB <= P).
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I4 = std::integral_constant<int, 4>;
+  constexpr int RGB1 = 4 / NM, RGB2 = 2 / NM;   // row groups per burst at JC = 1 and JC = 2
+  if (J % 2 == 0) {
+    if constexpr (RGB2 > 1) { if (P >= RGB2) { run(I2{}, std::integral_constant<int, RGB2>{}); return; } }
+    run(I2{}, I1{});
+  } else {
+    if (P >= RGB1) { run(I1{}, std::integral_constant<int, RGB1>{}); return; }
+    run(I1{}, I1{});
   }
-  if (!SWIGLU && nrm == 4) run(std::integral_constant<int, SWIGLU ? 2 : 4>{}, F_{});
-  else if (nrm >= 2) run(std::integral_constant<int, 2>{}, F_{});
-  else run(std::integral_constant<int, 1>{}, F_{});
 }
 
-// Phase 2 of one expert: yacc[i][r] += gate * s[row][grp] * sum_{col in slice} (u - 2^(b-1)) * h[col] for the
-// thread's row blocks. qT/sT are the dword-column-major codes and scales of W_out.
-template <int BITS>
-__device__ __forceinline__ void fused_out(const DevExpert& ex, int tid, int nthreads, int d, int group, int slice,
-                                          int SW, float gate, const uint16_t* HL, const uint16_t* HP,
-                                          float (&yacc)[kRbMax][4]) {
+// ---------------------------------------------------------------------------------------------
+// Phase 2 of one expert: Y[row] (+)= gate * s[row][grp] * sum_{col in slice} (u - 2^(b-1)) * h[col] for the
+// thread's row blocks rb = tid + i*nthreads (4 rows each). qT/sT are the dword-column-major codes and
+// scales of W_out; Y is the workgroup's partial output vector in LDS (every row block has one owner, so
+// no synchronisation is needed on it). A burst is RBC row blocks x DWC words; the first burst's loads
+// are issued by p2_issue before the barrier that completes h, the rest inside fused_out.
+template <int BITS, int DWC>
+struct P2Burst {
+  static constexpr int RBC = (kBurst / DWC) < kRbMax ? (kBurst / DWC) : kRbMax;
+  uint4 t[RBC][DWC];
+  uint2 sc[RBC];
+};
+
+// qT_w: the codes at word column w_first (uniform); a tile is at qT_w + w * d*4 + rb*16.
+template <int BITS, int DWC>
+__device__ __forceinline__ void p2_issue(P2Burst<BITS, DWC>& b, const uint8_t* qT_w, const uint8_t* sT_g, int d,
+                                         int nrb, int tid, int nthreads, int i0, bool want_scales) {
+  constexpr int RBC = P2Burst<BITS, DWC>::RBC;
+#pragma unroll
+  for (int i = 0; i < RBC; ++i) {
+    const int rb = tid + (i0 + i) * nthreads;
+    if (rb < nrb) {
+      if (want_scales) b.sc[i] = gload_u32x2(sT_g + (uint32_t)rb * 8u);
+#pragma unroll
+      for (int w = 0; w < DWC; ++w)
+        b.t[i][w] = load_stream16(qT_w + (size_t)w * ((size_t)d * 4) + (uint32_t)rb * 16u);
+    }
+  }
+}
+
+template <int BITS, int DWC>
+__device__ __forceinline__ void fused_out(P2Burst<BITS, DWC>& first, const uint8_t* qT_s, const uint8_t* sT_g,
+                                          int tid, int nthreads, int d, int SW, float gate, bool first_expert,
+                                          const uint16_t* HL, const uint16_t* HP, float4* Y) {
   constexpr int CPD = 32 / BITS, PPD = CPD / 2;
+  constexpr int RBC = P2Burst<BITS, DWC>::RBC;
   const int lane = tid & 63;
-  const int DW = SW / CPD;
-  const int w0 = slice * DW;
-  const int grp = (slice * SW) / group;
+  const int DW = SW / CPD;              // a multiple of DWC
   // offset term: 2^(b-1) * 2^-24 * (sum of the slice's activations), the same in every wavefront
   float hs = 0.f;
   for (int c = lane; c < SW; c += 64) hs += f16_bits_to_f32(HL[c]);
   hs = wave_sum(hs);
   const float K = hs * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
-  const uint8_t* qT = uniform_ptr(ex.q_out);
-  const uint8_t* sT = (const uint8_t*)uniform_ptr(ex.s_out);
+  const float g24 = gate * 16777216.0f;
   const uint32_t* HPw = (const uint32_t*)HP;
   const int nrb = d / 4;
+  const int RB = (nrb + nthreads - 1) / nthreads;
+  auto consume = [&](const P2Burst<BITS, DWC>& cur, int wb, float (&acc)[RBC][4]) __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < kRbMax; ++i) {
-    const int rb = tid + i * nthreads;
-    if (rb < nrb) {
-      const uint2 sraw = *(const uint2*)(sT + ((size_t)grp * d + 4 * (size_t)rb) * 2);
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
-      for (int wb = 0; wb < DW; wb += kP2Unroll) {
-        uint4 t[kP2Unroll];
+    for (int w = 0; w < DWC; ++w) {
+      __builtin_amdgcn_sched_barrier(0);   // one word column at a time: bounds the live pair registers
+      uint32_t xr[PPD];
 #pragma unroll
-        for (int u = 0; u < kP2Unroll; ++u)
-          if (wb + u < DW) t[u] = load_stream16(qT + ((size_t)(w0 + wb + u) * d + 4 * (size_t)rb) * 4);
+      for (int pp = 0; pp < PPD; ++pp) xr[pp] = HPw[(wb + w) * PPD + pp];
 #pragma unroll
-        for (int u = 0; u < kP2Unroll; ++u)
-          if (wb + u < DW) {
-            uint32_t xr[PPD];
-#pragma unroll
-            for (int p = 0; p < PPD; ++p) xr[p] = HPw[(wb + u) * PPD + p];
-            acc[0] = dword_dot<BITS>(t[u].x, xr, acc[0]);
-            acc[1] = dword_dot<BITS>(t[u].y, xr, acc[1]);
-            acc[2] = dword_dot<BITS>(t[u].z, xr, acc[2]);
-            acc[3] = dword_dot<BITS>(t[u].w, xr, acc[3]);
-          }
+      for (int i = 0; i < RBC; ++i) {
+        acc[i][0] = dword_dot<BITS>(cur.t[i][w].x, xr, acc[i][0]);
+        acc[i][1] = dword_dot<BITS>(cur.t[i][w].y, xr, acc[i][1]);
+        acc[i][2] = dword_dot<BITS>(cur.t[i][w].z, xr, acc[i][2]);
+        acc[i][3] = dword_dot<BITS>(cur.t[i][w].w, xr, acc[i][3]);
       }
-      const float g24 = gate * 16777216.0f;
-      yacc[i][0] = fmaf(f16_bits_to_f32(sraw.x & 0xffffu) * g24, acc[0] - K, yacc[i][0]);
-      yacc[i][1] = fmaf(f16_bits_to_f32(sraw.x >> 16) * g24, acc[1] - K, yacc[i][1]);
-      yacc[i][2] = fmaf(f16_bits_to_f32(sraw.y & 0xffffu) * g24, acc[2] - K, yacc[i][2]);
-      yacc[i][3] = fmaf(f16_bits_to_f32(sraw.y >> 16) * g24, acc[3] - K, yacc[i][3]);
+    }
+  };
+#pragma unroll
+  for (int i0 = 0; i0 < kRbMax; i0 += RBC) {
+    if (i0 < RB) {
+      float acc[RBC][4];
+#pragma unroll
+      for (int i = 0; i < RBC; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
+      uint2 sc[RBC];
+      // first burst of this row-block set: the one issued before the barrier, or a fresh one
+      {
+        P2Burst<BITS, DWC> cur;
+        if (i0 != 0) p2_issue<BITS, DWC>(cur, qT_s, sT_g, d, nrb, tid, nthreads, i0, true);
+        const P2Burst<BITS, DWC>& use = (i0 == 0) ? first : cur;
+#pragma unroll
+        for (int i = 0; i < RBC; ++i) sc[i] = use.sc[i];
+        consume(use, 0, acc);
+      }
+      for (int wb = DWC; wb < DW; wb += DWC) {
+        P2Burst<BITS, DWC> cur;
+        p2_issue<BITS, DWC>(cur, qT_s + (size_t)wb * ((size_t)d * 4), sT_g, d, nrb, tid, nthreads, i0, false);
+        consume(cur, wb, acc);
+      }
+#pragma unroll
+      for (int i = 0; i < RBC; ++i) {
+        const int rb = tid + (i0 + i) * nthreads;
+        if (rb < nrb) {
+          float4 y = first_expert ? make_float4(0.f, 0.f, 0.f, 0.f) : Y[rb];
+          y.x = fmaf(f16_bits_to_f32(sc[i].x & 0xffffu) * g24, acc[i][0] - K, y.x);
+          y.y = fmaf(f16_bits_to_f32(sc[i].x >> 16) * g24, acc[i][1] - K, y.y);
+          y.z = fmaf(f16_bits_to_f32(sc[i].y & 0xffffu) * g24, acc[i][2] - K, y.z);
+          y.w = fmaf(f16_bits_to_f32(sc[i].y >> 16) * g24, acc[i][3] - K, y.w);
+          Y[rb] = y;
+        }
+      }
     }
   }
 }
 
-template <bool BF16>
+// Phase 2 of one expert of one (slice, token). The first expert's call holds the one barrier between the
+// phases; its first burst does not depend on h and is in flight across that barrier.
+template <int BITS, int DWC>
+__device__ __forceinline__ void fused_expert_out(const DevExpert* ex, int tid, int nthreads, int d, int group,
+                                                 int slice, int SW, float gate, bool first_expert,
+                                                 const uint16_t* HL, const uint16_t* HP, float4* Y) {
+  // first_expert: the call that also waits for phase 1 (of every expert) to be complete
+  constexpr int CPD = 32 / BITS;
+  // this slice's first word column of the codes, and its scale group, as uniform pointers
+  const uint8_t* qT_s = uniform_ptr(ex->q_out) + (size_t)(slice * (SW / CPD)) * ((size_t)d * 4);
+  const uint8_t* sT_g = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)((slice * SW) / group) * ((size_t)d * 2);
+  P2Burst<BITS, DWC> first;
+  p2_issue<BITS, DWC>(first, qT_s, sT_g, d, d / 4, tid, nthreads, 0, true);
+  if (first_expert) __syncthreads();  // the h slices of all chosen experts are complete in LDS
+  fused_out<BITS, DWC>(first, qT_s, sT_g, tid, nthreads, d, SW, gate, first_expert, HL, HP, Y);
+}
+
+template <bool SWIGLU>
 __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
-  __shared__ DevExpert sel_x[8];
-  __shared__ float lg[kInlineMaxE];
+  __shared__ float rpart[kInlineMaxE * (kMaxSegs + 1)];   // router partial sums, unit u = e * n_seg + seg
+  __shared__ DevExpert tab[kTabLds];
   const LayerDims& L = P.L;
-  const int d = L.d_model, f = L.d_ff, E = L.n_experts, SW = P.SW;
+  const int d = L.d_model, E = L.n_experts, SW = P.SW;
   const int slice = blockIdx.x, token = blockIdx.y;
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int k = P.fixed_expert >= 0 ? 1 : L.top_k;
   const int lay_words = d / 2 + d / 16;
+  const bool bf16 = L.x_bf16 != 0;
   uint16_t* RAW = (uint16_t*)smem;                 // [d] activations, linear binary16
   uint16_t* HLs = RAW + d;                         // [k][SW] h of every chosen expert, linear binary16
   uint16_t* HPs = HLs + k * SW;                    // [k][SW] the same in the pair layout of the expert's bitwidth
-  uint32_t* LAY = (uint32_t*)(HPs + k * SW);       // [<= 3][lay_words] staged activations, one per distinct bitwidth
-  const size_t xbytes = BF16 ? 2 : 4;
-  const char* xt = (const char*)P.x + (size_t)token * d * xbytes;
+  float4* Y = (float4*)(HPs + k * SW);             // [d/4] this workgroup's partial output vector
+  uint32_t* LAY = (uint32_t*)(Y + d / 4);          // [#bitwidths][lay_words] staged activations
+  const char* xt = (const char*)P.x + (size_t)token * d * (bf16 ? 2 : 4);
+  const bool routed = P.fixed_expert < 0;
+  const bool inline_router = routed && !P.logits;
+  const bool tab_in_lds = routed && E <= kTabLds;
 
-  copy_x_to_lds(xt, BF16 ? X_BF16 : X_F32, d, threadIdx.x, nthreads, RAW);
-  if (P.fixed_expert < 0) {
-    const float* lgp;
-    if (P.logits) {
-      lgp = P.logits + (size_t)token * E;
-    } else {
-      // router: wavefront w scores the experts w, w + nwaves, ... in fp32 on the unrounded activations
-      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-      for (int e = wave; e < E; e += nwaves) {
-        const float* wr = P.Wr + (size_t)e * d;
-        float acc = 0.f;
-        for (int i = lane * 4; i < d; i += 256) {
-          const float4 w = *(const float4*)(wr + i);
-          float4 v;
-          if (BF16) {
+  // ---- everything that depends on nothing but the inputs is requested at once: the activations, the
+  // expert records, the router rows
+  copy_x_to_lds(xt, bf16 ? X_BF16 : X_F32, d, threadIdx.x, nthreads, RAW);
+  if (tab_in_lds && (int)threadIdx.x < E * 4) ((uint4*)tab)[threadIdx.x] = ((const uint4*)P.table)[threadIdx.x];
+  // router work unit = (expert, segment of seg_cols columns), one wavefront each; segments are sized so
+  // that the units about fill the wavefronts, at most eight 128-bit loads of the router row per lane
+  int n_seg = (d + 2047) / 2048;
+  if (inline_router) {
+    while (n_seg * 2 <= kMaxSegs && E * n_seg * 2 <= nwaves && d >= n_seg * 2 * 256) n_seg *= 2;
+    const int seg_cols = ((d + n_seg - 1) / n_seg + 255) / 256 * 256;
+    for (int u = wave; u < E * n_seg; u += nwaves) {
+      const int e = u / n_seg, seg = u - e * n_seg;
+      const float* wr = P.Wr + (size_t)e * d;
+      const int c_end = min(d, (seg + 1) * seg_cols);
+      float4 w[8], v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int i = seg * seg_cols + q * 256 + lane * 4;
+        w[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        v[q] = w[q];
+        if (i < c_end) {
+          w[q] = *(const float4*)(wr + i);
+          if (bf16) {
             const uint2 b = *(const uint2*)((const uint16_t*)xt + i);
-            v = make_float4(bf16_bits_to_f32(b.x & 0xffffu), bf16_bits_to_f32(b.x >> 16),
-                            bf16_bits_to_f32(b.y & 0xffffu), bf16_bits_to_f32(b.y >> 16));
+            v[q] = make_float4(bf16_bits_to_f32(b.x & 0xffffu), bf16_bits_to_f32(b.x >> 16),
+                               bf16_bits_to_f32(b.y & 0xffffu), bf16_bits_to_f32(b.y >> 16));
           } else {
-            v = *(const float4*)((const float*)xt + i);
+            v[q] = *(const float4*)((const float*)xt + i);
           }
-          acc = fmaf(w.x, v.x, acc); acc = fmaf(w.y, v.y, acc); acc = fmaf(w.z, v.z, acc); acc = fmaf(w.w, v.w, acc);
         }
-        acc = wave_sum(acc);
-        if (lane == 0) lg[e] = acc + (P.bias ? P.bias[e] : 0.f);
       }
-      __syncthreads();
-      lgp = lg;
+      float acc = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        acc = fmaf(w[q].x, v[q].x, acc); acc = fmaf(w[q].y, v[q].y, acc);
+        acc = fmaf(w[q].z, v[q].z, acc); acc = fmaf(w[q].w, v[q].w, acc);
+      }
+      acc = wave_sum(acc);
+      if (lane == 0) rpart[u] = acc;
     }
-    if (threadIdx.x < 64) topk_from_logits(lgp, E, k, L.renorm, threadIdx.x, sel_e, sel_g, nullptr);
-    __syncthreads();
-    if (threadIdx.x < k * 4) {
-      const int j = threadIdx.x >> 2, part = threadIdx.x & 3;
-      ((uint4*)&sel_x[j])[part] = ((const uint4*)&P.table[sel_e[j]])[part];
-    }
-    if (slice == 0 && threadIdx.x < k) {
-      if (P.idx_out) P.idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
-      if (P.gate_out) P.gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
+  }
+  __syncthreads();  // RAW, tab, rpart are complete
+
+  // ---- wavefront 0 turns the router sums into the top-k while the others stage the activations for
+  // every bitwidth the layer holds (the staging does not depend on the routing)
+  if (wave == 0) {
+    if (routed) {
+      if (inline_router) {
+        float* lg = rpart + E * n_seg;            // the logits go behind the partial sums
+        if (lane < E) {
+          float t = 0.f;
+          for (int sg = 0; sg < n_seg; ++sg) t += rpart[lane * n_seg + sg];
+          lg[lane] = t + (P.bias ? P.bias[lane] : 0.f);
+        }
+        topk_from_logits(lg, E, k, L.renorm, lane, sel_e, sel_g, nullptr);   // same wavefront wrote lg
+      } else {
+        topk_from_logits(P.logits + (size_t)token * E, E, k, L.renorm, lane, sel_e, sel_g, nullptr);
+      }
+    } else if (lane == 0) {
+      sel_e[0] = P.fixed_expert;
+      sel_g[0] = P.gate_in ? P.gate_in[token] : 1.0f;
     }
   } else {
-    if (threadIdx.x < 4) ((uint4*)&sel_x[0])[threadIdx.x] = ((const uint4*)&P.table[P.fixed_expert])[threadIdx.x];
-    if (threadIdx.x == 0) sel_g[0] = P.gate_in ? P.gate_in[token] : 1.0f;
-  }
-  __syncthreads();  // RAW, sel_x, sel_g are complete
-
-  // one staged activation layout per distinct bitwidth among the chosen experts, in first-use order
-  uint32_t lay_of = 0;  // 2 bits per slot: the layout its expert reads
-  {
-    int n_lay = 0;
-    for (int j = 0; j < k; ++j) {
-      const int bits = sel_x[j].bits;
-      int li = -1;
-      for (int i = 0; i < j; ++i)
-        if (li < 0 && sel_x[i].bits == bits) li = (int)((lay_of >> (2 * i)) & 3u);
-      if (li < 0) {
-        li = n_lay++;
-        uint32_t* XPs = LAY + li * lay_words;
-        float* XKs = (float*)(XPs + d / 2);
-        if (bits == 2) permute_x<2>(RAW, d, L.group, threadIdx.x, nthreads, XPs, XKs);
-        else if (bits == 4) permute_x<4>(RAW, d, L.group, threadIdx.x, nthreads, XPs, XKs);
-        else permute_x<8>(RAW, d, L.group, threadIdx.x, nthreads, XPs, XKs);
-      }
-      lay_of |= (uint32_t)li << (2 * j);
+    const int st = threadIdx.x - 64, sn = nthreads - 64;
+    if (P.bits_mask & 2) {
+      uint32_t* XPs = LAY + layout_slot(P.bits_mask, 2) * lay_words;
+      permute_x<2>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
+    }
+    if (P.bits_mask & 4) {
+      uint32_t* XPs = LAY + layout_slot(P.bits_mask, 4) * lay_words;
+      permute_x<4>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
+    }
+    if (P.bits_mask & 8) {
+      uint32_t* XPs = LAY + layout_slot(P.bits_mask, 8) * lay_words;
+      permute_x<8>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
     }
   }
-  __syncthreads();
+  __syncthreads();  // layouts, sel_e, sel_g are complete
+  if (routed && slice == 0 && (int)threadIdx.x < k) {
+    if (P.idx_out) P.idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
+    if (P.gate_out) P.gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
+  }
 
-  const int row_begin = slice * SW, row_end = row_begin + SW;
-  const bool sw = L.act == MOEQ_ACT_SWIGLU;
-  float yacc[kRbMax][4];
-#pragma unroll
-  for (int i = 0; i < kRbMax; ++i)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) yacc[i][r] = 0.f;
-
+  // ---- phase 1 of every chosen expert, back to back: no wavefront waits for another one here
   for (int j = 0; j < k; ++j) {
-    const DevExpert ex = sel_x[j];
-    const uint32_t* XP = LAY + (int)((lay_of >> (2 * j)) & 3u) * lay_words;
+    const int e = sel_e[j];
+    const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
+    const int bits = __builtin_amdgcn_readfirstlane(ex->bits);
+    const uint32_t* XP = LAY + layout_slot(P.bits_mask, bits) * lay_words;
     const float* XK = (const float*)(XP + d / 2);
-    uint16_t* HL = HLs + j * SW;
-    uint16_t* HP = HPs + j * SW;
-    const float gate = sel_g[j];
     int tid = threadIdx.x;  // opaque copy: keeps the per-bitwidth lane arithmetic inside this iteration
     asm volatile("" : "+v"(tid));
-    auto run = [&](auto bits_tag) {
+    switch (bits) {
+      case 2: fused_in<2, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+      case 4: fused_in<4, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+      default: fused_in<8, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+    }
+  }
+  // ---- phase 2 of every chosen expert (the first one's call holds the barrier between the phases)
+  for (int j = 0; j < k; ++j) {
+    const int e = sel_e[j];
+    const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
+    const int bits = __builtin_amdgcn_readfirstlane(ex->bits);
+    const uint16_t* HL = HLs + j * SW;
+    const uint16_t* HP = HPs + j * SW;
+    const float gate = sel_g[j];
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    auto run = [&](auto bits_tag) __attribute__((always_inline)) {
       constexpr int BITS = decltype(bits_tag)::value;
-      if (sw) fused_in_tasks<BITS, true>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, HL, HP, XP, XK);
-      else fused_in_tasks<BITS, false>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, HL, HP, XP, XK);
-      __syncthreads();  // this expert's h slice is complete in LDS
-      fused_out<BITS>(ex, tid, nthreads, d, L.group, slice, SW, gate, HL, HP, yacc);
+      const int DW = SW * BITS / 32;
+      if (DW >= 8) fused_expert_out<BITS, 8>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
+      else if (DW == 4) fused_expert_out<BITS, 4>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
+      else if (DW == 2) fused_expert_out<BITS, 2>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
+      else fused_expert_out<BITS, 1>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
     };
-    switch (ex.bits) {
+    switch (bits) {
       case 2: run(std::integral_constant<int, 2>{}); break;
       case 4: run(std::integral_constant<int, 4>{}); break;
       default: run(std::integral_constant<int, 8>{}); break;
     }
   }
 
-  float* out = P.part + ((size_t)token * gridDim.x + slice) * d;
-#pragma unroll
-  for (int i = 0; i < kRbMax; ++i) {
-    const int rb = (int)threadIdx.x + i * nthreads;
-    if (rb < d / 4) ((float4*)out)[rb] = make_float4(yacc[i][0], yacc[i][1], yacc[i][2], yacc[i][3]);
-  }
+  // every row block was accumulated by the thread that now writes it out
+  float4* out = (float4*)(P.part + ((size_t)token * gridDim.x + slice) * d);
+  for (int rb = threadIdx.x; rb < d / 4; rb += nthreads) out[rb] = Y[rb];
 }
 
 // y[t][r] (+)= sum over the slices of part[t][s][r], in a fixed order. Workgroup = 64 outputs x 16 slice
@@ -358,9 +590,9 @@ int cu_count() {
 
 constexpr size_t kFusedLdsBudget = 150 * 1024;
 
-size_t fused_lds_bytes(const LayerDims& L, int k, int SW) {
-  const int nl = k < 3 ? k : 3;
-  return (size_t)L.d_model * 2 + (size_t)k * SW * 4 + (size_t)nl * ((size_t)L.d_model / 2 + (size_t)L.d_model / 16) * 4;
+size_t fused_lds_bytes(const LayerDims& L, int k, int SW, int n_layouts) {
+  return (size_t)L.d_model * 2 + (size_t)k * SW * 4 + (size_t)L.d_model * 4 +
+         (size_t)n_layouts * ((size_t)L.d_model / 2 + (size_t)L.d_model / 16) * 4;
 }
 
 }  // namespace
@@ -386,25 +618,30 @@ FusedPlan plan_fused(const LayerDims& L) {
   static const int forced_nt = [] { const char* v = std::getenv("MOEQ_THREADS"); return v ? std::atoi(v) : 0; }();
   if (forced_nt >= 64 && forced_nt <= 1024 && forced_nt % 64 == 0) nt = forced_nt;
   if ((int64_t)nt * kRbMax * 4 < L.d_model) return p;   // every output row needs an owner
-  if (fused_lds_bytes(L, L.top_k, best) > kFusedLdsBudget) return p;
+  if (fused_lds_bytes(L, L.top_k, best, 3) > kFusedLdsBudget) return p;
+  if (L.d_model > 2048 * kMaxSegs) return p;
   p.SW = best;
   p.n_slices = L.d_ff / best;
   p.threads = nt;
   return p;
 }
 
+int fused_inline_router_max() { return kInlineMaxE; }
+
 hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const DevExpert* table, const float* router_w,
                              const float* router_bias, const float* logits, int32_t fixed_expert,
-                             const float* gate_in, const void* x, int32_t T, float* part, int32_t* idx_out,
-                             float* gate_out, hipStream_t st) {
-  if (!plan.SW || T < 1 || T > 65535) return hipErrorInvalidValue;
+                             const float* gate_in, int32_t bits_mask, const void* x, int32_t T, float* part,
+                             int32_t* idx_out, float* gate_out, hipStream_t st) {
+  if (!plan.SW || T < 1 || T > 65535 || !(bits_mask & 14)) return hipErrorInvalidValue;
   if (!logits && fixed_expert < 0 && L.n_experts > kInlineMaxE) return hipErrorInvalidValue;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
-  const size_t lds = fused_lds_bytes(L, k, plan.SW);
-  FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, x, part, idx_out, gate_out, plan.SW};
+  const int n_layouts = ((bits_mask >> 1) & 1) + ((bits_mask >> 2) & 1) + ((bits_mask >> 3) & 1);
+  const size_t lds = fused_lds_bytes(L, k, plan.SW, n_layouts);
+  FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, x, part, idx_out, gate_out, plan.SW,
+                bits_mask};
   static size_t granted[2] = {0, 0};
-  const int v = L.x_bf16 ? 1 : 0;
-  auto kernel = L.x_bf16 ? k_moe_decode<true> : k_moe_decode<false>;
+  const int v = L.act == MOEQ_ACT_SWIGLU ? 1 : 0;
+  auto kernel = v ? k_moe_decode<true> : k_moe_decode<false>;
   if (lds > 48 * 1024 && lds > granted[v]) {
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
