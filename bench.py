@@ -30,9 +30,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every layer from Python instead of a HIP graph")
     ap.add_argument("--layers", type=int, default=None, help="debug: truncate the stack")
-    ap.add_argument("--layout", default="columns", choices=["columns", "canonical"],
-                    help="W_out layout: columns = one streaming kernel per layer call (default), "
-                         "canonical = the two-kernel path on the boundary format")
+    ap.add_argument("--layout", default="auto", choices=["auto", "columns", "canonical"],
+                    help="W_out layout: columns = one streaming kernel per layer call, canonical = the "
+                         "two-kernel path on the boundary format, auto = columns for the Mixtral-sized "
+                         "experts (bandwidth-bound), canonical for the Switch-sized ones (latency-bound)")
     return ap.parse_args()
 
 
@@ -307,7 +308,10 @@ def main():
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]
     use_graph = not args.no_graph
-    columns = args.layout == "columns"
+    def use_columns(workload):
+        c = gen.CONFIGS[WORKLOADS[workload][0]]
+        return args.layout == "columns" or (args.layout == "auto" and c.d_model * c.d_ff >= (1 << 24))
+    columns = use_columns(name)
     stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers, columns=columns)
     cfg = stack.cfg
     achieved = res["kernel_bytes"] / (res["kernel_ms"] * 1e-3) / 1e9
@@ -320,7 +324,7 @@ def main():
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "act": cfg.act, "group": cfg.group,
                    "batch": stack.batch, "x_dtype": cfg.x_dtype, "bitwidths": cfg.bit_rule,
                    "packed_GB": round(res["packed_GB"], 3), "launch": "hip-graph" if use_graph else "eager",
-                   "w_out_layout": args.layout},
+                   "w_out_layout": "columns" if columns else "canonical"},
         "layer_tokens_per_s": res["layer_tokens_per_s"],
         "algorithmic_GBps": res["algorithmic_GBps"],
         "pct_hbm_peak": 100.0 * res["algorithmic_GBps"] / HBM_PEAK_GBS,
@@ -340,10 +344,12 @@ def main():
         for other, k in (("c1", 64), ("c2", 256), ("c3", 128), ("c3b8", 128)):
             if other == name:
                 continue
-            st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False, columns=columns)
-            extras[other] = {kk: r[kk] for kk in ("tokens_per_s", "layer_tokens_per_s", "ms_per_step",
+            st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False,
+                                 columns=use_columns(other))
+            extras[other] = {"w_out_layout": "columns" if use_columns(other) else "canonical"}
+            extras[other].update({kk: r[kk] for kk in ("tokens_per_s", "layer_tokens_per_s", "ms_per_step",
                                                   "algorithmic_GBps", "layers", "batch", "steps", "packed_GB")
-                             if kk in r}
+                             if kk in r})
             if "hot_expert_share" in r:
                 extras[other]["hot_expert_share"] = r["hot_expert_share"]
             del st

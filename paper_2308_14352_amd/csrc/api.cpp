@@ -123,7 +123,7 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   if (((uintptr_t)table_dev & 15u) || table_bytes < moe_layer_table_bytes(E)) return MOEQ_EINVAL;
   if (k > 8 || E > 1024 || d > 32768 || f > 32768 || d % 8 || f % 8) return MOEQ_EUNSUPPORTED;
   const LayerDims dims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0};
-  FusedPlan plan{0, 0, 0};
+  FusedPlan plan{0, 0, 0, 0};
   if (desc->out_layout == MOEQ_OUT_COLUMNS) {
     plan = plan_fused(dims);
     if (!plan.SW) return MOEQ_EUNSUPPORTED;

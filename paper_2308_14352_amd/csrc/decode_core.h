@@ -45,6 +45,11 @@ __device__ __forceinline__ uint4 load_stream16(const uint8_t* ptr) {
 }
 __device__ __forceinline__ uint32_t gload_u16(const uint8_t* ptr) { return *(const MOEQ_GLOBAL uint16_t*)ptr; }
 __device__ __forceinline__ uint32_t gload_u32(const uint8_t* ptr) { return *(const MOEQ_GLOBAL uint32_t*)ptr; }
+__device__ __forceinline__ uint2 gload_u32x2_nt(const uint8_t* ptr) {
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+  const u32x2_t v = __builtin_nontemporal_load((const MOEQ_GLOBAL u32x2_t*)ptr);
+  return make_uint2(v.x, v.y);
+}
 __device__ __forceinline__ uint2 gload_u32x2(const uint8_t* ptr) {
   typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
   const u32x2_t v = *(const MOEQ_GLOBAL u32x2_t*)ptr;

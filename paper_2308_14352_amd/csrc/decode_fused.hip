@@ -375,7 +375,317 @@ __device__ __forceinline__ void fused_expert_out(const DevExpert* ex, int tid, i
   fused_out<BITS, DWC>(first, qT_s, sT_g, tid, nthreads, d, SW, gate, first_expert, HL, HP, Y);
 }
 
-template <bool SWIGLU>
+// ---------------------------------------------------------------------------------------------
+// Matrix-core variant of the two phases. Unpacking costs half a vector instruction per weight, the
+// multiply-accumulate another half; handing the second half to the matrix cores (which otherwise idle)
+// about halves the vector work, which is what bounds this kernel at 2 and 4 bits. One
+// v_mfma_f32_16x16x32_f16 computes D[token][row] += sum_k X[token][k] * W[row][k] for 16 rows and 32
+// values of k: lane l supplies 8 consecutive k (block kb = l/16) of weight row n = l%16 as the B operand,
+// the activations are the A operand (all 16 token rows carry the same single token here), and the
+// result for weight row n arrives in lane n, element 0. The weights enter exactly as in the vector
+// path: masked code fields read as binary16 subnormals (the matrix cores honour them) against
+// activations pre-divided by the fields' powers of two, in the same staged pair order; the reduction
+// over k happens inside the instruction, so no cross-lane folding is needed.
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4v_t __attribute__((ext_vector_type(4)));
+
+// Eight codes as the four pair registers dword_dot<BITS> would consume: INT4: the 8 codes of w0; INT2: the
+// lower (HH = 0) or upper (HH = 1) half of the 16 codes of w0; INT8: the 4 + 4 codes of w0 and w1.
+template <int BITS, int HH>
+__device__ __forceinline__ half8_t codes8(uint32_t w0, uint32_t w1) {
+  u32x4v_t r;
+  if (BITS == 4) {
+    const uint32_t w8 = w0 >> 8;
+    r = {w0 & 0x000f000fu, w0 & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u};
+  } else if (BITS == 8) {
+    r = {w0 & 0x00ff00ffu, (w0 >> 8) & 0x00ff00ffu, w1 & 0x00ff00ffu, (w1 >> 8) & 0x00ff00ffu};
+  } else if (HH == 0) {
+    r = {w0 & 0x00030003u, w0 & 0x000c000cu, w0 & 0x00300030u, w0 & 0x00c000c0u};
+  } else {
+    const uint32_t w10 = w0 >> 10;
+    r = {w0 & 0x03000300u, w10 & 0x00030003u, w10 & 0x000c000cu, w10 & 0x00300030u};
+  }
+  return __builtin_bit_cast(half8_t, r);
+}
+__device__ __forceinline__ half8_t as_half8(const uint4& v) {
+  const u32x4v_t r = {v.x, v.y, v.z, v.w};
+  return __builtin_bit_cast(half8_t, r);
+}
+__device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+constexpr int kMxSlice = 64;   // slice width of the matrix-core variant
+
+// Phase 1 on the matrix cores, with the same coalesced row reads as the vector path. A tile is a
+// contiguous run of a row covering 16 lane columns x 4 k blocks: 1 KB (2048 columns at 4 bits, 1024 at 8
+// bits) read as 16 bytes per lane, or 512 bytes (2048 columns at 2 bits) read as 8 bytes per lane. Lane
+// (n, kb) takes the piece 4*n + kb of the run, so that the four lanes the instruction sums over (same n)
+// hold four consecutive pieces: 128 columns (64 at 8 bits), inside one scale group. Since every lane
+// column n then covers a different range of k, the activations go in with the A-operand row m holding the
+// activations of column group m: D[m][n] is the dot product of weight group n with activation group m, and
+// the useful results are the diagonal m == n (16 group dot products per instruction chain), found in lane
+// n + 16*(n/4), element n%4. Each diagonal lane scales its group's dot product with its own group scale
+// and accumulates; a wavefront sum per row finishes the dot product.
+template <int BITS, int NM, int JC, typename Epilogue>
+__device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uint8_t* const (&s)[NM], int d, int group,
+                                        int row_begin, int n_rows, int lane, int wave, int nwaves,
+                                        const uint32_t* XP, const float* XK, Epilogue epilogue) {
+  constexpr int WPC = 128 / BITS;
+  constexpr int TCOLS = BITS == 8 ? 1024 : 2048;        // columns of a tile
+  using TileT = std::conditional_t<BITS == 2, uint2, uint4>;
+  struct Set { TileT t[JC][NM]; uint32_t sc[JC][NM]; };
+  const int C = d / WPC;
+  const int J = d / TCOLS, JB = J / JC;                 // tiles per row, bursts per row
+  const int m = lane & 15, kb = lane >> 4;              // lane column (B operand) = group row (A operand)
+  const bool diag = kb == (m >> 2);
+  const int dsel = m & 3;
+  const uint32_t row_bytes = (uint32_t)C * 16u;
+  const uint32_t ng2 = (uint32_t)(d / group) * 2u;
+  const uint4* XP4 = (const uint4*)XP;
+  // rows of this wavefront: a contiguous run, walked from a workgroup-dependent start
+  const int rpw = (n_rows + nwaves - 1) / nwaves;
+  const int r_begin = wave * rpw;
+  const int my_rows = max(0, min(rpw, n_rows - r_begin));
+  const int rot = my_rows > 0 ? (int)blockIdx.x % my_rows : 0;
+  const int nb = my_rows * JB;
+  // lane's byte offset inside a tile, and the first column of its piece
+  const uint32_t lane_off = BITS == 2 ? (uint32_t)(32 * m + 8 * kb) : (uint32_t)(4 * m + kb) * 16u;
+  const uint32_t lane_col = BITS == 2 ? (uint32_t)(128 * m) : (uint32_t)(4 * m + kb) * (uint32_t)WPC;
+  constexpr uint32_t TBYTES = BITS == 2 ? 512u : 1024u;
+
+  auto row_of = [&](int b) __attribute__((always_inline)) {
+    const int ri = b / JB;
+    return r_begin + (ri + rot < my_rows ? ri + rot : ri + rot - my_rows);
+  };
+  auto issue = [&](Set& S, int b) __attribute__((always_inline)) {
+    const int j0 = (b % JB) * JC;
+    const uint32_t row = (uint32_t)(row_begin + row_of(b));
+#pragma unroll
+    for (int jj = 0; jj < JC; ++jj) {
+      const uint32_t j = (uint32_t)(j0 + jj);
+      const uint32_t g0 = ((j * (uint32_t)TCOLS + lane_col) / (uint32_t)group) * 2u;
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) {
+        const uint8_t* src = q[mm] + (row * row_bytes + j * TBYTES + lane_off);
+        if constexpr (BITS == 2) S.t[jj][mm] = gload_u32x2_nt(src);
+        else S.t[jj][mm] = load_stream16(src);
+        S.sc[jj][mm] = gload_u16(s[mm] + (row * ng2 + g0));
+      }
+    }
+  };
+  float acc[NM];
+  auto compute = [&](const Set& S, int b) __attribute__((always_inline)) {
+    const int j0 = (b % JB) * JC;
+    if (j0 == 0) {
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) acc[mm] = 0.f;
+    }
+    const float4_t zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jj = 0; jj < JC; ++jj) {
+      const int j = j0 + jj;
+      float4_t D[NM];
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) D[mm] = zero;
+      float K;   // offset term of the diagonal lane's column group
+      if constexpr (BITS == 2) {
+        const float2 k2 = *(const float2*)(XK + 32 * j + 2 * m);
+        K = k2.x + k2.y;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const half8_t A = as_half8(XP4[(2 * (2 * (kb & 1) + t) + hh) * C + 32 * j + 2 * m + (kb >> 1)]);
+#pragma unroll
+            for (int mm = 0; mm < NM; ++mm) {
+              const uint32_t dw = t ? S.t[jj][mm].y : S.t[jj][mm].x;
+              D[mm] = mfma16(A, hh ? codes8<2, 1>(dw, 0u) : codes8<2, 0>(dw, 0u), D[mm]);
+            }
+          }
+      } else {
+        const float4 k4 = *(const float4*)(XK + 64 * j + 4 * m);
+        K = (k4.x + k4.y) + (k4.z + k4.w);
+        constexpr int NI = BITS == 4 ? 4 : 2;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          const half8_t A = as_half8(XP4[i * C + 64 * j + 4 * m + kb]);
+#pragma unroll
+          for (int mm = 0; mm < NM; ++mm) {
+            const uint4 w = S.t[jj][mm];
+            if constexpr (BITS == 4) D[mm] = mfma16(A, codes8<4, 0>(i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w, 0u), D[mm]);
+            else D[mm] = mfma16(A, i == 0 ? codes8<8, 0>(w.x, w.y) : codes8<8, 0>(w.z, w.w), D[mm]);
+          }
+        }
+      }
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) {
+        const float dv = dsel == 0 ? D[mm][0] : dsel == 1 ? D[mm][1] : dsel == 2 ? D[mm][2] : D[mm][3];
+        const float contrib = f16_bits_to_f32(S.sc[jj][mm]) * (dv - K);
+        acc[mm] += diag ? contrib : 0.f;
+      }
+    }
+    if (j0 + JC == J) {
+      float r[NM];
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) r[mm] = wave_sum(acc[mm]) * 16777216.0f;
+      if (lane == 0) epilogue(row_begin + row_of(b), r);
+    }
+  };
+
+  Set A, B;
+  if (nb > 0) issue(A, 0);
+  for (int b = 0; b < nb; b += 2) {
+    if (b + 1 < nb) issue(B, b + 1);
+    compute(A, b);
+    if (b + 2 < nb) issue(A, b + 2);
+    if (b + 1 < nb) compute(B, b + 1);
+  }
+}
+
+template <int BITS, bool SWIGLU>
+__device__ __forceinline__ void fused_in_mfma(const DevExpert* ex, int tid, int nwaves, int d, int group, int row_begin,
+                                              int SW, uint16_t* HL, uint16_t* HP, const uint32_t* XP, const float* XK) {
+  constexpr int NM = SWIGLU ? 2 : 1;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  auto epi = [&](int row, const float (&r)[NM]) __attribute__((always_inline)) {
+    float v;
+    if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
+    else v = fmaxf(r[0], 0.f);
+    const uint32_t hb = f32_to_f16_bits(v);
+    const int c = row - row_begin;
+    HL[c] = (uint16_t)hb;
+    float ps;
+    const int si = slice_pair_index<BITS>(c, ps);
+    HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+  };
+  const uint8_t* q0 = uniform_ptr(ex->q_in);
+  const uint8_t* s0 = (const uint8_t*)uniform_ptr(ex->s_in);
+  const int J = d / (BITS == 8 ? 1024 : 2048);
+  auto run = [&](auto jc_tag) __attribute__((always_inline)) {
+    constexpr int JC = decltype(jc_tag)::value;
+    if constexpr (SWIGLU) {
+      const uint8_t* const qq[2] = {q0, uniform_ptr(ex->q_gate)};
+      const uint8_t* const ss[2] = {s0, (const uint8_t*)uniform_ptr(ex->s_gate)};
+      p1_mfma<BITS, 2, JC>(qq, ss, d, group, row_begin, SW, lane, wave, nwaves, XP, XK, epi);
+    } else {
+      const uint8_t* const qq[1] = {q0};
+      const uint8_t* const ss[1] = {s0};
+      p1_mfma<BITS, 1, JC>(qq, ss, d, group, row_begin, SW, lane, wave, nwaves, XP, XK, epi);
+    }
+  };
+  if (J % 2 == 0) run(std::integral_constant<int, 2>{});
+  else run(std::integral_constant<int, 1>{});
+}
+
+// Phase 2 on the matrix cores: a wavefront takes groups of 64 output rows; lane (n, kb) loads the 16-byte
+// tile with word column 4*step + kb (8-bit codes: the word columns 8*step + 2*kb and + 1) of the rows
+// 64*g + 4*n .. + 3, and instruction i multiplies row 4*n + i of every lane (here all A-operand rows
+// carry the same activations and the result for row n of the instruction arrives in lane n, element 0).
+// Register sets hold the tiles of GPS row groups; the first set is requested by the caller before the
+// barrier that completes h.
+template <int BITS>
+struct P2Mx {
+  static constexpr int DW = kMxSlice * BITS / 32;                   // word columns of a slice: 4 / 8 / 16
+  static constexpr int TPR = BITS == 2 ? 1 : (BITS == 4 ? 2 : 4);   // tiles per row group and lane
+  static constexpr int GPS = 4 / TPR;                               // row groups per register set
+  uint4 t[GPS][TPR];
+  uint2 sc[GPS];
+};
+
+// Row groups of a set: wave + (set * GPS + i) * nwaves.
+template <int BITS>
+__device__ __forceinline__ void p2_mfma_issue(P2Mx<BITS>& S, const uint8_t* qT_s, const uint8_t* sT_g, int d, int set,
+                                              int lane, int wave, int nwaves) {
+  const int n = lane & 15, kb = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < P2Mx<BITS>::GPS; ++i) {
+    const int g = wave + (set * P2Mx<BITS>::GPS + i) * nwaves;
+    if (g < d / 64) {
+      const uint32_t roff = (uint32_t)(64 * g + 4 * n) * 4u;
+#pragma unroll
+      for (int tt = 0; tt < P2Mx<BITS>::TPR; ++tt) {
+        const int w = BITS == 8 ? 8 * (tt >> 1) + 2 * kb + (tt & 1) : 4 * tt + kb;
+        S.t[i][tt] = load_stream16(qT_s + (size_t)w * ((size_t)d * 4) + roff);
+      }
+      S.sc[i] = gload_u32x2(sT_g + (uint32_t)(64 * g + 4 * n) * 2u);
+    }
+  }
+}
+
+template <int BITS>
+__device__ __forceinline__ void p2_mfma_compute(const P2Mx<BITS>& S, int d, int set, int lane, int wave, int nwaves,
+                                                const uint4* HP4, float K, float g24, bool first_expert, float4* Y) {
+  const int n = lane & 15, kb = lane >> 4;
+  const float4_t zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < P2Mx<BITS>::GPS; ++i) {
+    const int g = wave + (set * P2Mx<BITS>::GPS + i) * nwaves;
+    if (g < d / 64) {
+      float4_t D[4] = {zero, zero, zero, zero};
+      if constexpr (BITS == 4) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const half8_t A = as_half8(HP4[4 * tt + kb]);
+          D[0] = mfma16(A, codes8<4, 0>(S.t[i][tt].x, 0u), D[0]);
+          D[1] = mfma16(A, codes8<4, 0>(S.t[i][tt].y, 0u), D[1]);
+          D[2] = mfma16(A, codes8<4, 0>(S.t[i][tt].z, 0u), D[2]);
+          D[3] = mfma16(A, codes8<4, 0>(S.t[i][tt].w, 0u), D[3]);
+        }
+      } else if constexpr (BITS == 2) {
+        const half8_t A0 = as_half8(HP4[2 * kb]), A1 = as_half8(HP4[2 * kb + 1]);
+        const uint4 w = S.t[i][0];
+        D[0] = mfma16(A0, codes8<2, 0>(w.x, 0u), D[0]); D[0] = mfma16(A1, codes8<2, 1>(w.x, 0u), D[0]);
+        D[1] = mfma16(A0, codes8<2, 0>(w.y, 0u), D[1]); D[1] = mfma16(A1, codes8<2, 1>(w.y, 0u), D[1]);
+        D[2] = mfma16(A0, codes8<2, 0>(w.z, 0u), D[2]); D[2] = mfma16(A1, codes8<2, 1>(w.z, 0u), D[2]);
+        D[3] = mfma16(A0, codes8<2, 0>(w.w, 0u), D[3]); D[3] = mfma16(A1, codes8<2, 1>(w.w, 0u), D[3]);
+      } else {
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          const half8_t A = as_half8(HP4[4 * st + kb]);
+          D[0] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].x, S.t[i][2 * st + 1].x), D[0]);
+          D[1] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].y, S.t[i][2 * st + 1].y), D[1]);
+          D[2] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].z, S.t[i][2 * st + 1].z), D[2]);
+          D[3] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].w, S.t[i][2 * st + 1].w), D[3]);
+        }
+      }
+      if (lane < 16) {
+        float4 y = first_expert ? make_float4(0.f, 0.f, 0.f, 0.f) : Y[16 * g + n];
+        y.x = fmaf(f16_bits_to_f32(S.sc[i].x & 0xffffu) * g24, D[0][0] - K, y.x);
+        y.y = fmaf(f16_bits_to_f32(S.sc[i].x >> 16) * g24, D[1][0] - K, y.y);
+        y.z = fmaf(f16_bits_to_f32(S.sc[i].y & 0xffffu) * g24, D[2][0] - K, y.z);
+        y.w = fmaf(f16_bits_to_f32(S.sc[i].y >> 16) * g24, D[3][0] - K, y.w);
+        Y[16 * g + n] = y;
+      }
+    }
+  }
+}
+
+// Phase 2 of one expert; `first` holds the wavefront's first set (already requested).
+template <int BITS>
+__device__ __forceinline__ void fused_out_mfma(P2Mx<BITS>& first, const uint8_t* qT_s, const uint8_t* sT_g, int tid,
+                                               int nwaves, int d, float gate, bool first_expert,
+                                               const uint16_t* HL, const uint16_t* HP, float4* Y) {
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float hs = f16_bits_to_f32(HL[lane]);            // kMxSlice == 64: one activation per lane
+  hs = wave_sum(hs);
+  const float K = hs * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+  const float g24 = gate * 16777216.0f;
+  const uint4* HP4 = (const uint4*)HP;
+  const int RG = d / 64;
+  const int per_set = P2Mx<BITS>::GPS * nwaves;
+  const int n_sets = (RG + per_set - 1) / per_set;
+  P2Mx<BITS> other;
+  for (int st = 0; st < n_sets; st += 2) {
+    if (st + 1 < n_sets) p2_mfma_issue<BITS>(other, qT_s, sT_g, d, st + 1, lane, wave, nwaves);
+    p2_mfma_compute<BITS>(first, d, st, lane, wave, nwaves, HP4, K, g24, first_expert, Y);
+    if (st + 2 < n_sets) p2_mfma_issue<BITS>(first, qT_s, sT_g, d, st + 2, lane, wave, nwaves);
+    if (st + 1 < n_sets) p2_mfma_compute<BITS>(other, d, st + 1, lane, wave, nwaves, HP4, K, g24, first_expert, Y);
+  }
+}
+
+template <bool SWIGLU, bool MX>
 __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
@@ -483,6 +793,49 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     if (P.gate_out) P.gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
   }
 
+  if constexpr (MX) {
+    // ---- phase 1 of every chosen expert on the matrix cores, back to back
+    for (int j = 0; j < k; ++j) {
+      const int e = sel_e[j];
+      const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
+      const int bits = __builtin_amdgcn_readfirstlane(ex->bits);
+      const uint32_t* XP = LAY + layout_slot(P.bits_mask, bits) * lay_words;
+      const float* XK = (const float*)(XP + d / 2);
+      int tid = threadIdx.x;  // opaque copy: keeps the per-bitwidth lane arithmetic inside this iteration
+      asm volatile("" : "+v"(tid));
+      switch (bits) {
+        case 2: fused_in_mfma<2, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+        case 4: fused_in_mfma<4, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+        default: fused_in_mfma<8, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+      }
+    }
+    // ---- phase 2: per expert, the first set of tiles is requested ahead of the arithmetic; for the first
+    // expert ahead of the barrier between the phases
+    for (int j = 0; j < k; ++j) {
+      const int e = sel_e[j];
+      const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
+      const int bits = __builtin_amdgcn_readfirstlane(ex->bits);
+      const float gate = sel_g[j];
+      int tid = threadIdx.x;
+      asm volatile("" : "+v"(tid));
+      const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+      auto run = [&](auto bits_tag) __attribute__((always_inline)) {
+        constexpr int BITS = decltype(bits_tag)::value;
+        const uint8_t* qT_s = uniform_ptr(ex->q_out) + (size_t)(slice * P2Mx<BITS>::DW) * ((size_t)d * 4);
+        const uint8_t* sT_g = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)((slice * SW) / L.group) * ((size_t)d * 2);
+        P2Mx<BITS> first;
+        p2_mfma_issue<BITS>(first, qT_s, sT_g, d, 0, tid & 63, wv, nwaves);
+        if (j == 0) __syncthreads();   // the h slices of all chosen experts are complete in LDS
+        fused_out_mfma<BITS>(first, qT_s, sT_g, tid, nwaves, d, gate, j == 0, HLs + j * SW, HPs + j * SW, Y);
+      };
+      switch (bits) {
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        default: run(std::integral_constant<int, 8>{}); break;
+      }
+    }
+    __syncthreads();   // Y was written by the lanes that hold the instruction results, it is read by all
+  } else {
   // ---- phase 1 of every chosen expert, back to back: no wavefront waits for another one here
   for (int j = 0; j < k; ++j) {
     const int e = sel_e[j];
@@ -523,7 +876,9 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     }
   }
 
-  // every row block was accumulated by the thread that now writes it out
+  }
+
+  // (vector path: every row block was accumulated by the thread that now writes it out)
   float4* out = (float4*)(P.part + ((size_t)token * gridDim.x + slice) * d);
   for (int rb = threadIdx.x; rb < d / 4; rb += nthreads) out[rb] = Y[rb];
 }
@@ -601,7 +956,7 @@ size_t fused_lds_bytes(const LayerDims& L, int k, int SW, int n_layouts) {
 // a slice has one scale per output row; the widest one that still gives at least 3/4 of a workgroup per
 // compute unit, else the narrowest.
 FusedPlan plan_fused(const LayerDims& L) {
-  FusedPlan p{0, 0, 0};
+  FusedPlan p{0, 0, 0, 0};
   if (L.d_model % 8 || L.d_ff % 16 || L.group % 16) return p;
   static const int forced = [] { const char* v = std::getenv("MOEQ_SLICE"); return v ? std::atoi(v) : 0; }();
   const int want = cu_count() * 3 / 4;
@@ -618,11 +973,16 @@ FusedPlan plan_fused(const LayerDims& L) {
   static const int forced_nt = [] { const char* v = std::getenv("MOEQ_THREADS"); return v ? std::atoi(v) : 0; }();
   if (forced_nt >= 64 && forced_nt <= 1024 && forced_nt % 64 == 0) nt = forced_nt;
   if ((int64_t)nt * kRbMax * 4 < L.d_model) return p;   // every output row needs an owner
+  // Matrix-core variant: scale groups that are whole 128-column runs, 64-column slices, rows that are
+  // whole tiles at every bitwidth (2048 columns).
+  static const bool no_mx = [] { const char* v = std::getenv("MOEQ_NO_MFMA"); return v && v[0] == '1'; }();
+  const int mx = (!no_mx && best == kMxSlice && L.group % 128 == 0 && L.d_model % 2048 == 0) ? 1 : 0;
   if (fused_lds_bytes(L, L.top_k, best, 3) > kFusedLdsBudget) return p;
   if (L.d_model > 2048 * kMaxSegs) return p;
   p.SW = best;
   p.n_slices = L.d_ff / best;
   p.threads = nt;
+  p.mx = mx;
   return p;
 }
 
@@ -639,9 +999,11 @@ hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const De
   const size_t lds = fused_lds_bytes(L, k, plan.SW, n_layouts);
   FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, x, part, idx_out, gate_out, plan.SW,
                 bits_mask};
-  static size_t granted[2] = {0, 0};
-  const int v = L.act == MOEQ_ACT_SWIGLU ? 1 : 0;
-  auto kernel = v ? k_moe_decode<true> : k_moe_decode<false>;
+  static size_t granted[4] = {0, 0, 0, 0};
+  const bool sw = L.act == MOEQ_ACT_SWIGLU, mx = plan.mx != 0;
+  const int v = (sw ? 1 : 0) + (mx ? 2 : 0);
+  auto kernel = mx ? (sw ? k_moe_decode<true, true> : k_moe_decode<false, true>)
+                   : (sw ? k_moe_decode<true, false> : k_moe_decode<false, false>);
   if (lds > 48 * 1024 && lds > granted[v]) {
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

@@ -49,8 +49,9 @@ hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevE
 
 // ---- one-kernel decode path (W_out in the dword-column-major layout) -------------------------------
 // Split of a layer for the fused kernel: slices of SW columns of d_ff, one workgroup of `threads` per
-// (slice, token). SW == 0: the shape does not fit the scheme.
-struct FusedPlan { int32_t SW, n_slices, threads; };
+// (slice, token). SW == 0: the shape does not fit the scheme. mx != 0: the matrix-core variant of the kernel
+// runs.
+struct FusedPlan { int32_t SW, n_slices, threads, mx; };
 FusedPlan plan_fused(const LayerDims& L);
 
 // Router (inline when logits == nullptr: at most fused_inline_router_max() experts) + top-k + both FFN
