@@ -35,8 +35,13 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Workspace carving. Both paths keep idx, gate and logits; the two-kernel path adds the chosen experts'
 // records and the two copies of h, the one-kernel path the partial output vectors.
 struct WsLayout {
-  size_t idx_off, gate_off, logits_off, sel_off, h_off, hp_off, part_off, total;
+  size_t idx_off, gate_off, logits_off, sel_off, h_off, hp_off, part_off, prefill_off, total;
 };
+
+// Calls with at least this many tokens on a canonical-layout layer run as grouped GEMMs on the matrix cores
+// (when the shape allows); fewer tokens run the streaming decode kernels, token by token.
+constexpr int64_t kPrefillMinTokens = 32;
+bool use_prefill(const moeq_layer* layer, int64_t T);
 
 WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
   const LayerDims& L = layer->dims;
@@ -54,8 +59,17 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
     w.h_off = w.sel_off + align_up(slots * sizeof(DevExpert), 256);
     w.hp_off = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
     w.total = w.hp_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
+    if (use_prefill(layer, T)) {      // moe_layer_forward takes the grouped path; the single-expert call keeps h/hp
+      w.prefill_off = w.total;
+      w.total = w.prefill_off + prefill_ws(L, T).total;
+    }
   }
   return w;
+}
+
+bool use_prefill(const moeq_layer* layer, int64_t T) {
+  static const bool off = [] { const char* v = std::getenv("MOEQ_NO_PREFILL"); return v && v[0] == '1'; }();
+  return !off && T >= kPrefillMinTokens && layer->out_layout == MOEQ_OUT_CANONICAL && prefill_supported(layer->dims);
 }
 
 // Routers with at most this many experts are evaluated inside the one-kernel path by every workgroup;
@@ -251,6 +265,14 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
         return MOEQ_EDEVICE;
     }
     return dev(launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n_tokens, 0, y, st));
+  }
+  if (use_prefill(layer, n_tokens)) {
+    // batched path: router kernels, then the pairs grouped by expert through two quantized GEMMs
+    if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
+      return MOEQ_EDEVICE;
+    if (launch_topk(L, logits, n_tokens, idx, gate, nullptr, st) != hipSuccess) return MOEQ_EDEVICE;
+    const PrefillWs pw = prefill_ws(L, n_tokens);
+    return dev(launch_prefill(L, layer->table, x, n_tokens, idx, gate, (char*)ws + w.prefill_off, pw, y, st));
   }
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);

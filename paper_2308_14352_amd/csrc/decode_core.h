@@ -43,6 +43,10 @@ __device__ __forceinline__ uint4 load_stream16(const uint8_t* ptr) {
   const u32x4_t v = __builtin_nontemporal_load((const MOEQ_GLOBAL u32x4_t*)ptr);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ uint4 gload_u32x4(const uint8_t* ptr) {
+  const u32x4_t v = *(const MOEQ_GLOBAL u32x4_t*)ptr;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ uint32_t gload_u16(const uint8_t* ptr) { return *(const MOEQ_GLOBAL uint16_t*)ptr; }
 __device__ __forceinline__ uint32_t gload_u32(const uint8_t* ptr) { return *(const MOEQ_GLOBAL uint32_t*)ptr; }
 __device__ __forceinline__ uint2 gload_u32x2_nt(const uint8_t* ptr) {
@@ -135,6 +139,40 @@ __device__ __forceinline__ float dword_dot(uint32_t w, const uint32_t* xr, float
     acc = dot2(w10 & 0x00300030u, xr[7], acc);
   }
   return acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core operands (v_mfma_f32_16x16x32_f16). B-operand lane l holds 8 consecutive k of column n = l%16
+// (k block l/16); A-operand lane l holds 8 consecutive k of row m = l%16; D element i of lane l is
+// D[4*(l/16) + i][l%16].
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4v_t __attribute__((ext_vector_type(4)));
+
+// Eight codes as the four pair registers dword_dot<BITS> would consume: INT4: the 8 codes of w0; INT2: the
+// lower (HH = 0) or upper (HH = 1) half of the 16 codes of w0; INT8: the 4 + 4 codes of w0 and w1.
+template <int BITS, int HH>
+__device__ __forceinline__ half8_t codes8(uint32_t w0, uint32_t w1) {
+  u32x4v_t r;
+  if (BITS == 4) {
+    const uint32_t w8 = w0 >> 8;
+    r = {w0 & 0x000f000fu, w0 & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u};
+  } else if (BITS == 8) {
+    r = {w0 & 0x00ff00ffu, (w0 >> 8) & 0x00ff00ffu, w1 & 0x00ff00ffu, (w1 >> 8) & 0x00ff00ffu};
+  } else if (HH == 0) {
+    r = {w0 & 0x00030003u, w0 & 0x000c000cu, w0 & 0x00300030u, w0 & 0x00c000c0u};
+  } else {
+    const uint32_t w10 = w0 >> 10;
+    r = {w0 & 0x03000300u, w10 & 0x00030003u, w10 & 0x000c000cu, w10 & 0x00300030u};
+  }
+  return __builtin_bit_cast(half8_t, r);
+}
+__device__ __forceinline__ half8_t as_half8(const uint4& v) {
+  const u32x4v_t r = {v.x, v.y, v.z, v.w};
+  return __builtin_bit_cast(half8_t, r);
+}
+__device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -386,36 +386,6 @@ __device__ __forceinline__ void fused_expert_out(const DevExpert* ex, int tid, i
 // path: masked code fields read as binary16 subnormals (the matrix cores honour them) against
 // activations pre-divided by the fields' powers of two, in the same staged pair order; the reduction
 // over k happens inside the instruction, so no cross-lane folding is needed.
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4v_t __attribute__((ext_vector_type(4)));
-
-// Eight codes as the four pair registers dword_dot<BITS> would consume: INT4: the 8 codes of w0; INT2: the
-// lower (HH = 0) or upper (HH = 1) half of the 16 codes of w0; INT8: the 4 + 4 codes of w0 and w1.
-template <int BITS, int HH>
-__device__ __forceinline__ half8_t codes8(uint32_t w0, uint32_t w1) {
-  u32x4v_t r;
-  if (BITS == 4) {
-    const uint32_t w8 = w0 >> 8;
-    r = {w0 & 0x000f000fu, w0 & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u};
-  } else if (BITS == 8) {
-    r = {w0 & 0x00ff00ffu, (w0 >> 8) & 0x00ff00ffu, w1 & 0x00ff00ffu, (w1 >> 8) & 0x00ff00ffu};
-  } else if (HH == 0) {
-    r = {w0 & 0x00030003u, w0 & 0x000c000cu, w0 & 0x00300030u, w0 & 0x00c000c0u};
-  } else {
-    const uint32_t w10 = w0 >> 10;
-    r = {w0 & 0x03000300u, w10 & 0x00030003u, w10 & 0x000c000cu, w10 & 0x00300030u};
-  }
-  return __builtin_bit_cast(half8_t, r);
-}
-__device__ __forceinline__ half8_t as_half8(const uint4& v) {
-  const u32x4v_t r = {v.x, v.y, v.z, v.w};
-  return __builtin_bit_cast(half8_t, r);
-}
-__device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
-
 constexpr int kMxSlice = 64;   // slice width of the matrix-core variant
 
 // Phase 1 on the matrix cores, with the same coalesced row reads as the vector path. A tile is a

@@ -69,6 +69,19 @@ hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_
 hipError_t launch_transpose(const void* in, int64_t rows, int64_t cols, int elem_bytes, void* out,
                             hipStream_t st);
 
+// ---- batched (prefill) path: pairs grouped by expert, two quantized GEMMs on the matrix cores ----------
+// Byte offsets of the pieces of the prefill workspace (all 256-byte aligned) and the per-pair strides.
+struct PrefillWs {
+  size_t poff, nblk, blocks, gpair, ginv, gexp, xa, ha, ypair, total;
+  size_t a_pair_words, h_pair_words, max_blocks;
+};
+bool prefill_supported(const LayerDims& L);
+PrefillWs prefill_ws(const LayerDims& L, int64_t T);
+// idx / gate: the routing of the T tokens ([T][k], already computed). W_out in the canonical layout.
+hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void* x, int32_t T,
+                          const int32_t* idx, const float* gate, char* ws, const PrefillWs& w, float* y,
+                          hipStream_t st);
+
 hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
                                 uint8_t* q, uint16_t* s, hipStream_t st);
 hipError_t launch_unpack_codes(const uint8_t* q, int64_t rows, int64_t cols, int bits, int8_t* codes,

@@ -1,0 +1,429 @@
+// Batched (prefill) path of the MoE layer: the (token, choice) pairs are grouped by expert and every
+// expert's FFN runs as two GEMMs on the matrix cores over its own tokens (Section 2.1: only the chosen
+// experts work on a token; Section 3.2: their weights are decompressed by the mirror of the linear
+// quantization before use - here inside the GEMM, on the way from the packed tile to the instruction).
+//
+//   grouping : histogram of the pairs per expert, offsets, a list of (expert, block of 64 tokens) work
+//              items, a stable scatter of the pairs into expert order (and its inverse)
+//   staging  : per pair, the token's activations as binary16 in the pair order of its expert's
+//              bitwidth (the order dword_dot / codes8 consume), plus the offset term of every K step
+//   GEMM 1   : H[pair][row] = act(W_in x [, W_gate x]) for 64 tokens x 128 or 256 rows per workgroup
+//   GEMM 2   : Ypair[pair][row] = W_out h for 64 tokens x 256 rows per workgroup
+//   combine  : y[t] = sum_j gate[t][j] * Ypair[pair(t, j)], in top-k order
+//
+// The GEMMs never form floating-point weights: a wavefront reads 16-byte pieces of packed rows, masks
+// the code fields into binary16 subnormals (codes8) and feeds them to v_mfma_f32_16x16x32_f16 as the B
+// operand; the A operand (activations pre-divided by the fields' powers of two) comes from LDS. One K
+// step (128 columns, 64 at 8 bits) lies inside one scale group, so the group scale and the code offset
+// are applied to the step's partial product: acc += s * (D - 2^(b-1) * sum(x_step)).
+#include "decode_core.h"
+
+namespace moeq {
+namespace {
+
+constexpr int kTB = 64;        // tokens per work item
+constexpr int kGemmThreads = 256;
+
+// ---------------------------------------------------------------------------------------------
+// grouping
+__global__ __launch_bounds__(1024) void k_count_pairs(const int32_t* __restrict__ idx, int M, int E,
+                                                      int32_t* __restrict__ poff, int2* __restrict__ blocks,
+                                                      int32_t* __restrict__ n_blocks) {
+  __shared__ int h[1024];
+  for (int e = threadIdx.x; e < E; e += blockDim.x) h[e] = 0;
+  __syncthreads();
+  for (int p = threadIdx.x; p < M; p += blockDim.x) atomicAdd(&h[idx[p]], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int off = 0, nb = 0;
+    for (int e = 0; e < E; ++e) {
+      poff[e] = off;
+      const int c = h[e];
+      for (int tb = 0; tb * kTB < c; ++tb) blocks[nb++] = make_int2(e, tb);
+      off += c;
+    }
+    poff[E] = off;
+    *n_blocks = nb;
+  }
+}
+
+// Workgroup e writes the pairs routed to expert e, in increasing pair order, behind poff[e].
+__global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ idx, int M,
+                                                       const int32_t* __restrict__ poff, int32_t* __restrict__ gpair,
+                                                       int32_t* __restrict__ ginv, int32_t* __restrict__ gexp) {
+  __shared__ int wcnt[4];
+  const int e = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int base = poff[e];
+  for (int p0 = 0; p0 < M; p0 += 256) {
+    const int p = p0 + threadIdx.x;
+    const bool hit = p < M && idx[p] == e;
+    const unsigned long long mask = __ballot(hit);
+    const int before = __popcll(mask & ((1ull << lane) - 1ull));
+    if (lane == 0) wcnt[wave] = __popcll(mask);
+    __syncthreads();
+    int wbase = 0;
+    for (int w = 0; w < wave; ++w) wbase += wcnt[w];
+    const int total = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+    if (hit) {
+      const int g = base + wbase + before;
+      gpair[g] = p;
+      ginv[p] = g;
+      gexp[g] = e;
+    }
+    base += total;
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// staging of the activations of one pair. Per pair: [K/2 words in pair order][n_steps offset terms].
+template <int BITS>
+__device__ __forceinline__ void step_sums(const uint16_t* RAW, int cols, int tid, int nthreads, float* KS) {
+  constexpr int SC = BITS == 8 ? 64 : 128;
+  for (int st = tid; st < cols / SC; st += nthreads) {
+    float a = 0.f;
+    for (int i = 0; i < SC; ++i) a += f16_bits_to_f32(RAW[st * SC + i]);
+    KS[st] = a * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_stage_x(LayerDims L, const DevExpert* __restrict__ table,
+                                                 const void* __restrict__ x, const int32_t* __restrict__ gpair,
+                                                 const int32_t* __restrict__ gexp, uint32_t* __restrict__ XA,
+                                                 int64_t pair_words) {
+  extern __shared__ uint32_t smem[];
+  uint16_t* RAW = (uint16_t*)smem;
+  const int d = L.d_model;
+  const int g = blockIdx.x;
+  const int t = gpair[g] / L.top_k;
+  const int bits = table[gexp[g]].bits;
+  const char* xt = (const char*)x + (size_t)t * d * (L.x_bf16 ? 2 : 4);
+  copy_x_to_lds(xt, L.x_bf16 ? X_BF16 : X_F32, d, threadIdx.x, blockDim.x, RAW);
+  __syncthreads();
+  uint32_t* XP = XA + (size_t)g * pair_words;
+  float* KS = (float*)(XP + d / 2);
+  float* scratch = (float*)(smem + d / 2);     // the per-chunk offset terms permute_x also makes; not kept
+  if (bits == 2) { permute_x<2>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<2>(RAW, d, threadIdx.x, blockDim.x, KS); }
+  else if (bits == 4) { permute_x<4>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<4>(RAW, d, threadIdx.x, blockDim.x, KS); }
+  else { permute_x<8>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<8>(RAW, d, threadIdx.x, blockDim.x, KS); }
+}
+
+// Offset terms of the K steps of GEMM 2 from the staged h of one pair (values back from the pair order).
+template <int BITS>
+__device__ __forceinline__ void h_step_sums(const uint16_t* HP, int f, int tid, int nthreads, float* KS) {
+  constexpr int SC = BITS == 8 ? 64 : 128;
+  const int C = f / Fmt<BITS>::WPC;
+  for (int st = tid; st < f / SC; st += nthreads) {
+    float a = 0.f;
+    for (int i = 0; i < SC; ++i) {
+      float ps;
+      const int si = staged_index<BITS>(st * SC + i, C, ps);
+      a += f16_bits_to_f32(HP[si]) / ps;
+    }
+    KS[st] = a * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+  }
+}
+__global__ __launch_bounds__(256) void k_h_sums(LayerDims L, const DevExpert* __restrict__ table,
+                                                const int32_t* __restrict__ gexp, uint32_t* __restrict__ HA,
+                                                int64_t pair_words) {
+  const int f = L.d_ff;
+  const int g = blockIdx.x;
+  const int bits = table[gexp[g]].bits;
+  uint32_t* HPw = HA + (size_t)g * pair_words;
+  float* KS = (float*)(HPw + f / 2);
+  if (bits == 2) h_step_sums<2>((const uint16_t*)HPw, f, threadIdx.x, blockDim.x, KS);
+  else if (bits == 4) h_step_sums<4>((const uint16_t*)HPw, f, threadIdx.x, blockDim.x, KS);
+  else h_step_sums<8>((const uint16_t*)HPw, f, threadIdx.x, blockDim.x, KS);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The quantized GEMM. Workgroup = 4 wavefronts = 64 tokens x (4 wavefronts x 4 streams x 16 rows); a
+// stream is (matrix, block of 16 rows): with two matrices (SwiGLU phase 1) a wavefront owns 32 rows of both,
+// else 64 rows. Lane (n, kb) of a wavefront holds, per K step, the 16-byte piece 4*step + kb of row n of
+// each stream (8 bytes at 2 bits): four k blocks along one scale group.
+struct GemmArgs {
+  LayerDims L;
+  const DevExpert* table;
+  const int2* blocks;
+  const int32_t* n_blocks;
+  const int32_t* poff;
+  const uint32_t* A;        // staged activations: per pair [K/2 pair words][K steps of offset terms]
+  int64_t a_pair_words;
+  uint32_t* H;              // phase 1 out: staged h per pair (same structure, K = d_ff)
+  int64_t h_pair_words;
+  float* Y;                 // phase 2 out: [pairs][d_model]
+};
+
+// uint4 index, inside a pair's staged words, of A operand q of a K step for k block kb
+template <int BITS>
+__device__ __forceinline__ int a_src_index(int C, int step, int q, int kb) {
+  if (BITS == 2) return (2 * (2 * (kb & 1) + (q >> 1)) + (q & 1)) * C + 2 * step + (kb >> 1);
+  return q * C + 4 * step + kb;
+}
+
+template <int BITS, int NM, int PHASE>
+__device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex, int e, int tb, uint4* As, float* Ks) {
+  constexpr int WPC = 128 / BITS;
+  constexpr int SC = BITS == 8 ? 64 : 128;        // columns per K step
+  constexpr int NQ = BITS == 8 ? 2 : 4;           // instructions per step, stream and token block
+  constexpr int NS = 4;                           // streams per wavefront
+  constexpr int RBW = NS / NM;                    // row blocks per wavefront and matrix
+  constexpr int BN = 4 * RBW * 16;                // rows per workgroup
+  constexpr int APAD = 65;                        // tokens per (q, kb) line of the LDS tile, padded
+  using TileT = std::conditional_t<BITS == 2, uint2, uint4>;
+  const int K = PHASE == 0 ? G.L.d_model : G.L.d_ff;
+  const int N = PHASE == 0 ? G.L.d_ff : G.L.d_model;
+  const int group = G.L.group;
+  const int C = K / WPC, n_steps = K / SC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, kb = lane >> 4;
+  const int g0 = G.poff[e] + tb * kTB;
+  const int ntok = min(kTB, G.poff[e + 1] - g0);
+  const int R0 = blockIdx.x * BN + wave * (RBW * 16);
+  const uint32_t row_bytes = (uint32_t)C * 16u;
+  const uint32_t ng2 = (uint32_t)(K / group) * 2u;
+
+  const uint8_t* qs[NM];
+  const uint8_t* ss[NM];
+  if (PHASE == 0) {
+    qs[0] = ex.q_in; ss[0] = (const uint8_t*)ex.s_in;
+    if (NM == 2) { qs[NM - 1] = ex.q_gate; ss[NM - 1] = (const uint8_t*)ex.s_gate; }
+  } else {
+    qs[0] = ex.q_out; ss[0] = (const uint8_t*)ex.s_out;
+  }
+  uint32_t qrow[NS], srow[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    const uint32_t row = (uint32_t)min(R0 + (s % RBW) * 16 + n, N - 1);
+    qrow[s] = row * row_bytes;
+    srow[s] = row * ng2;
+  }
+  struct BSet { TileT t[NS]; uint32_t sc[NS]; };
+  auto load_b = [&](BSet& B, int step) __attribute__((always_inline)) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const uint8_t* q = qs[s / RBW];
+      if constexpr (BITS == 2) B.t[s] = gload_u32x2(q + (qrow[s] + (uint32_t)step * 32u + (uint32_t)kb * 8u));
+      else B.t[s] = gload_u32x4(q + (qrow[s] + (uint32_t)step * 64u + (uint32_t)kb * 16u));
+      B.sc[s] = gload_u16(ss[s / RBW] + (srow[s] + (((uint32_t)step * (uint32_t)SC) / (uint32_t)group) * 2u));
+    }
+  };
+  // A tile of a step: thread -> (kb, token, q) items; 4 consecutive threads read 64 contiguous bytes
+  constexpr int AITEMS = NQ * 4 * kTB / kGemmThreads;     // 16-byte items per thread and step
+  struct ASet { uint4 v[AITEMS]; float ks; };
+  auto load_a = [&](ASet& A, int step) __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < AITEMS; ++r) {
+      const int item = threadIdx.x + r * kGemmThreads;
+      const int akb = item & 3, tok = (item >> 2) & 63, q = item >> 8;
+      A.v[r] = make_uint4(0u, 0u, 0u, 0u);
+      if (tok < ntok) {
+        const uint4* src = (const uint4*)(G.A + (size_t)(g0 + tok) * G.a_pair_words);
+        A.v[r] = src[a_src_index<BITS>(C, step, q, akb)];
+      }
+    }
+    A.ks = 0.f;
+    if ((int)threadIdx.x < ntok)
+      A.ks = ((const float*)(G.A + (size_t)(g0 + threadIdx.x) * G.a_pair_words + K / 2))[step];
+  };
+  auto store_a = [&](const ASet& A, int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < AITEMS; ++r) {
+      const int item = threadIdx.x + r * kGemmThreads;
+      const int akb = item & 3, tok = (item >> 2) & 63, q = item >> 8;
+      As[(buf * NQ * 4 + q * 4 + akb) * APAD + tok] = A.v[r];
+    }
+    if (threadIdx.x < kTB) Ks[buf * kTB + threadIdx.x] = A.ks;
+  };
+
+  float4_t acc[NS][4];
+  const float4_t zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) acc[s][t4] = zero;
+
+  auto compute = [&](const BSet& B, int buf) __attribute__((always_inline)) {
+    half8_t Bop[NS][NQ];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      if constexpr (BITS == 4) {
+        Bop[s][0] = codes8<4, 0>(B.t[s].x, 0u); Bop[s][1] = codes8<4, 0>(B.t[s].y, 0u);
+        Bop[s][2] = codes8<4, 0>(B.t[s].z, 0u); Bop[s][3] = codes8<4, 0>(B.t[s].w, 0u);
+      } else if constexpr (BITS == 8) {
+        Bop[s][0] = codes8<8, 0>(B.t[s].x, B.t[s].y); Bop[s][1] = codes8<8, 0>(B.t[s].z, B.t[s].w);
+      } else {
+        Bop[s][0] = codes8<2, 0>(B.t[s].x, 0u); Bop[s][1] = codes8<2, 1>(B.t[s].x, 0u);
+        Bop[s][2] = codes8<2, 0>(B.t[s].y, 0u); Bop[s][3] = codes8<2, 1>(B.t[s].y, 0u);
+      }
+    }
+    float sc[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) sc[s] = f16_bits_to_f32(B.sc[s]);
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) {
+      const float4 k4 = *(const float4*)(Ks + buf * kTB + 16 * t4 + 4 * kb);
+      const float4_t kv = {k4.x, k4.y, k4.z, k4.w};
+      float4_t D[NS];
+#pragma unroll
+      for (int s = 0; s < NS; ++s) D[s] = zero;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const half8_t A = as_half8(As[(buf * NQ * 4 + q * 4 + kb) * APAD + 16 * t4 + n]);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) D[s] = mfma16(A, Bop[s][q], D[s]);
+      }
+#pragma unroll
+      for (int s = 0; s < NS; ++s) acc[s][t4] += sc[s] * (D[s] - kv);
+    }
+  };
+
+  BSet B0, B1;
+  ASet A0;
+  load_a(A0, 0);
+  load_b(B0, 0);
+  store_a(A0, 0);
+  __syncthreads();
+  for (int step = 0; step < n_steps; step += 2) {
+    // even step: tiles in B0 / LDS buffer 0; odd step: B1 / buffer 1
+    if (step + 1 < n_steps) { load_a(A0, step + 1); load_b(B1, step + 1); }
+    compute(B0, 0);
+    if (step + 1 < n_steps) store_a(A0, 1);
+    __syncthreads();
+    if (step + 1 < n_steps) {
+      if (step + 2 < n_steps) { load_a(A0, step + 2); load_b(B0, step + 2); }
+      compute(B1, 1);
+      if (step + 2 < n_steps) store_a(A0, 0);
+      __syncthreads();
+    }
+  }
+
+  // D element i of lane (n, kb) belongs to token 16*t4 + 4*kb + i and row n of the stream
+  if constexpr (PHASE == 0) {
+    const int Cf = N / WPC;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      const int row = R0 + rb * 16 + n;
+      float ps;
+      const int si = staged_index<BITS>(min(row, N - 1), Cf, ps);
+#pragma unroll
+      for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = 16 * t4 + 4 * kb + i;
+          if (tok < ntok && row < N) {
+            float v;
+            const float a = acc[rb][t4][i] * 16777216.0f;
+            if constexpr (NM == 2) v = a / (1.0f + __expf(-a)) * (acc[RBW + rb][t4][i] * 16777216.0f);
+            else v = fmaxf(a, 0.f);
+            const uint32_t hb = f32_to_f16_bits(v);
+            uint16_t* Hp = (uint16_t*)(G.H + (size_t)(g0 + tok) * G.h_pair_words);
+            Hp[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+          }
+        }
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int row = R0 + s * 16 + n;
+#pragma unroll
+      for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int tok = 16 * t4 + 4 * kb + i;
+          if (tok < ntok && row < N) G.Y[(size_t)(g0 + tok) * N + row] = acc[s][t4][i] * 16777216.0f;
+        }
+    }
+  }
+}
+
+template <int NM, int PHASE>
+__global__ __launch_bounds__(kGemmThreads) void k_gemm_q(GemmArgs G) {
+  __shared__ uint4 As[2 * 4 * 4 * 65];
+  __shared__ float Ks[2 * kTB];
+  if ((int)blockIdx.y >= *G.n_blocks) return;
+  const int2 blk = G.blocks[blockIdx.y];
+  const DevExpert ex = G.table[blk.x];
+  switch (ex.bits) {
+    case 2: gemm_body<2, NM, PHASE>(G, ex, blk.x, blk.y, As, Ks); break;
+    case 4: gemm_body<4, NM, PHASE>(G, ex, blk.x, blk.y, As, Ks); break;
+    default: gemm_body<8, NM, PHASE>(G, ex, blk.x, blk.y, As, Ks); break;
+  }
+}
+
+// y[t][r] = sum_j gate[t][j] * Ypair[ginv[t*k + j]][r], j in top-k order
+__global__ __launch_bounds__(256) void k_combine(const float* __restrict__ Ypair, const int32_t* __restrict__ ginv,
+                                                 const float* __restrict__ gate, int k, int d, float* __restrict__ y) {
+  const int t = blockIdx.x;
+  for (int r = threadIdx.x * 4; r < d; r += blockDim.x * 4) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; ++j) {
+      const float g = gate[(size_t)t * k + j];
+      const float4 v = *(const float4*)(Ypair + (size_t)ginv[(size_t)t * k + j] * d + r);
+      a.x = fmaf(g, v.x, a.x); a.y = fmaf(g, v.y, a.y); a.z = fmaf(g, v.z, a.z); a.w = fmaf(g, v.w, a.w);
+    }
+    *(float4*)(y + (size_t)t * d + r) = a;
+  }
+}
+
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+}  // namespace
+
+bool prefill_supported(const LayerDims& L) {
+  return L.group % 128 == 0 && L.d_model % 256 == 0 && L.d_ff % 256 == 0 && L.d_model <= 16384 && L.n_experts <= 1024;
+}
+
+PrefillWs prefill_ws(const LayerDims& L, int64_t T) {
+  PrefillWs w{};
+  const size_t M = (size_t)T * L.top_k;
+  const size_t max_blocks = M / kTB + (size_t)L.n_experts;
+  w.a_pair_words = (size_t)L.d_model / 2 + (size_t)L.d_model / 64;
+  w.h_pair_words = (size_t)L.d_ff / 2 + (size_t)L.d_ff / 64;
+  size_t off = 0;
+  w.poff = off;    off += up256(((size_t)L.n_experts + 1) * 4);
+  w.nblk = off;    off += 256;
+  w.blocks = off;  off += up256(max_blocks * 8);
+  w.gpair = off;   off += up256(M * 4);
+  w.ginv = off;    off += up256(M * 4);
+  w.gexp = off;    off += up256(M * 4);
+  w.xa = off;      off += up256(M * w.a_pair_words * 4);
+  w.ha = off;      off += up256(M * w.h_pair_words * 4);
+  w.ypair = off;   off += up256(M * (size_t)L.d_model * 4);
+  w.total = off;
+  w.max_blocks = max_blocks;
+  return w;
+}
+
+hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void* x, int32_t T, const int32_t* idx,
+                          const float* gate, char* ws, const PrefillWs& w, float* y, hipStream_t st) {
+  const int M = T * L.top_k;
+  int32_t* poff = (int32_t*)(ws + w.poff);
+  int32_t* nblk = (int32_t*)(ws + w.nblk);
+  int2* blocks = (int2*)(ws + w.blocks);
+  int32_t* gpair = (int32_t*)(ws + w.gpair);
+  int32_t* ginv = (int32_t*)(ws + w.ginv);
+  int32_t* gexp = (int32_t*)(ws + w.gexp);
+  uint32_t* XA = (uint32_t*)(ws + w.xa);
+  uint32_t* HA = (uint32_t*)(ws + w.ha);
+  float* Ypair = (float*)(ws + w.ypair);
+  hipLaunchKernelGGL(k_count_pairs, dim3(1), dim3(1024), 0, st, idx, M, L.n_experts, poff, blocks, nblk);
+  hipLaunchKernelGGL(k_scatter_pairs, dim3(L.n_experts), dim3(256), 0, st, idx, M, poff, gpair, ginv, gexp);
+  const size_t stage_lds = (size_t)L.d_model * 2 + (size_t)L.d_model / 16 * 4 + 64;
+  hipLaunchKernelGGL(k_stage_x, dim3(M), dim3(256), stage_lds, st, L, table, x, gpair, gexp, XA, (int64_t)w.a_pair_words);
+  GemmArgs G{L, table, blocks, nblk, poff, XA, (int64_t)w.a_pair_words, HA, (int64_t)w.h_pair_words, Ypair};
+  const unsigned nb = (unsigned)w.max_blocks;
+  if (L.act == MOEQ_ACT_SWIGLU)
+    hipLaunchKernelGGL((k_gemm_q<2, 0>), dim3((L.d_ff + 127) / 128, nb), dim3(kGemmThreads), 0, st, G);
+  else
+    hipLaunchKernelGGL((k_gemm_q<1, 0>), dim3((L.d_ff + 255) / 256, nb), dim3(kGemmThreads), 0, st, G);
+  hipLaunchKernelGGL(k_h_sums, dim3(M), dim3(256), 0, st, L, table, gexp, HA, (int64_t)w.h_pair_words);
+  G.A = HA;
+  G.a_pair_words = (int64_t)w.h_pair_words;
+  hipLaunchKernelGGL((k_gemm_q<1, 1>), dim3((L.d_model + 255) / 256, nb), dim3(kGemmThreads), 0, st, G);
+  hipLaunchKernelGGL(k_combine, dim3(T), dim3(256), 0, st, Ypair, ginv, gate, L.top_k, L.d_model, y);
+  return hipGetLastError();
+}
+
+}  // namespace moeq

@@ -241,3 +241,61 @@ def test_layer_forward_batch8_switch_large_and_workspace_errors(columns):
     assert ei.value.status == moeq.binding.MOEQ_EWORKSPACE
     with pytest.raises(moeq.MoeqError):
         moeq.moe_expert_ffn_q(layer, 99, x)
+
+
+# ------------------------------------------------------------------ batched (prefill) path: grouped GEMMs on the matrix cores
+PREFILL_TOL = 2e-2   # the bar for the matrix-core path
+
+
+@pytest.mark.parametrize("base,d,f,E,g,T", [
+    ("c5", 512, 1024, 8, 128, 300),     # SwiGLU, 4/8-bit experts, ragged groups (not multiples of 64 tokens)
+    ("c4", 256, 768, 4, 128, 97),       # SwiGLU, 2/4-bit experts
+    ("c1", 256, 512, 4, 128, 130),      # ReLU, top-1, 2/4/8-bit experts
+])
+def test_prefill_layer_matches_oracle(base, d, f, E, g, T):
+    cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1, group=g)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 2
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    err = rel_err(y.cpu().numpy()[keep], y_ref[keep])
+    assert err.max() < PREFILL_TOL, err.max()
+    # the same tokens through the decode kernels (one by one) agree with the grouped path
+    y_dec = torch.cat([moeq.moe_layer_forward(layer, x[t:t + 1]) for t in range(0, min(T, 8))])
+    torch.cuda.synchronize()
+    assert rel_err(y.cpu().numpy()[:8], y_dec.cpu().numpy()).max() < PREFILL_TOL
+    # purity
+    y_b = moeq.moe_layer_forward(layer, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_b)
+
+
+def test_prefill_full_size_mixtral_layer_on_sampled_tokens():
+    """The prefill configuration at its real shape (2048 tokens, top-2 of 8 SwiGLU experts at 4/8 bits):
+    routing of every token against the oracle, outputs of a sample of tokens against the oracle."""
+    cfg = gen.CONFIGS["c5"]
+    T = cfg.prefill_tokens
+    bits_table = gen.bitwidth_table(cfg, 0)
+    layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, want_oracle=False)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, _ = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(), bias.cpu().numpy(), cfg.top_k,
+                                              cfg.renorm)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = np.array([t for t in range(T) if t not in skip])
+    assert len(keep) >= T - 4
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    counts = np.bincount(idx_ref.flatten(), minlength=cfg.n_experts)
+    assert counts.sum() == T * cfg.top_k and counts.max() > counts.min()      # the bias makes the load uneven
+    sample = [int(t) for t in keep[np.linspace(0, len(keep) - 1, 6).astype(int)]]
+    experts = _lazy_oracle_experts(cfg, 0, bits_table, set(idx_ref[sample].flatten().tolist()))
+    y_ref, _, _ = oracle_layer(cfg, experts, Wr, bias, x[sample])
+    assert rel_err(y.cpu().numpy()[sample], y_ref).max() < PREFILL_TOL
+    assert torch.isfinite(y).all()
