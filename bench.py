@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every layer from Python instead of a HIP graph")
     ap.add_argument("--layers", type=int, default=None, help="debug: truncate the stack")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="run only a plain elementwise pass over 1 GiB (reads 1 GiB, writes 1 GiB) and exit: the "
+                         "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--layout", default="auto", choices=["auto", "columns", "canonical"],
                     help="W_out layout: columns = one streaming kernel per layer call, canonical = the "
                          "two-kernel path on the boundary format, auto = columns for the Mixtral-sized "
@@ -253,6 +256,31 @@ def cpu_baseline(stack, dev, budget_layers):
                       f"{per_layer * 1e3:.1f} ms per token-layer, scaled to the {stack.L}-layer stack"}
 
 
+def run_prefill(dev, reps=5):
+    """c5: one Mixtral-8x7B-shaped layer, 2048 tokens in one call (grouped GEMMs on the matrix cores)."""
+    import torch
+    import gen
+    import paper_2308_14352_amd as moeq
+    cfg = gen.CONFIGS["c5"]
+    T = cfg.prefill_tokens
+    st = Stack(cfg, T, 1, dev, 1, columns=False)
+    layer, x = st.layers[0], st.x_all[0, 0]
+    y = torch.empty((T, cfg.d_model), dtype=torch.float32, device=dev)
+    ws = torch.empty(layer.workspace_bytes(T), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        moeq.moe_layer_forward(layer, x, y=y, ws=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        moeq.moe_layer_forward(layer, x, y=y, ws=ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    flops = 2.0 * 3 * cfg.d_model * cfg.d_ff * T * cfg.top_k
+    return {"tokens_per_s": T / dt, "ms_per_call": dt * 1e3, "tokens": T, "achieved_TFLOPs": flops / dt / 1e12,
+            "mfma_f16_peak_TFLOPs": 2500.0, "frac_of_mfma_peak": flops / dt / 2.5e15,
+            "packed_GB": st.packed_bytes / 1e9, "bitwidths": st.bits[0]}
+
+
 WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8), "c4": ("c4", 1)}
 DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
 
@@ -305,6 +333,15 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.pmc_calibrate:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch.add over 2^28 fp32", "read_bytes": a.numel() * 4,
+                          "write_bytes": b.numel() * 4}))
+        return
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]
     use_graph = not args.no_graph
@@ -354,6 +391,7 @@ def main():
                 extras[other]["hot_expert_share"] = r["hot_expert_share"]
             del st
             torch.cuda.empty_cache()
+        extras["c5_prefill"] = run_prefill(dev)
         out["other_workloads"] = extras
     print(json.dumps(out))
 

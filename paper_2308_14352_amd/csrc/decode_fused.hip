@@ -853,37 +853,40 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   for (int rb = threadIdx.x; rb < d / 4; rb += nthreads) out[rb] = Y[rb];
 }
 
-// y[t][r] (+)= sum over the slices of part[t][s][r], in a fixed order. Workgroup = 64 outputs x 16 slice
-// teams: team g sums the slices g, g+16, ... for its 4 outputs, then the 16 team sums are added in order.
+// y[t][r] (+)= sum over the slices of part[t][s][r], in a fixed order. Workgroup = 16 outputs x 64 slice
+// teams: team g sums the slices g, g+64, ... for its 4 outputs, then the 64 team sums are added pairwise in
+// a fixed tree. Small workgroups on many compute units: the kernel is one memory round trip long.
 __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ part, int n_slices, int d,
                                                          int accumulate, float* __restrict__ y) {
-  __shared__ float4 red[16][16];
+  __shared__ float4 red[64][4];
   const int token = blockIdx.y;
-  const int rq = threadIdx.x & 15, sg = threadIdx.x >> 4;
-  const int r0 = blockIdx.x * 64 + rq * 4;
+  const int rq = threadIdx.x & 3, sg = threadIdx.x >> 2;
+  const int r0 = blockIdx.x * 16 + rq * 4;
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   if (r0 < d) {
     const float* p = part + (size_t)token * n_slices * d + r0;
-    for (int s = sg; s < n_slices; s += 16) {
+    for (int s = sg; s < n_slices; s += 64) {
       const float4 v = *(const float4*)(p + (size_t)s * d);
       a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
   }
   red[sg][rq] = a;
   __syncthreads();
-  if (threadIdx.x < 16 && r0 < d) {
-    float4 t = red[0][rq];
-#pragma unroll
-    for (int g = 1; g < 16; ++g) {
-      const float4 v = red[g][rq];
-      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+  for (int half = 32; half >= 1; half >>= 1) {
+    if (sg < half) {
+      const float4 v = red[sg + half][rq];
+      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+      red[sg][rq] = a;
     }
+    __syncthreads();
+  }
+  if (sg == 0 && r0 < d) {
     float4* o = (float4*)(y + (size_t)token * d + r0);
     if (accumulate) {
       const float4 v = *o;
-      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
     }
-    *o = t;
+    *o = a;
   }
 }
 
@@ -985,7 +988,7 @@ hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const De
 
 hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_t T, int accumulate, float* y,
                                   hipStream_t st) {
-  hipLaunchKernelGGL(k_reduce_partials, dim3((d + 63) / 64, T), dim3(256), 0, st, part, n_slices, d, accumulate, y);
+  hipLaunchKernelGGL(k_reduce_partials, dim3((d + 15) / 16, T), dim3(256), 0, st, part, n_slices, d, accumulate, y);
   return hipGetLastError();
 }
 
