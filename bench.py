@@ -19,6 +19,12 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by
+# what the counter reads for a plain pass over 1 GiB: factors 2.000 and 1.000), mean over the dispatches of
+# `bench.py --no-extras --no-cpu-baseline --no-graph --layers 4 --steps 6 --warmup 2`, whose algorithmic bytes
+# per launch are 130.4 MB. The summary with the commands is profiles/c4_decode_pmc.md.
+PMC_TRAFFIC_C4 = {"fetch_bytes": 134.5e6, "write_bytes": 3.67e6, "algorithmic_bytes_same_slice": 130.4e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -370,7 +376,9 @@ def main():
                                 else "k_ffn_in (phase 1: top-k + dequantize-fused W_in/W_gate GEMVs)"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": res["kernel_bytes"], "avg_launch_ms": res["kernel_ms"],
-                     "traffic": None},
+                     "traffic": (PMC_TRAFFIC_C4["fetch_bytes"] + PMC_TRAFFIC_C4["write_bytes"])
+                     if (name == "c4" and columns) else None,
+                     "traffic_detail": PMC_TRAFFIC_C4 if (name == "c4" and columns) else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stack, dev, 4 if name == "c4" else 12)
