@@ -60,6 +60,14 @@ __device__ __forceinline__ uint2 gload_u32x2(const uint8_t* ptr) {
   return make_uint2(v.x, v.y);
 }
 
+// v / group for a per-lane v: a shift when the group size is a power of two (gsh = its log2, else -1), the
+// (40-instruction) division otherwise. gsh is uniform, so this is a branch, not a select.
+__device__ __forceinline__ int group_shift(int group) { return (group & (group - 1)) == 0 ? __builtin_ctz(group) : -1; }
+__device__ __forceinline__ uint32_t div_group(uint32_t v, int group, int gsh) {
+  if (gsh >= 0) return v >> gsh;
+  return v / (uint32_t)group;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float v) { return (uint32_t)__half_as_ushort(__float2half_rn(v)); }
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t h) { return __half2float(__ushort_as_half((uint16_t)h)); }
@@ -365,6 +373,7 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
   const int jb = (part * Jfull) / ks_parts;
   const int J = (wave < nwaves) ? ((part + 1) * Jfull) / ks_parts - jb : 0;
   const int ng = cols / group;
+  const int gsh = group_shift(group);
   const int task_rows = RW * NRM;
   const int n_tasks = (row_end - row_begin + task_rows - 1) / task_rows;
   const int n_my = (wave < nwaves && tw < n_tasks) ? (n_tasks - tw + wpp - 1) / wpp : 0;
@@ -387,7 +396,7 @@ __device__ __forceinline__ void gemv_stream(const uint8_t* const (&q)[NM], const
         soff[v] = ((uint32_t)row * (uint32_t)ng) * 2u;
       }
     }
-    const uint32_t g0 = ((uint32_t)((p + (jb + pj) * P) * WPC) / (uint32_t)group) * 2u;
+    const uint32_t g0 = div_group((uint32_t)((p + (jb + pj) * P) * WPC), group, gsh) * 2u;
 #pragma unroll
     for (int v = 0; v < NR; ++v) {
       const int m = v / NRM;

@@ -107,6 +107,7 @@ __device__ __forceinline__ void p1_stream(const uint8_t* const (&q)[NM], const u
   const int p = lane & (P - 1), rsub = lane / P;
   const uint32_t row_bytes = (uint32_t)C * 16u;
   const uint32_t ng2 = (uint32_t)(d / group) * 2u;
+  const int gsh = group_shift(group);
   const bool two = (BITS == 2) && (group == 32);
   const uint4* XP4 = (const uint4*)XP;
 
@@ -123,7 +124,7 @@ __device__ __forceinline__ void p1_stream(const uint8_t* const (&q)[NM], const u
 #pragma unroll
       for (int jj = 0; jj < JC; ++jj) {
         const uint32_t c = (uint32_t)(p + (j0 + jj) * P);
-        const uint32_t g0 = (c * (uint32_t)WPC / (uint32_t)group) * 2u;
+        const uint32_t g0 = div_group(c * (uint32_t)WPC, group, gsh) * 2u;
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
           B.t[i][jj][m] = load_stream16(q[m] + (qoff + (uint32_t)(j0 + jj) * (uint32_t)P * 16u));
@@ -413,6 +414,7 @@ __device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uin
   const int dsel = m & 3;
   const uint32_t row_bytes = (uint32_t)C * 16u;
   const uint32_t ng2 = (uint32_t)(d / group) * 2u;
+  const int gsh = group_shift(group);
   const uint4* XP4 = (const uint4*)XP;
   // rows of this wavefront: a contiguous run, walked from a workgroup-dependent start
   const int rpw = (n_rows + nwaves - 1) / nwaves;
@@ -435,7 +437,7 @@ __device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uin
 #pragma unroll
     for (int jj = 0; jj < JC; ++jj) {
       const uint32_t j = (uint32_t)(j0 + jj);
-      const uint32_t g0 = ((j * (uint32_t)TCOLS + lane_col) / (uint32_t)group) * 2u;
+      const uint32_t g0 = div_group(j * (uint32_t)TCOLS + lane_col, group, gsh) * 2u;
 #pragma unroll
       for (int mm = 0; mm < NM; ++mm) {
         const uint8_t* src = q[mm] + (row * row_bytes + j * TBYTES + lane_off);

@@ -130,6 +130,7 @@ def test_router_exact_ties_go_to_lowest_index():
 @pytest.mark.parametrize("bits", (2, 4, 8))
 @pytest.mark.parametrize("base,d,f,g,T", [
     ("c1", 768, 3072, 32, 1),      # Switch-base expert, full size
+    ("c1", 768, 3072, 768, 2),     # one scale per row of wi (the paper's per-channel granularity), 4 per row of wo
     ("c1", 192, 320, 32, 3),       # short ragged rows (3 / 6 / 12 chunks per row)
     ("c3", 1024, 4096, 64, 2),     # Switch-large expert, full size
     ("c4", 512, 1792, 128, 2),     # SwiGLU, Mixtral-like 7 * 2^k row length
