@@ -448,6 +448,9 @@ __device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uin
     }
   };
   float acc[NM];
+  float racc[NM * 4];
+#pragma unroll
+  for (int v = 0; v < NM * 4; ++v) racc[v] = 0.f;
   auto compute = [&](const Set& S, int b) __attribute__((always_inline)) {
     const int j0 = (b % JB) * JC;
     if (j0 == 0) {
@@ -499,10 +502,25 @@ __device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uin
       }
     }
     if (j0 + JC == J) {
-      float r[NM];
+      // the row is done: park its partial sums; every four rows (and at the end) one transposing fold sums
+      // all parked rows across the wavefront and four lanes finish one row each
+      const int ri = b / JB, slot = ri & 3;
 #pragma unroll
-      for (int mm = 0; mm < NM; ++mm) r[mm] = wave_sum(acc[mm]) * 16777216.0f;
-      if (lane == 0) epilogue(row_begin + row_of(b), r);
+      for (int mm = 0; mm < NM; ++mm)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) racc[mm * 4 + q4] = slot == q4 ? acc[mm] : racc[mm * 4 + q4];
+      if (slot == 3 || ri == my_rows - 1) {
+        fold_rows<4, NM>(racc, 64, lane);
+        const int rj = (ri & ~3) + (lane & 3);
+        if (lane < 4 && rj <= ri) {
+          float r[NM];
+#pragma unroll
+          for (int mm = 0; mm < NM; ++mm) r[mm] = racc[mm * 4] * 16777216.0f;
+          epilogue(row_begin + r_begin + (rj + rot < my_rows ? rj + rot : rj + rot - my_rows), r);
+        }
+#pragma unroll
+        for (int v = 0; v < NM * 4; ++v) racc[v] = 0.f;
+      }
     }
   };
 
