@@ -399,68 +399,76 @@ constexpr int kMxSlice = 64;   // slice width of the matrix-core variant
 // the useful results are the diagonal m == n (16 group dot products per instruction chain), found in lane
 // n + 16*(n/4), element n%4. Each diagonal lane scales its group's dot product with its own group scale
 // and accumulates; a wavefront sum per row finishes the dot product.
-template <int BITS, int NM, int JC, typename Epilogue>
-__device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uint8_t* const (&s)[NM], int d, int group,
-                                        int row_begin, int n_rows, int lane, int wave, int nwaves,
-                                        const uint32_t* XP, const float* XK, Epilogue epilogue) {
-  constexpr int WPC = 128 / BITS;
-  constexpr int TCOLS = BITS == 8 ? 1024 : 2048;        // columns of a tile
-  using TileT = std::conditional_t<BITS == 2, uint2, uint4>;
-  struct Set { TileT t[JC][NM]; uint32_t sc[JC][NM]; };
-  const int C = d / WPC;
-  const int J = d / TCOLS, JB = J / JC;                 // tiles per row, bursts per row
-  const int m = lane & 15, kb = lane >> 4;              // lane column (B operand) = group row (A operand)
-  const bool diag = kb == (m >> 2);
-  const int dsel = m & 3;
-  const uint32_t row_bytes = (uint32_t)C * 16u;
-  const uint32_t ng2 = (uint32_t)(d / group) * 2u;
-  const int gsh = group_shift(group);
-  const uint4* XP4 = (const uint4*)XP;
-  // rows of this wavefront: a contiguous run, walked from a workgroup-dependent start
-  const int rpw = (n_rows + nwaves - 1) / nwaves;
-  const int r_begin = wave * rpw;
-  const int my_rows = max(0, min(rpw, n_rows - r_begin));
-  const int rot = my_rows > 0 ? (int)blockIdx.x % my_rows : 0;
-  const int nb = my_rows * JB;
-  // lane's byte offset inside a tile, and the first column of its piece
-  const uint32_t lane_off = BITS == 2 ? (uint32_t)(32 * m + 8 * kb) : (uint32_t)(4 * m + kb) * 16u;
-  const uint32_t lane_col = BITS == 2 ? (uint32_t)(128 * m) : (uint32_t)(4 * m + kb) * (uint32_t)WPC;
-  constexpr uint32_t TBYTES = BITS == 2 ? 512u : 1024u;
+//
+// A wavefront owns a run of rows of the slice and walks ONE list of bursts (a burst = up to two tiles of
+// each matrix of a row) that goes through all chosen experts: expert, then row, then burst of the row.
+// Two register sets alternate, the loads of the next burst are issued before the arithmetic of the
+// current one, and since the list does not stop at the change of expert the loads never drain there.
+struct MxSet1 { uint4 t[2][2]; uint32_t sc[2][2]; };   // [tile of the burst][matrix]
 
-  auto row_of = [&](int b) __attribute__((always_inline)) {
-    const int ri = b / JB;
-    return r_begin + (ri + rot < my_rows ? ri + rot : ri + rot - my_rows);
-  };
-  auto issue = [&](Set& S, int b) __attribute__((always_inline)) {
-    const int j0 = (b % JB) * JC;
-    const uint32_t row = (uint32_t)(row_begin + row_of(b));
+struct MxWalk1 {          // a position in the wavefront's burst list, and what the bursts of that expert need
+  int j, ri, jb;          // expert slot, row among the wavefront's rows, burst of the row
+  int bits, JB;           // of the expert at slot j: its bitwidth and bursts per row
+  // for the loads only: the same instructions serve every bitwidth, the differences are in these values
+  const uint8_t* q[2];
+  const uint8_t* s[2];
+  uint32_t row_bytes, tile_bytes, tile_groups2;   // bytes of a row, of a tile; 2 * scale groups of a tile
+  uint32_t lane_off, lane_g2;                     // per lane: byte offset in a tile, 2 * group of its piece in a tile
+};
+
+template <bool SWIGLU>
+__device__ __forceinline__ void mx1_enter(MxWalk1& w, const DevExpert* ex, int d, int gsh, int lane) {
+  w.bits = __builtin_amdgcn_readfirstlane(ex->bits);
+  w.JB = d / (w.bits == 8 ? 2048 : 4096);
+  w.q[0] = uniform_ptr(ex->q_in);
+  w.s[0] = (const uint8_t*)uniform_ptr(ex->s_in);
+  if constexpr (SWIGLU) {
+    w.q[1] = uniform_ptr(ex->q_gate);
+    w.s[1] = (const uint8_t*)uniform_ptr(ex->s_gate);
+  } else {
+    w.q[1] = w.q[0];
+    w.s[1] = w.s[0];
+  }
+  const int m = lane & 15, kb = lane >> 4;
+  w.row_bytes = (uint32_t)d * (uint32_t)w.bits / 8u;
+  w.tile_bytes = w.bits == 2 ? 512u : 1024u;
+  w.tile_groups2 = ((w.bits == 8 ? 1024u : 2048u) >> gsh) * 2u;
+  // 2-bit codes: the lane's piece is 8 bytes at 32*m + 8*kb; it reads the aligned 16 bytes that hold it
+  w.lane_off = w.bits == 2 ? (uint32_t)(32 * m + 16 * (kb >> 1)) : (uint32_t)(4 * m + kb) * 16u;
+  const uint32_t lane_col = w.bits == 2 ? (uint32_t)(128 * m) : (uint32_t)(4 * m + kb) * (128u / (uint32_t)w.bits);
+  w.lane_g2 = (lane_col >> gsh) * 2u;
+}
+
+// Requests the burst at w: two tiles of each matrix and the scales of the lane's pieces. ng2 = bytes of a
+// row of scales.
+template <int NM>
+__device__ __forceinline__ void mx1_issue(MxSet1& S, const MxWalk1& w, uint32_t row, uint32_t ng2) {
+  const uint32_t t0 = (uint32_t)w.jb * 2u;
+  const uint32_t qoff = row * w.row_bytes + t0 * w.tile_bytes + w.lane_off;
+  const uint32_t soff = row * ng2 + t0 * w.tile_groups2 + w.lane_g2;
 #pragma unroll
-    for (int jj = 0; jj < JC; ++jj) {
-      const uint32_t j = (uint32_t)(j0 + jj);
-      const uint32_t g0 = div_group(j * (uint32_t)TCOLS + lane_col, group, gsh) * 2u;
+  for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-      for (int mm = 0; mm < NM; ++mm) {
-        const uint8_t* src = q[mm] + (row * row_bytes + j * TBYTES + lane_off);
-        if constexpr (BITS == 2) S.t[jj][mm] = gload_u32x2_nt(src);
-        else S.t[jj][mm] = load_stream16(src);
-        S.sc[jj][mm] = gload_u16(s[mm] + (row * ng2 + g0));
-      }
+    for (int mm = 0; mm < NM; ++mm) {
+      S.t[jj][mm] = load_stream16(w.q[mm] + (qoff + (jj ? w.tile_bytes : 0u)));
+      S.sc[jj][mm] = gload_u16(w.s[mm] + (soff + (jj ? w.tile_groups2 : 0u)));
     }
-  };
-  float acc[NM];
-  float racc[NM * 4];
+}
+
+// The arithmetic of one burst: adds the lane's share of the row's dot products to acc. dm[i] is 1 in the
+// lane that holds a diagonal result in element i, else 0.
+template <int BITS, int NM>
+__device__ __forceinline__ void mx1_burst(const MxSet1& S, const MxWalk1& w, int d, int lane, const float (&dm)[4],
+                                          const uint4* XP4, const float* XK, float (&acc)[NM]) {
+  constexpr int WPC = 128 / BITS;
+  const int C = d / WPC;
+  const int m = lane & 15, kb = lane >> 4;
+  const bool diag = kb == (m >> 2);
+  const float4_t zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int v = 0; v < NM * 4; ++v) racc[v] = 0.f;
-  auto compute = [&](const Set& S, int b) __attribute__((always_inline)) {
-    const int j0 = (b % JB) * JC;
-    if (j0 == 0) {
-#pragma unroll
-      for (int mm = 0; mm < NM; ++mm) acc[mm] = 0.f;
-    }
-    const float4_t zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int jj = 0; jj < JC; ++jj) {
-      const int j = j0 + jj;
+  for (int jj = 0; jj < 2; ++jj) {
+    {
+      const int j = w.jb * 2 + jj;
       float4_t D[NM];
 #pragma unroll
       for (int mm = 0; mm < NM; ++mm) D[mm] = zero;
@@ -475,7 +483,9 @@ __device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uin
             const half8_t A = as_half8(XP4[(2 * (2 * (kb & 1) + t) + hh) * C + 32 * j + 2 * m + (kb >> 1)]);
 #pragma unroll
             for (int mm = 0; mm < NM; ++mm) {
-              const uint32_t dw = t ? S.t[jj][mm].y : S.t[jj][mm].x;
+              // the lane's 8 bytes are the upper half of the 16 loaded ones when kb is odd
+              const uint4 wd = S.t[jj][mm];
+              const uint32_t dw = t ? ((kb & 1) ? wd.w : wd.y) : ((kb & 1) ? wd.z : wd.x);
               D[mm] = mfma16(A, hh ? codes8<2, 1>(dw, 0u) : codes8<2, 0>(dw, 0u), D[mm]);
             }
           }
@@ -488,160 +498,161 @@ __device__ __forceinline__ void p1_mfma(const uint8_t* const (&q)[NM], const uin
           const half8_t A = as_half8(XP4[i * C + 64 * j + 4 * m + kb]);
 #pragma unroll
           for (int mm = 0; mm < NM; ++mm) {
-            const uint4 w = S.t[jj][mm];
-            if constexpr (BITS == 4) D[mm] = mfma16(A, codes8<4, 0>(i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w, 0u), D[mm]);
-            else D[mm] = mfma16(A, i == 0 ? codes8<8, 0>(w.x, w.y) : codes8<8, 0>(w.z, w.w), D[mm]);
+            const uint4 wd = S.t[jj][mm];
+            if constexpr (BITS == 4) D[mm] = mfma16(A, codes8<4, 0>(i == 0 ? wd.x : i == 1 ? wd.y : i == 2 ? wd.z : wd.w, 0u), D[mm]);
+            else D[mm] = mfma16(A, i == 0 ? codes8<8, 0>(wd.x, wd.y) : codes8<8, 0>(wd.z, wd.w), D[mm]);
           }
         }
       }
+      const float Kd = diag ? K : 0.f;
 #pragma unroll
       for (int mm = 0; mm < NM; ++mm) {
-        const float dv = dsel == 0 ? D[mm][0] : dsel == 1 ? D[mm][1] : dsel == 2 ? D[mm][2] : D[mm][3];
-        const float contrib = f16_bits_to_f32(S.sc[jj][mm]) * (dv - K);
-        acc[mm] += diag ? contrib : 0.f;
+        // exactly one of the four products is non-zero in a diagonal lane, none elsewhere
+        const float dv = fmaf(D[mm][3], dm[3], fmaf(D[mm][2], dm[2], fmaf(D[mm][1], dm[1], D[mm][0] * dm[0])));
+        acc[mm] = fmaf(f16_bits_to_f32(S.sc[jj][mm]), dv - Kd, acc[mm]);
       }
     }
-    if (j0 + JC == J) {
-      // the row is done: park its partial sums; every four rows (and at the end) one transposing fold sums
-      // all parked rows across the wavefront and four lanes finish one row each
-      const int ri = b / JB, slot = ri & 3;
-#pragma unroll
-      for (int mm = 0; mm < NM; ++mm)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) racc[mm * 4 + q4] = slot == q4 ? acc[mm] : racc[mm * 4 + q4];
-      if (slot == 3 || ri == my_rows - 1) {
-        fold_rows<4, NM>(racc, 64, lane);
-        const int rj = (ri & ~3) + (lane & 3);
-        if (lane < 4 && rj <= ri) {
-          float r[NM];
-#pragma unroll
-          for (int mm = 0; mm < NM; ++mm) r[mm] = racc[mm * 4] * 16777216.0f;
-          epilogue(row_begin + r_begin + (rj + rot < my_rows ? rj + rot : rj + rot - my_rows), r);
-        }
-#pragma unroll
-        for (int v = 0; v < NM * 4; ++v) racc[v] = 0.f;
-      }
-    }
-  };
-
-  Set A, B;
-  if (nb > 0) issue(A, 0);
-  for (int b = 0; b < nb; b += 2) {
-    if (b + 1 < nb) issue(B, b + 1);
-    compute(A, b);
-    if (b + 2 < nb) issue(A, b + 2);
-    if (b + 1 < nb) compute(B, b + 1);
   }
 }
 
+// Activation and store of h for the slice column c of one expert: linear for the offset term of phase 2,
+// and in the pair layout of the expert's bitwidth for its dot products.
+template <int BITS, bool SWIGLU, int NM>
+__device__ __forceinline__ void mx1_store_h(int c, const float (&r)[NM], uint16_t* HL, uint16_t* HP) {
+  float v;
+  if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
+  else v = fmaxf(r[0], 0.f);
+  const uint32_t hb = f32_to_f16_bits(v);
+  HL[c] = (uint16_t)hb;
+  float ps;
+  const int si = slice_pair_index<BITS>(c, ps);
+  HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+}
+
+// One burst at the position w of the list: the arithmetic, and, when it completes a row, the sum of the
+// lanes' shares over the wavefront, after which one lane applies the activation.
 template <int BITS, bool SWIGLU>
-__device__ __forceinline__ void fused_in_mfma(const DevExpert* ex, int tid, int nwaves, int d, int group, int row_begin,
-                                              int SW, uint16_t* HL, uint16_t* HP, const uint32_t* XP, const float* XK) {
+__device__ __forceinline__ void mx1_compute(const MxSet1& S, const MxWalk1& w, int d, int lane, const float (&dm)[4],
+                                            const uint32_t* XP, const float* XK, int r_begin, int my_rows, int rot,
+                                            uint16_t* HL, uint16_t* HP, float (&acc)[SWIGLU ? 2 : 1]) {
   constexpr int NM = SWIGLU ? 2 : 1;
-  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  auto epi = [&](int row, const float (&r)[NM]) __attribute__((always_inline)) {
-    float v;
-    if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
-    else v = fmaxf(r[0], 0.f);
-    const uint32_t hb = f32_to_f16_bits(v);
-    const int c = row - row_begin;
-    HL[c] = (uint16_t)hb;
-    float ps;
-    const int si = slice_pair_index<BITS>(c, ps);
-    HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
-  };
-  const uint8_t* q0 = uniform_ptr(ex->q_in);
-  const uint8_t* s0 = (const uint8_t*)uniform_ptr(ex->s_in);
-  const int J = d / (BITS == 8 ? 1024 : 2048);
-  auto run = [&](auto jc_tag) __attribute__((always_inline)) {
-    constexpr int JC = decltype(jc_tag)::value;
-    if constexpr (SWIGLU) {
-      const uint8_t* const qq[2] = {q0, uniform_ptr(ex->q_gate)};
-      const uint8_t* const ss[2] = {s0, (const uint8_t*)uniform_ptr(ex->s_gate)};
-      p1_mfma<BITS, 2, JC>(qq, ss, d, group, row_begin, SW, lane, wave, nwaves, XP, XK, epi);
-    } else {
-      const uint8_t* const qq[1] = {q0};
-      const uint8_t* const ss[1] = {s0};
-      p1_mfma<BITS, 1, JC>(qq, ss, d, group, row_begin, SW, lane, wave, nwaves, XP, XK, epi);
-    }
-  };
-  if (J % 2 == 0) run(std::integral_constant<int, 2>{});
-  else run(std::integral_constant<int, 1>{});
+  if (w.jb == 0) {
+#pragma unroll
+    for (int mm = 0; mm < NM; ++mm) acc[mm] = 0.f;
+  }
+  mx1_burst<BITS, NM>(S, w, d, lane, dm, (const uint4*)XP, XK, acc);
+  if (w.jb + 1 == w.JB) {
+    float r[NM];
+#pragma unroll
+    for (int mm = 0; mm < NM; ++mm) r[mm] = wave_sum(acc[mm]) * 16777216.0f;
+    if (lane == 0)
+      mx1_store_h<BITS, SWIGLU, NM>(r_begin + (w.ri + rot < my_rows ? w.ri + rot : w.ri + rot - my_rows), r, HL, HP);
+  }
 }
 
 // Phase 2 on the matrix cores: a wavefront takes groups of 64 output rows; lane (n, kb) loads the 16-byte
 // tile with word column 4*step + kb (8-bit codes: the word columns 8*step + 2*kb and + 1) of the rows
 // 64*g + 4*n .. + 3, and instruction i multiplies row 4*n + i of every lane (here all A-operand rows
 // carry the same activations and the result for row n of the instruction arrives in lane n, element 0).
-// Register sets hold the tiles of GPS row groups; the first set is requested by the caller before the
+// A register set holds four tiles: the tiles of GPS row groups. As in phase 1 the wavefront walks one
+// list of sets through all chosen experts with two register sets; the first set is requested before the
 // barrier that completes h.
+struct MxSet2 { uint4 t[4]; uint2 sc[4]; };
+
 template <int BITS>
 struct P2Mx {
   static constexpr int DW = kMxSlice * BITS / 32;                   // word columns of a slice: 4 / 8 / 16
   static constexpr int TPR = BITS == 2 ? 1 : (BITS == 4 ? 2 : 4);   // tiles per row group and lane
   static constexpr int GPS = 4 / TPR;                               // row groups per register set
-  uint4 t[GPS][TPR];
-  uint2 sc[GPS];
 };
 
-// Row groups of a set: wave + (set * GPS + i) * nwaves.
-template <int BITS>
-__device__ __forceinline__ void p2_mfma_issue(P2Mx<BITS>& S, const uint8_t* qT_s, const uint8_t* sT_g, int d, int set,
-                                              int lane, int wave, int nwaves) {
+struct MxWalk2 {
+  int j, set, n_sets, bits;      // expert slot, set of the expert, its number of sets
+  // for the loads only (one instruction sequence for every bitwidth):
+  const uint8_t* qT_s;           // the slice's first word column of the expert's W_out
+  const uint8_t* sT_g;           // the slice's scale row
+  uint32_t slot_q[4], slot_s[4]; // byte offsets of the four tiles / scale vectors of a set
+  uint32_t set_q, set_s;         // byte strides from set to set
+  uint32_t lane_q, lane_s;       // per lane
+};
+
+__device__ __forceinline__ void mx2_enter(MxWalk2& w, const DevExpert* ex, int d, int slice, int gsh, int lane,
+                                          int wave, int nwaves) {
+  w.bits = __builtin_amdgcn_readfirstlane(ex->bits);
+  const int dw = kMxSlice * w.bits / 32;
+  const int tpr = w.bits == 2 ? 1 : (w.bits == 4 ? 2 : 4), gps = 4 / tpr;
+  w.qT_s = uniform_ptr(ex->q_out) + (size_t)(slice * dw) * ((size_t)d * 4);
+  w.sT_g = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)((slice * kMxSlice) >> gsh) * ((size_t)d * 2);
+  w.n_sets = d / (64 * gps * nwaves);
+  w.set = 0;
   const int n = lane & 15, kb = lane >> 4;
+  const uint32_t col_bytes = (uint32_t)d * 4u;           // bytes of a word column
 #pragma unroll
-  for (int i = 0; i < P2Mx<BITS>::GPS; ++i) {
-    const int g = wave + (set * P2Mx<BITS>::GPS + i) * nwaves;
-    if (g < d / 64) {
-      const uint32_t roff = (uint32_t)(64 * g + 4 * n) * 4u;
+  for (int sl = 0; sl < 4; ++sl) {
+    const int i = sl / tpr, tt = sl - i * tpr;           // row group of the set, tile of the row group
+    const int wc = w.bits == 8 ? 8 * (tt >> 1) + (tt & 1) : 4 * tt;
+    w.slot_q[sl] = (uint32_t)wc * col_bytes + (uint32_t)(i * nwaves) * 256u;
+    w.slot_s[sl] = (uint32_t)((sl % gps) * nwaves) * 128u;   // slots past the set's row groups repeat one
+  }
+  w.set_q = (uint32_t)(gps * nwaves) * 256u;
+  w.set_s = (uint32_t)(gps * nwaves) * 128u;
+  w.lane_q = (uint32_t)(w.bits == 8 ? 2 * kb : kb) * col_bytes + (uint32_t)(64 * wave + 4 * n) * 4u;
+  w.lane_s = (uint32_t)(64 * wave + 4 * n) * 2u;
+}
+
+// Row groups of a set: wave + (set * GPS + i) * nwaves, all below d / 64 (the plan makes d / 64 a multiple
+// of 4 * nwaves).
+__device__ __forceinline__ void mx2_issue(MxSet2& S, const MxWalk2& w) {
+  const uint32_t q0 = w.lane_q + (uint32_t)w.set * w.set_q;
+  const uint32_t s0 = w.lane_s + (uint32_t)w.set * w.set_s;
 #pragma unroll
-      for (int tt = 0; tt < P2Mx<BITS>::TPR; ++tt) {
-        const int w = BITS == 8 ? 8 * (tt >> 1) + 2 * kb + (tt & 1) : 4 * tt + kb;
-        S.t[i][tt] = load_stream16(qT_s + (size_t)w * ((size_t)d * 4) + roff);
-      }
-      S.sc[i] = gload_u32x2(sT_g + (uint32_t)(64 * g + 4 * n) * 2u);
-    }
+  for (int sl = 0; sl < 4; ++sl) {
+    S.t[sl] = load_stream16(w.qT_s + (q0 + w.slot_q[sl]));
+    S.sc[sl] = gload_u32x2(w.sT_g + (s0 + w.slot_s[sl]));
   }
 }
 
 template <int BITS>
-__device__ __forceinline__ void p2_mfma_compute(const P2Mx<BITS>& S, int d, int set, int lane, int wave, int nwaves,
-                                                const uint4* HP4, float K, float g24, bool first_expert, float4* Y) {
+__device__ __forceinline__ void mx2_compute(const MxSet2& S, const MxWalk2& w, int d, int lane, int wave, int nwaves,
+                                            const uint4* HP4, float K, float g24, float4* Y) {
+  constexpr int TPR = P2Mx<BITS>::TPR, GPS = P2Mx<BITS>::GPS;
   const int n = lane & 15, kb = lane >> 4;
   const float4_t zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int i = 0; i < P2Mx<BITS>::GPS; ++i) {
-    const int g = wave + (set * P2Mx<BITS>::GPS + i) * nwaves;
-    if (g < d / 64) {
+  for (int i = 0; i < GPS; ++i) {
+    const int g = wave + (w.set * GPS + i) * nwaves;
+    {
       float4_t D[4] = {zero, zero, zero, zero};
       if constexpr (BITS == 4) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const half8_t A = as_half8(HP4[4 * tt + kb]);
-          D[0] = mfma16(A, codes8<4, 0>(S.t[i][tt].x, 0u), D[0]);
-          D[1] = mfma16(A, codes8<4, 0>(S.t[i][tt].y, 0u), D[1]);
-          D[2] = mfma16(A, codes8<4, 0>(S.t[i][tt].z, 0u), D[2]);
-          D[3] = mfma16(A, codes8<4, 0>(S.t[i][tt].w, 0u), D[3]);
+          const uint4 t = S.t[i * TPR + tt];
+          D[0] = mfma16(A, codes8<4, 0>(t.x, 0u), D[0]);
+          D[1] = mfma16(A, codes8<4, 0>(t.y, 0u), D[1]);
+          D[2] = mfma16(A, codes8<4, 0>(t.z, 0u), D[2]);
+          D[3] = mfma16(A, codes8<4, 0>(t.w, 0u), D[3]);
         }
       } else if constexpr (BITS == 2) {
         const half8_t A0 = as_half8(HP4[2 * kb]), A1 = as_half8(HP4[2 * kb + 1]);
-        const uint4 w = S.t[i][0];
-        D[0] = mfma16(A0, codes8<2, 0>(w.x, 0u), D[0]); D[0] = mfma16(A1, codes8<2, 1>(w.x, 0u), D[0]);
-        D[1] = mfma16(A0, codes8<2, 0>(w.y, 0u), D[1]); D[1] = mfma16(A1, codes8<2, 1>(w.y, 0u), D[1]);
-        D[2] = mfma16(A0, codes8<2, 0>(w.z, 0u), D[2]); D[2] = mfma16(A1, codes8<2, 1>(w.z, 0u), D[2]);
-        D[3] = mfma16(A0, codes8<2, 0>(w.w, 0u), D[3]); D[3] = mfma16(A1, codes8<2, 1>(w.w, 0u), D[3]);
+        const uint4 t = S.t[i];
+        D[0] = mfma16(A0, codes8<2, 0>(t.x, 0u), D[0]); D[0] = mfma16(A1, codes8<2, 1>(t.x, 0u), D[0]);
+        D[1] = mfma16(A0, codes8<2, 0>(t.y, 0u), D[1]); D[1] = mfma16(A1, codes8<2, 1>(t.y, 0u), D[1]);
+        D[2] = mfma16(A0, codes8<2, 0>(t.z, 0u), D[2]); D[2] = mfma16(A1, codes8<2, 1>(t.z, 0u), D[2]);
+        D[3] = mfma16(A0, codes8<2, 0>(t.w, 0u), D[3]); D[3] = mfma16(A1, codes8<2, 1>(t.w, 0u), D[3]);
       } else {
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
           const half8_t A = as_half8(HP4[4 * st + kb]);
-          D[0] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].x, S.t[i][2 * st + 1].x), D[0]);
-          D[1] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].y, S.t[i][2 * st + 1].y), D[1]);
-          D[2] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].z, S.t[i][2 * st + 1].z), D[2]);
-          D[3] = mfma16(A, codes8<8, 0>(S.t[i][2 * st].w, S.t[i][2 * st + 1].w), D[3]);
+          const uint4 t0 = S.t[2 * st], t1 = S.t[2 * st + 1];
+          D[0] = mfma16(A, codes8<8, 0>(t0.x, t1.x), D[0]);
+          D[1] = mfma16(A, codes8<8, 0>(t0.y, t1.y), D[1]);
+          D[2] = mfma16(A, codes8<8, 0>(t0.z, t1.z), D[2]);
+          D[3] = mfma16(A, codes8<8, 0>(t0.w, t1.w), D[3]);
         }
       }
       if (lane < 16) {
-        float4 y = first_expert ? make_float4(0.f, 0.f, 0.f, 0.f) : Y[16 * g + n];
+        float4 y = w.j == 0 ? make_float4(0.f, 0.f, 0.f, 0.f) : Y[16 * g + n];
         y.x = fmaf(f16_bits_to_f32(S.sc[i].x & 0xffffu) * g24, D[0][0] - K, y.x);
         y.y = fmaf(f16_bits_to_f32(S.sc[i].x >> 16) * g24, D[1][0] - K, y.y);
         y.z = fmaf(f16_bits_to_f32(S.sc[i].y & 0xffffu) * g24, D[2][0] - K, y.z);
@@ -649,29 +660,6 @@ __device__ __forceinline__ void p2_mfma_compute(const P2Mx<BITS>& S, int d, int 
         Y[16 * g + n] = y;
       }
     }
-  }
-}
-
-// Phase 2 of one expert; `first` holds the wavefront's first set (already requested).
-template <int BITS>
-__device__ __forceinline__ void fused_out_mfma(P2Mx<BITS>& first, const uint8_t* qT_s, const uint8_t* sT_g, int tid,
-                                               int nwaves, int d, float gate, bool first_expert,
-                                               const uint16_t* HL, const uint16_t* HP, float4* Y) {
-  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float hs = f16_bits_to_f32(HL[lane]);            // kMxSlice == 64: one activation per lane
-  hs = wave_sum(hs);
-  const float K = hs * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
-  const float g24 = gate * 16777216.0f;
-  const uint4* HP4 = (const uint4*)HP;
-  const int RG = d / 64;
-  const int per_set = P2Mx<BITS>::GPS * nwaves;
-  const int n_sets = (RG + per_set - 1) / per_set;
-  P2Mx<BITS> other;
-  for (int st = 0; st < n_sets; st += 2) {
-    if (st + 1 < n_sets) p2_mfma_issue<BITS>(other, qT_s, sT_g, d, st + 1, lane, wave, nwaves);
-    p2_mfma_compute<BITS>(first, d, st, lane, wave, nwaves, HP4, K, g24, first_expert, Y);
-    if (st + 2 < n_sets) p2_mfma_issue<BITS>(first, qT_s, sT_g, d, st + 2, lane, wave, nwaves);
-    if (st + 1 < n_sets) p2_mfma_compute<BITS>(other, d, st + 1, lane, wave, nwaves, HP4, K, g24, first_expert, Y);
   }
 }
 
@@ -784,44 +772,130 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   }
 
   if constexpr (MX) {
-    // ---- phase 1 of every chosen expert on the matrix cores, back to back
+    constexpr int NM = SWIGLU ? 2 : 1;
+    const DevExpert* tabp = tab_in_lds ? tab : P.table;
+    const int gsh = __builtin_ctz((unsigned)L.group);           // the plan admits powers of two only
+    const int m16 = lane & 15, kb4 = lane >> 4;
+    float dm[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dm[i] = (kb4 == (m16 >> 2) && (m16 & 3) == i) ? 1.f : 0.f;
+    // ---- phase 1: the wavefront's rows of the slice, a contiguous run walked from a workgroup-dependent
+    // start, for every chosen expert in one list of bursts
+    const int my_rows = SW / nwaves;                            // the plan makes nwaves divide the slice width
+    const int r_begin = wave * my_rows;
+    const int rot = slice % my_rows;
+    const uint32_t row0 = (uint32_t)(slice * SW + r_begin);
+    const uint32_t ng2 = (uint32_t)(d >> gsh) * 2u;
+    int nb = 0;
     for (int j = 0; j < k; ++j) {
-      const int e = sel_e[j];
-      const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
-      const int bits = __builtin_amdgcn_readfirstlane(ex->bits);
-      const uint32_t* XP = LAY + layout_slot(P.bits_mask, bits) * lay_words;
+      const int bits = __builtin_amdgcn_readfirstlane(tabp[sel_e[j]].bits);
+      nb += my_rows * (d / (bits == 8 ? 2048 : 4096));
+    }
+    MxWalk1 wi, wc;
+    wi.j = wi.ri = wi.jb = 0;
+    mx1_enter<SWIGLU>(wi, tabp + sel_e[0], d, gsh, lane);
+    wc = wi;
+    auto advance = [&](MxWalk1& w) __attribute__((always_inline)) {
+      if (++w.jb == w.JB) {
+        w.jb = 0;
+        if (++w.ri == my_rows) {
+          w.ri = 0;
+          if (++w.j < k) mx1_enter<SWIGLU>(w, tabp + sel_e[w.j], d, gsh, lane);
+        }
+      }
+    };
+    auto issue = [&](MxSet1& S) __attribute__((always_inline)) {
+      const uint32_t row = row0 + (uint32_t)(wi.ri + rot < my_rows ? wi.ri + rot : wi.ri + rot - my_rows);
+      mx1_issue<NM>(S, wi, row, ng2);
+      advance(wi);
+    };
+    float acc[NM];
+    auto compute = [&](const MxSet1& S) __attribute__((always_inline)) {
+      const uint32_t* XP = LAY + layout_slot(P.bits_mask, wc.bits) * lay_words;
       const float* XK = (const float*)(XP + d / 2);
-      int tid = threadIdx.x;  // opaque copy: keeps the per-bitwidth lane arithmetic inside this iteration
-      asm volatile("" : "+v"(tid));
-      switch (bits) {
-        case 2: fused_in_mfma<2, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
-        case 4: fused_in_mfma<4, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
-        default: fused_in_mfma<8, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+      uint16_t* HL = HLs + wc.j * SW;
+      uint16_t* HP = HPs + wc.j * SW;
+      switch (wc.bits) {
+        case 2: mx1_compute<2, SWIGLU>(S, wc, d, lane, dm, XP, XK, r_begin, my_rows, rot, HL, HP, acc); break;
+        case 4: mx1_compute<4, SWIGLU>(S, wc, d, lane, dm, XP, XK, r_begin, my_rows, rot, HL, HP, acc); break;
+        default: mx1_compute<8, SWIGLU>(S, wc, d, lane, dm, XP, XK, r_begin, my_rows, rot, HL, HP, acc); break;
+      }
+      advance(wc);
+    };
+    {
+      // the loop body holds no condition around the loads: every path through it issues the same number,
+      // so the arithmetic of a set waits for that set alone while the other one stays in flight
+      MxSet1 A, B;
+      int b = 0;
+      if (nb > 0) issue(A);
+      for (; b + 2 < nb; b += 2) {
+        issue(B);
+        compute(A);
+        issue(A);
+        compute(B);
+      }
+      if (b + 1 < nb) {
+        issue(B);
+        compute(A);
+        compute(B);
+      } else if (b < nb) {
+        compute(A);
       }
     }
-    // ---- phase 2: per expert, the first set of tiles is requested ahead of the arithmetic; for the first
-    // expert ahead of the barrier between the phases
+    // ---- phase 2: one list of register sets through all chosen experts; the first set is requested ahead
+    // of the barrier between the phases
+    MxWalk2 vi, vc;
+    vi.j = 0;
+    mx2_enter(vi, tabp + sel_e[0], d, slice, gsh, lane, wave, nwaves);
+    vc = vi;
+    int ns = 0;
     for (int j = 0; j < k; ++j) {
-      const int e = sel_e[j];
-      const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
-      const int bits = __builtin_amdgcn_readfirstlane(ex->bits);
-      const float gate = sel_g[j];
-      int tid = threadIdx.x;
-      asm volatile("" : "+v"(tid));
-      const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-      auto run = [&](auto bits_tag) __attribute__((always_inline)) {
-        constexpr int BITS = decltype(bits_tag)::value;
-        const uint8_t* qT_s = uniform_ptr(ex->q_out) + (size_t)(slice * P2Mx<BITS>::DW) * ((size_t)d * 4);
-        const uint8_t* sT_g = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)((slice * SW) / L.group) * ((size_t)d * 2);
-        P2Mx<BITS> first;
-        p2_mfma_issue<BITS>(first, qT_s, sT_g, d, 0, tid & 63, wv, nwaves);
-        if (j == 0) __syncthreads();   // the h slices of all chosen experts are complete in LDS
-        fused_out_mfma<BITS>(first, qT_s, sT_g, tid, nwaves, d, gate, j == 0, HLs + j * SW, HPs + j * SW, Y);
-      };
-      switch (bits) {
-        case 2: run(std::integral_constant<int, 2>{}); break;
-        case 4: run(std::integral_constant<int, 4>{}); break;
-        default: run(std::integral_constant<int, 8>{}); break;
+      const int bits = __builtin_amdgcn_readfirstlane(tabp[sel_e[j]].bits);
+      const int gps = bits == 2 ? 4 : (bits == 4 ? 2 : 1);
+      ns += d / (64 * gps * nwaves);
+    }
+    auto advance2 = [&](MxWalk2& w) __attribute__((always_inline)) {
+      if (++w.set == w.n_sets) {
+        if (++w.j < k) mx2_enter(w, tabp + sel_e[w.j], d, slice, gsh, lane, wave, nwaves);
+      }
+    };
+    auto issue2 = [&](MxSet2& S) __attribute__((always_inline)) {
+      mx2_issue(S, vi);
+      advance2(vi);
+    };
+    float K2 = 0.f, g24 = 0.f;
+    auto compute2 = [&](const MxSet2& S) __attribute__((always_inline)) {
+      if (vc.set == 0) {
+        // offset term of the expert: the sum of its h slice (one value per lane, kMxSlice == 64)
+        const float hs = wave_sum(f16_bits_to_f32(HLs[vc.j * SW + lane]));
+        K2 = hs * ((float)(1 << (vc.bits - 1)) * 5.9604644775390625e-08f);
+        g24 = sel_g[vc.j] * 16777216.0f;
+      }
+      const uint4* HP4 = (const uint4*)(HPs + vc.j * SW);
+      switch (vc.bits) {
+        case 2: mx2_compute<2>(S, vc, d, lane, wave, nwaves, HP4, K2, g24, Y); break;
+        case 4: mx2_compute<4>(S, vc, d, lane, wave, nwaves, HP4, K2, g24, Y); break;
+        default: mx2_compute<8>(S, vc, d, lane, wave, nwaves, HP4, K2, g24, Y); break;
+      }
+      advance2(vc);
+    };
+    {
+      MxSet2 A, B;
+      issue2(A);                      // ns >= 1
+      __syncthreads();                // the h slices of all chosen experts are complete in LDS
+      int b = 0;
+      for (; b + 2 < ns; b += 2) {
+        issue2(B);
+        compute2(A);
+        issue2(A);
+        compute2(B);
+      }
+      if (b + 1 < ns) {
+        issue2(B);
+        compute2(A);
+        compute2(B);
+      } else {
+        compute2(A);
       }
     }
     __syncthreads();   // Y was written by the lanes that hold the instruction results, it is read by all
@@ -966,10 +1040,12 @@ FusedPlan plan_fused(const LayerDims& L) {
   static const int forced_nt = [] { const char* v = std::getenv("MOEQ_THREADS"); return v ? std::atoi(v) : 0; }();
   if (forced_nt >= 64 && forced_nt <= 1024 && forced_nt % 64 == 0) nt = forced_nt;
   if ((int64_t)nt * kRbMax * 4 < L.d_model) return p;   // every output row needs an owner
-  // Matrix-core variant: scale groups that are whole 128-column runs, 64-column slices, rows that are
-  // whole tiles at every bitwidth (2048 columns).
+  // Matrix-core variant: scale groups of 128, 256, 512 or 1024 columns, 64-column slices,
+  // rows that are whole bursts (two tiles) at every bitwidth (4096 columns), and wavefronts that share the
+  // rows of a slice and the 64-row groups of the output evenly.
   static const bool no_mx = [] { const char* v = std::getenv("MOEQ_NO_MFMA"); return v && v[0] == '1'; }();
-  const int mx = (!no_mx && best == kMxSlice && L.group % 128 == 0 && L.d_model % 2048 == 0) ? 1 : 0;
+  const int mx = (!no_mx && best == kMxSlice && L.group % 128 == 0 && (L.group & (L.group - 1)) == 0 && L.group <= 1024 &&
+                  L.d_model % 4096 == 0 && kMxSlice % (nt / 64) == 0 && L.d_model % (4 * nt) == 0) ? 1 : 0;
   if (fused_lds_bytes(L, L.top_k, best, 3) > kFusedLdsBudget) return p;
   if (L.d_model > 2048 * kMaxSegs) return p;
   p.SW = best;
