@@ -400,16 +400,25 @@ constexpr int kMxSlice = 64;   // slice width of the matrix-core variant
 // n + 16*(n/4), element n%4. Each diagonal lane scales its group's dot product with its own group scale
 // and accumulates; a wavefront sum per row finishes the dot product.
 //
-// A wavefront owns a run of rows of the slice and walks ONE list of bursts (a burst = up to two tiles of
-// each matrix of a row) that goes through all chosen experts: expert, then row, then burst of the row.
-// Two register sets alternate, the loads of the next burst are issued before the arithmetic of the
-// current one, and since the list does not stop at the change of expert the loads never drain there.
+// The rows of the slice, for all chosen experts, form one list of tasks (expert, then row); a task is the
+// row's bursts (a burst = two tiles of each matrix). Wavefront w takes the tasks w, w + nwaves, ... Two
+// register sets alternate: both are requested ahead, the set that was just consumed is requested again
+// at once, and since the list does not stop at the change of expert the loads never drain there. Past
+// the end of the list a wavefront requests a few bytes of the activation vector instead (cached, ignored),
+// so that the loop holds no condition around its loads: every path issues the same number, and the
+// arithmetic of a set waits for that set alone.
+// The hardware serves the oldest wavefront of a SIMD first, which lets the four wavefronts of a SIMD drift
+// apart by a third of the phase; each wavefront therefore lowers its own priority as its list gets
+// shorter, so that the ones that are behind are served first and all reach the barrier together.
+// (Handing tasks out through a counter in LDS was tried: the LDS atomics alone cost more than the drift.)
 struct MxSet1 { uint4 t[2][2]; uint32_t sc[2][2]; };   // [tile of the burst][matrix]
 
-struct MxWalk1 {          // a position in the wavefront's burst list, and what the bursts of that expert need
-  int j, ri, jb;          // expert slot, row among the wavefront's rows, burst of the row
+struct MxTag1 { int valid, t, j, r, jb, bits, JB; };   // what a requested set holds: task, expert slot, row, burst
+
+struct MxWalk1 {          // the next burst to request, and what the bursts of that expert need
+  int t, valid, j, r, jb; // task, task in range; expert slot, row of the slice, burst of the row
   int bits, JB;           // of the expert at slot j: its bitwidth and bursts per row
-  // for the loads only: the same instructions serve every bitwidth, the differences are in these values
+  // the same load instructions serve every bitwidth, the differences are in these values
   const uint8_t* q[2];
   const uint8_t* s[2];
   uint32_t row_bytes, tile_bytes, tile_groups2;   // bytes of a row, of a tile; 2 * scale groups of a tile
@@ -439,26 +448,31 @@ __device__ __forceinline__ void mx1_enter(MxWalk1& w, const DevExpert* ex, int d
   w.lane_g2 = (lane_col >> gsh) * 2u;
 }
 
-// Requests the burst at w: two tiles of each matrix and the scales of the lane's pieces. ng2 = bytes of a
-// row of scales.
+// Requests the burst at w (two tiles of each matrix and the scales of the lane's pieces) and notes in tag
+// what the set will hold. row0 = first row of the slice, ng2 = bytes of a row of scales; idle = cached
+// bytes (at least 2 KB + 1 KB) to read when the list is exhausted.
 template <int NM>
-__device__ __forceinline__ void mx1_issue(MxSet1& S, const MxWalk1& w, uint32_t row, uint32_t ng2) {
-  const uint32_t t0 = (uint32_t)w.jb * 2u;
-  const uint32_t qoff = row * w.row_bytes + t0 * w.tile_bytes + w.lane_off;
-  const uint32_t soff = row * ng2 + t0 * w.tile_groups2 + w.lane_g2;
+__device__ __forceinline__ void mx1_issue(MxSet1& S, MxTag1& tag, const MxWalk1& w, uint32_t row0, uint32_t ng2,
+                                          const uint8_t* idle, int lane) {
+  tag.valid = w.valid; tag.t = w.t; tag.j = w.j; tag.r = w.r; tag.jb = w.jb; tag.bits = w.bits; tag.JB = w.JB;
+  const uint32_t row = row0 + (uint32_t)w.r, t0 = (uint32_t)w.jb * 2u;
+  const uint32_t qoff = w.valid ? row * w.row_bytes + t0 * w.tile_bytes + w.lane_off : (uint32_t)lane * 16u;
+  const uint32_t soff = w.valid ? row * ng2 + t0 * w.tile_groups2 + w.lane_g2 : (uint32_t)lane * 2u;
 #pragma unroll
   for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
     for (int mm = 0; mm < NM; ++mm) {
-      S.t[jj][mm] = load_stream16(w.q[mm] + (qoff + (jj ? w.tile_bytes : 0u)));
-      S.sc[jj][mm] = gload_u16(w.s[mm] + (soff + (jj ? w.tile_groups2 : 0u)));
+      const uint8_t* qb = w.valid ? w.q[mm] : idle;
+      const uint8_t* sb = w.valid ? w.s[mm] : idle;
+      S.t[jj][mm] = load_stream16(qb + (qoff + (jj ? w.tile_bytes : 0u)));
+      S.sc[jj][mm] = gload_u16(sb + (soff + (jj ? w.tile_groups2 : 0u)));
     }
 }
 
 // The arithmetic of one burst: adds the lane's share of the row's dot products to acc. dm[i] is 1 in the
 // lane that holds a diagonal result in element i, else 0.
 template <int BITS, int NM>
-__device__ __forceinline__ void mx1_burst(const MxSet1& S, const MxWalk1& w, int d, int lane, const float (&dm)[4],
+__device__ __forceinline__ void mx1_burst(const MxSet1& S, int jb, int d, int lane, const float (&dm)[4],
                                           const uint4* XP4, const float* XK, float (&acc)[NM]) {
   constexpr int WPC = 128 / BITS;
   const int C = d / WPC;
@@ -468,7 +482,7 @@ __device__ __forceinline__ void mx1_burst(const MxSet1& S, const MxWalk1& w, int
 #pragma unroll
   for (int jj = 0; jj < 2; ++jj) {
     {
-      const int j = w.jb * 2 + jj;
+      const int j = jb * 2 + jj;
       float4_t D[NM];
 #pragma unroll
       for (int mm = 0; mm < NM; ++mm) D[mm] = zero;
@@ -529,24 +543,23 @@ __device__ __forceinline__ void mx1_store_h(int c, const float (&r)[NM], uint16_
   HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
 }
 
-// One burst at the position w of the list: the arithmetic, and, when it completes a row, the sum of the
-// lanes' shares over the wavefront, after which one lane applies the activation.
+// One requested burst: the arithmetic, and, when it completes a row, the sum of the lanes' shares over the
+// wavefront, after which one lane applies the activation.
 template <int BITS, bool SWIGLU>
-__device__ __forceinline__ void mx1_compute(const MxSet1& S, const MxWalk1& w, int d, int lane, const float (&dm)[4],
-                                            const uint32_t* XP, const float* XK, int r_begin, int my_rows, int rot,
-                                            uint16_t* HL, uint16_t* HP, float (&acc)[SWIGLU ? 2 : 1]) {
+__device__ __forceinline__ void mx1_compute(const MxSet1& S, const MxTag1& tag, int d, int lane, const float (&dm)[4],
+                                            const uint32_t* XP, const float* XK, uint16_t* HL, uint16_t* HP,
+                                            float (&acc)[SWIGLU ? 2 : 1]) {
   constexpr int NM = SWIGLU ? 2 : 1;
-  if (w.jb == 0) {
+  if (tag.jb == 0) {
 #pragma unroll
     for (int mm = 0; mm < NM; ++mm) acc[mm] = 0.f;
   }
-  mx1_burst<BITS, NM>(S, w, d, lane, dm, (const uint4*)XP, XK, acc);
-  if (w.jb + 1 == w.JB) {
+  mx1_burst<BITS, NM>(S, tag.jb, d, lane, dm, (const uint4*)XP, XK, acc);
+  if (tag.jb + 1 == tag.JB) {
     float r[NM];
 #pragma unroll
     for (int mm = 0; mm < NM; ++mm) r[mm] = wave_sum(acc[mm]) * 16777216.0f;
-    if (lane == 0)
-      mx1_store_h<BITS, SWIGLU, NM>(r_begin + (w.ri + rot < my_rows ? w.ri + rot : w.ri + rot - my_rows), r, HL, HP);
+    if (lane == 0) mx1_store_h<BITS, SWIGLU, NM>(tag.r, r, HL, HP);
   }
 }
 
@@ -674,7 +687,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   const int d = L.d_model, E = L.n_experts, SW = P.SW;
   const int slice = blockIdx.x, token = blockIdx.y;
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int k = P.fixed_expert >= 0 ? 1 : L.top_k;
   const int lay_words = d / 2 + d / 16;
   const bool bf16 = L.x_bf16 != 0;
@@ -690,8 +703,12 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
 
   // ---- everything that depends on nothing but the inputs is requested at once: the activations, the
   // expert records, the router rows
-  copy_x_to_lds(xt, bf16 ? X_BF16 : X_F32, d, threadIdx.x, nthreads, RAW);
-  if (tab_in_lds && (int)threadIdx.x < E * 4) ((uint4*)tab)[threadIdx.x] = ((const uint4*)P.table)[threadIdx.x];
+  bool staged = false;
+  auto stage_inputs = [&]() __attribute__((always_inline)) {
+    copy_x_to_lds(xt, bf16 ? X_BF16 : X_F32, d, threadIdx.x, nthreads, RAW);
+    if (tab_in_lds && (int)threadIdx.x < E * 4) ((uint4*)tab)[threadIdx.x] = ((const uint4*)P.table)[threadIdx.x];
+    staged = true;
+  };
   // router work unit = (expert, segment of seg_cols columns), one wavefront each; segments are sized so
   // that the units about fill the wavefronts, at most eight 128-bit loads of the router row per lane
   int n_seg = (d + 2047) / 2048;
@@ -719,6 +736,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
           }
         }
       }
+      if (!staged) stage_inputs();   // behind the router loads: one memory round trip for both
       float acc = 0.f;
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
@@ -729,11 +747,12 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       if (lane == 0) rpart[u] = acc;
     }
   }
+  if (!staged) stage_inputs();
   __syncthreads();  // RAW, tab, rpart are complete
 
   // ---- wavefront 0 turns the router sums into the top-k while the others stage the activations for
   // every bitwidth the layer holds (the staging does not depend on the routing)
-  if (wave == 0) {
+  auto route = [&]() __attribute__((always_inline)) {
     if (routed) {
       if (inline_router) {
         float* lg = rpart + E * n_seg;            // the logits go behind the partial sums
@@ -750,8 +769,8 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       sel_e[0] = P.fixed_expert;
       sel_g[0] = P.gate_in ? P.gate_in[token] : 1.0f;
     }
-  } else {
-    const int st = threadIdx.x - 64, sn = nthreads - 64;
+  };
+  auto stage_layouts = [&](int st, int sn) __attribute__((always_inline)) {
     if (P.bits_mask & 2) {
       uint32_t* XPs = LAY + layout_slot(P.bits_mask, 2) * lay_words;
       permute_x<2>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
@@ -764,83 +783,82 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       uint32_t* XPs = LAY + layout_slot(P.bits_mask, 8) * lay_words;
       permute_x<8>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
     }
-  }
-  __syncthreads();  // layouts, sel_e, sel_g are complete
-  if (routed && slice == 0 && (int)threadIdx.x < k) {
-    if (P.idx_out) P.idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
-    if (P.gate_out) P.gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
-  }
+  };
+  auto publish_routing = [&]() __attribute__((always_inline)) {
+    if (routed && slice == 0 && (int)threadIdx.x < k) {
+      if (P.idx_out) P.idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
+      if (P.gate_out) P.gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
+    }
+  };
 
   if constexpr (MX) {
     constexpr int NM = SWIGLU ? 2 : 1;
+    if (wave == 0) route();
+    else stage_layouts(threadIdx.x - 64, nthreads - 64);
+    __syncthreads();  // layouts, sel_e, sel_g are complete
+    publish_routing();
     const DevExpert* tabp = tab_in_lds ? tab : P.table;
     const int gsh = __builtin_ctz((unsigned)L.group);           // the plan admits powers of two only
     const int m16 = lane & 15, kb4 = lane >> 4;
     float dm[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) dm[i] = (kb4 == (m16 >> 2) && (m16 & 3) == i) ? 1.f : 0.f;
-    // ---- phase 1: the wavefront's rows of the slice, a contiguous run walked from a workgroup-dependent
-    // start, for every chosen expert in one list of bursts
-    const int my_rows = SW / nwaves;                            // the plan makes nwaves divide the slice width
-    const int r_begin = wave * my_rows;
-    const int rot = slice % my_rows;
-    const uint32_t row0 = (uint32_t)(slice * SW + r_begin);
+    // ---- phase 1: tasks (expert slot t / SW, row t % SW of the slice) from the counter in LDS
+    const uint32_t row0 = (uint32_t)(slice * SW);
     const uint32_t ng2 = (uint32_t)(d >> gsh) * 2u;
-    int nb = 0;
-    for (int j = 0; j < k; ++j) {
-      const int bits = __builtin_amdgcn_readfirstlane(tabp[sel_e[j]].bits);
-      nb += my_rows * (d / (bits == 8 ? 2048 : 4096));
-    }
-    MxWalk1 wi, wc;
-    wi.j = wi.ri = wi.jb = 0;
-    mx1_enter<SWIGLU>(wi, tabp + sel_e[0], d, gsh, lane);
-    wc = wi;
-    auto advance = [&](MxWalk1& w) __attribute__((always_inline)) {
-      if (++w.jb == w.JB) {
-        w.jb = 0;
-        if (++w.ri == my_rows) {
-          w.ri = 0;
-          if (++w.j < k) mx1_enter<SWIGLU>(w, tabp + sel_e[w.j], d, gsh, lane);
+    const int n_tasks = k * SW;
+    MxWalk1 wi;
+    wi.j = -1;
+    auto take = [&](int t) __attribute__((always_inline)) {
+      wi.t = t;
+      wi.valid = t < n_tasks;
+      wi.jb = 0;
+      if (wi.valid) {
+        // SW == 64. Consecutive tasks are rows 4 apart, rotated by the slice: what the workgroup reads at
+        // any moment is spread over its whole block of rows, and differently in every workgroup
+        const int j = t >> 6, u = t & 63;
+        wi.r = ((u & 15) << 2) | (((u >> 4) + slice) & 3);
+        if (j != wi.j) {
+          wi.j = j;
+          mx1_enter<SWIGLU>(wi, tabp + sel_e[j], d, gsh, lane);
         }
       }
     };
-    auto issue = [&](MxSet1& S) __attribute__((always_inline)) {
-      const uint32_t row = row0 + (uint32_t)(wi.ri + rot < my_rows ? wi.ri + rot : wi.ri + rot - my_rows);
-      mx1_issue<NM>(S, wi, row, ng2);
-      advance(wi);
+    auto issue = [&](MxSet1& S, MxTag1& tag) __attribute__((always_inline)) {
+      mx1_issue<NM>(S, tag, wi, row0, ng2, (const uint8_t*)xt, lane);
+      if (wi.valid && ++wi.jb == wi.JB) take(wi.t + nwaves);
     };
     float acc[NM];
-    auto compute = [&](const MxSet1& S) __attribute__((always_inline)) {
-      const uint32_t* XP = LAY + layout_slot(P.bits_mask, wc.bits) * lay_words;
+    auto compute = [&](const MxSet1& S, const MxTag1& tag) __attribute__((always_inline)) {
+      const uint32_t* XP = LAY + layout_slot(P.bits_mask, tag.bits) * lay_words;
       const float* XK = (const float*)(XP + d / 2);
-      uint16_t* HL = HLs + wc.j * SW;
-      uint16_t* HP = HPs + wc.j * SW;
-      switch (wc.bits) {
-        case 2: mx1_compute<2, SWIGLU>(S, wc, d, lane, dm, XP, XK, r_begin, my_rows, rot, HL, HP, acc); break;
-        case 4: mx1_compute<4, SWIGLU>(S, wc, d, lane, dm, XP, XK, r_begin, my_rows, rot, HL, HP, acc); break;
-        default: mx1_compute<8, SWIGLU>(S, wc, d, lane, dm, XP, XK, r_begin, my_rows, rot, HL, HP, acc); break;
+      uint16_t* HL = HLs + tag.j * SW;
+      uint16_t* HP = HPs + tag.j * SW;
+      switch (tag.bits) {
+        case 2: mx1_compute<2, SWIGLU>(S, tag, d, lane, dm, XP, XK, HL, HP, acc); break;
+        case 4: mx1_compute<4, SWIGLU>(S, tag, d, lane, dm, XP, XK, HL, HP, acc); break;
+        default: mx1_compute<8, SWIGLU>(S, tag, d, lane, dm, XP, XK, HL, HP, acc); break;
       }
-      advance(wc);
     };
     {
-      // the loop body holds no condition around the loads: every path through it issues the same number,
-      // so the arithmetic of a set waits for that set alone while the other one stays in flight
       MxSet1 A, B;
-      int b = 0;
-      if (nb > 0) issue(A);
-      for (; b + 2 < nb; b += 2) {
-        issue(B);
-        compute(A);
-        issue(A);
-        compute(B);
+      MxTag1 ta, tb;
+      take(wave);                     // n_tasks >= 64 > wave
+      issue(A, ta);
+      issue(B, tb);
+      while (ta.valid) {
+        // priority by the tasks still ahead (n_tasks / nwaves = 4k at the start)
+        const int left = (n_tasks - ta.t) / nwaves;
+        if (left >= 6) __builtin_amdgcn_s_setprio(3);
+        else if (left >= 4) __builtin_amdgcn_s_setprio(2);
+        else if (left >= 2) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+        compute(A, ta);
+        issue(A, ta);
+        if (tb.valid) compute(B, tb);
+        issue(B, tb);
       }
-      if (b + 1 < nb) {
-        issue(B);
-        compute(A);
-        compute(B);
-      } else if (b < nb) {
-        compute(A);
-      }
+      __builtin_amdgcn_s_setprio(0);
     }
     // ---- phase 2: one list of register sets through all chosen experts; the first set is requested ahead
     // of the barrier between the phases
@@ -900,6 +918,10 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     }
     __syncthreads();   // Y was written by the lanes that hold the instruction results, it is read by all
   } else {
+  if (wave == 0) route();
+  else stage_layouts(threadIdx.x - 64, nthreads - 64);
+  __syncthreads();  // layouts, sel_e, sel_g are complete
+  publish_routing();
   // ---- phase 1 of every chosen expert, back to back: no wavefront waits for another one here
   for (int j = 0; j < k; ++j) {
     const int e = sel_e[j];
