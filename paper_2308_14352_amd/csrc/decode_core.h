@@ -233,7 +233,12 @@ __device__ __forceinline__ void offset_terms(const uint16_t* lin, int cols, int 
   }
 }
 
+// The negated offset terms of whole lane-column ranges (128 columns, 64 at 8 bits) of a linear binary16
+// vector in LDS: KS[r] = -2^(b-1) * 2^-24 * (sum of the activations of range r). Four threads share a range.
 template <int BITS>
+__device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS);
+
+template <int BITS, bool RANGES = false>
 __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int group, int tid, int nthreads,
                                           uint32_t* XP, float* XK) {
   constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
@@ -247,7 +252,8 @@ __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int gro
     const uint32_t bh = f32_to_f16_bits(f16_bits_to_f32(RAW[c * WPC + hi]) * ps);
     XP[((pi >> 2) * C + c) * 4 + (pi & 3)] = bl | (bh << 16);
   }
-  offset_terms<BITS>(RAW, cols, group, tid, nthreads, XK);
+  if constexpr (RANGES) range_offset_terms<BITS>(RAW, cols, tid, nthreads, XK);
+  else offset_terms<BITS>(RAW, cols, group, tid, nthreads, XK);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -260,6 +266,26 @@ constexpr int kDppXor1 = 0xB1;   // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;   // quad_perm [2,3,0,1]
 constexpr int kDppRor4 = 0x124;  // row_ror:4  (rotation inside a 16-lane row)
 constexpr int kDppRor8 = 0x128;  // row_ror:8
+
+template <int BITS>
+__device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS) {
+  constexpr int R = BITS == 8 ? 64 : 128;    // columns of a range
+  constexpr int V = R / 32;                  // 128-bit loads per thread
+  const uint4* lin4 = (const uint4*)lin;
+  const int n4 = (cols / R) * 4;             // a multiple of 4: whole quads of lanes run the loop together
+  for (int i = tid; i < n4; i += nthreads) {
+    float acc = 0.f;
+#pragma unroll
+    for (int v4 = 0; v4 < V; ++v4) {
+      const uint4 v = lin4[i * V + v4];
+      acc += (f16_bits_to_f32(v.x & 0xffffu) + f16_bits_to_f32(v.x >> 16)) + (f16_bits_to_f32(v.y & 0xffffu) + f16_bits_to_f32(v.y >> 16));
+      acc += (f16_bits_to_f32(v.z & 0xffffu) + f16_bits_to_f32(v.z >> 16)) + (f16_bits_to_f32(v.w & 0xffffu) + f16_bits_to_f32(v.w >> 16));
+    }
+    acc += dpp<kDppXor1>(acc);
+    acc += dpp<kDppXor2>(acc);
+    if ((i & 3) == 0) KS[i >> 2] = acc * (-Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+  }
+}
 
 // Sum over the P lanes of a row group (P a power of two, groups are contiguous lanes) of NM*NRM row
 // totals per lane; v = m*NRM + i, NRM <= min(P, 4). Afterwards every lane holds, in v[m*NRM] (m < NM),

@@ -470,61 +470,55 @@ __device__ __forceinline__ void mx1_issue(MxSet1& S, MxTag1& tag, const MxWalk1&
 }
 
 // The arithmetic of one burst: adds the lane's share of the row's dot products to acc. dm[i] is 1 in the
-// lane that holds a diagonal result in element i, else 0.
+// lane that holds a diagonal result in element i, else 0. KS holds the negated offset terms of the lane
+// column ranges: the accumulation of D[m][.] starts there, so the diagonal comes out with its offset
+// already taken off (the other entries are never looked at).
 template <int BITS, int NM>
 __device__ __forceinline__ void mx1_burst(const MxSet1& S, int jb, int d, int lane, const float (&dm)[4],
-                                          const uint4* XP4, const float* XK, float (&acc)[NM]) {
+                                          const uint4* XP4, const float* KS, float (&acc)[NM]) {
   constexpr int WPC = 128 / BITS;
   const int C = d / WPC;
   const int m = lane & 15, kb = lane >> 4;
-  const bool diag = kb == (m >> 2);
-  const float4_t zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int jj = 0; jj < 2; ++jj) {
-    {
-      const int j = jb * 2 + jj;
-      float4_t D[NM];
+    const int j = jb * 2 + jj;
+    const float4 k4 = *(const float4*)(KS + 16 * j + 4 * kb);
+    const float4_t init = {k4.x, k4.y, k4.z, k4.w};
+    float4_t D[NM];
 #pragma unroll
-      for (int mm = 0; mm < NM; ++mm) D[mm] = zero;
-      float K;   // offset term of the diagonal lane's column group
-      if constexpr (BITS == 2) {
-        const float2 k2 = *(const float2*)(XK + 32 * j + 2 * m);
-        K = k2.x + k2.y;
+    for (int mm = 0; mm < NM; ++mm) D[mm] = init;
+    if constexpr (BITS == 2) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-          for (int hh = 0; hh < 2; ++hh) {
-            const half8_t A = as_half8(XP4[(2 * (2 * (kb & 1) + t) + hh) * C + 32 * j + 2 * m + (kb >> 1)]);
-#pragma unroll
-            for (int mm = 0; mm < NM; ++mm) {
-              // the lane's 8 bytes are the upper half of the 16 loaded ones when kb is odd
-              const uint4 wd = S.t[jj][mm];
-              const uint32_t dw = t ? ((kb & 1) ? wd.w : wd.y) : ((kb & 1) ? wd.z : wd.x);
-              D[mm] = mfma16(A, hh ? codes8<2, 1>(dw, 0u) : codes8<2, 0>(dw, 0u), D[mm]);
-            }
-          }
-      } else {
-        const float4 k4 = *(const float4*)(XK + 64 * j + 4 * m);
-        K = (k4.x + k4.y) + (k4.z + k4.w);
-        constexpr int NI = BITS == 4 ? 4 : 2;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-          const half8_t A = as_half8(XP4[i * C + 64 * j + 4 * m + kb]);
+        for (int hh = 0; hh < 2; ++hh) {
+          const half8_t A = as_half8(XP4[(2 * (2 * (kb & 1) + t) + hh) * C + 32 * j + 2 * m + (kb >> 1)]);
 #pragma unroll
           for (int mm = 0; mm < NM; ++mm) {
+            // the lane's 8 bytes are the upper half of the 16 loaded ones when kb is odd
             const uint4 wd = S.t[jj][mm];
-            if constexpr (BITS == 4) D[mm] = mfma16(A, codes8<4, 0>(i == 0 ? wd.x : i == 1 ? wd.y : i == 2 ? wd.z : wd.w, 0u), D[mm]);
-            else D[mm] = mfma16(A, i == 0 ? codes8<8, 0>(wd.x, wd.y) : codes8<8, 0>(wd.z, wd.w), D[mm]);
+            const uint32_t dw = t ? ((kb & 1) ? wd.w : wd.y) : ((kb & 1) ? wd.z : wd.x);
+            D[mm] = mfma16(A, hh ? codes8<2, 1>(dw, 0u) : codes8<2, 0>(dw, 0u), D[mm]);
           }
         }
-      }
-      const float Kd = diag ? K : 0.f;
+    } else {
+      constexpr int NI = BITS == 4 ? 4 : 2;
 #pragma unroll
-      for (int mm = 0; mm < NM; ++mm) {
-        // exactly one of the four products is non-zero in a diagonal lane, none elsewhere
-        const float dv = fmaf(D[mm][3], dm[3], fmaf(D[mm][2], dm[2], fmaf(D[mm][1], dm[1], D[mm][0] * dm[0])));
-        acc[mm] = fmaf(f16_bits_to_f32(S.sc[jj][mm]), dv - Kd, acc[mm]);
+      for (int i = 0; i < NI; ++i) {
+        const half8_t A = as_half8(XP4[i * C + 64 * j + 4 * m + kb]);
+#pragma unroll
+        for (int mm = 0; mm < NM; ++mm) {
+          const uint4 wd = S.t[jj][mm];
+          if constexpr (BITS == 4) D[mm] = mfma16(A, codes8<4, 0>(i == 0 ? wd.x : i == 1 ? wd.y : i == 2 ? wd.z : wd.w, 0u), D[mm]);
+          else D[mm] = mfma16(A, i == 0 ? codes8<8, 0>(wd.x, wd.y) : codes8<8, 0>(wd.z, wd.w), D[mm]);
+        }
       }
+    }
+#pragma unroll
+    for (int mm = 0; mm < NM; ++mm) {
+      // exactly one of the four products is non-zero in a diagonal lane, none elsewhere
+      const float dv = fmaf(D[mm][3], dm[3], fmaf(D[mm][2], dm[2], fmaf(D[mm][1], dm[1], D[mm][0] * dm[0])));
+      acc[mm] = fmaf(f16_bits_to_f32(S.sc[jj][mm]), dv, acc[mm]);
     }
   }
 }
@@ -544,22 +538,25 @@ __device__ __forceinline__ void mx1_store_h(int c, const float (&r)[NM], uint16_
 }
 
 // One requested burst: the arithmetic, and, when it completes a row, the sum of the lanes' shares over the
-// wavefront, after which one lane applies the activation.
+// wavefront; lane i keeps the sums of the wavefront's i-th finished row (rows_done counts them), and the
+// activation is applied to all of them at once when the list is through.
 template <int BITS, bool SWIGLU>
 __device__ __forceinline__ void mx1_compute(const MxSet1& S, const MxTag1& tag, int d, int lane, const float (&dm)[4],
-                                            const uint32_t* XP, const float* XK, uint16_t* HL, uint16_t* HP,
-                                            float (&acc)[SWIGLU ? 2 : 1]) {
+                                            const uint32_t* XP, const float* KS, float (&acc)[SWIGLU ? 2 : 1],
+                                            float (&keep)[SWIGLU ? 2 : 1], int& rows_done) {
   constexpr int NM = SWIGLU ? 2 : 1;
   if (tag.jb == 0) {
 #pragma unroll
     for (int mm = 0; mm < NM; ++mm) acc[mm] = 0.f;
   }
-  mx1_burst<BITS, NM>(S, tag.jb, d, lane, dm, (const uint4*)XP, XK, acc);
+  mx1_burst<BITS, NM>(S, tag.jb, d, lane, dm, (const uint4*)XP, KS, acc);
   if (tag.jb + 1 == tag.JB) {
-    float r[NM];
 #pragma unroll
-    for (int mm = 0; mm < NM; ++mm) r[mm] = wave_sum(acc[mm]) * 16777216.0f;
-    if (lane == 0) mx1_store_h<BITS, SWIGLU, NM>(tag.r, r, HL, HP);
+    for (int mm = 0; mm < NM; ++mm) {
+      const float r = wave_sum(acc[mm]);
+      keep[mm] = lane == rows_done ? r : keep[mm];
+    }
+    ++rows_done;
   }
 }
 
@@ -771,17 +768,19 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     }
   };
   auto stage_layouts = [&](int st, int sn) __attribute__((always_inline)) {
+    // behind the staged pairs of a bitwidth: its offset terms (matrix-core variant: negated, per range of
+    // a lane column)
     if (P.bits_mask & 2) {
       uint32_t* XPs = LAY + layout_slot(P.bits_mask, 2) * lay_words;
-      permute_x<2>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
+      permute_x<2, MX>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
     }
     if (P.bits_mask & 4) {
       uint32_t* XPs = LAY + layout_slot(P.bits_mask, 4) * lay_words;
-      permute_x<4>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
+      permute_x<4, MX>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
     }
     if (P.bits_mask & 8) {
       uint32_t* XPs = LAY + layout_slot(P.bits_mask, 8) * lay_words;
-      permute_x<8>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
+      permute_x<8, MX>(RAW, d, L.group, st, sn, XPs, (float*)(XPs + d / 2));
     }
   };
   auto publish_routing = [&]() __attribute__((always_inline)) {
@@ -828,16 +827,17 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       mx1_issue<NM>(S, tag, wi, row0, ng2, (const uint8_t*)xt, lane);
       if (wi.valid && ++wi.jb == wi.JB) take(wi.t + nwaves);
     };
-    float acc[NM];
+    float acc[NM], keep[NM];
+#pragma unroll
+    for (int mm = 0; mm < NM; ++mm) keep[mm] = 0.f;
+    int rows_done = 0;
     auto compute = [&](const MxSet1& S, const MxTag1& tag) __attribute__((always_inline)) {
       const uint32_t* XP = LAY + layout_slot(P.bits_mask, tag.bits) * lay_words;
-      const float* XK = (const float*)(XP + d / 2);
-      uint16_t* HL = HLs + tag.j * SW;
-      uint16_t* HP = HPs + tag.j * SW;
+      const float* KS = (const float*)(XP + d / 2);
       switch (tag.bits) {
-        case 2: mx1_compute<2, SWIGLU>(S, tag, d, lane, dm, XP, XK, HL, HP, acc); break;
-        case 4: mx1_compute<4, SWIGLU>(S, tag, d, lane, dm, XP, XK, HL, HP, acc); break;
-        default: mx1_compute<8, SWIGLU>(S, tag, d, lane, dm, XP, XK, HL, HP, acc); break;
+        case 2: mx1_compute<2, SWIGLU>(S, tag, d, lane, dm, XP, KS, acc, keep, rows_done); break;
+        case 4: mx1_compute<4, SWIGLU>(S, tag, d, lane, dm, XP, KS, acc, keep, rows_done); break;
+        default: mx1_compute<8, SWIGLU>(S, tag, d, lane, dm, XP, KS, acc, keep, rows_done); break;
       }
     };
     {
@@ -859,6 +859,21 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
         issue(B, tb);
       }
       __builtin_amdgcn_s_setprio(0);
+    }
+    // the activation of the wavefront's rows: lane i finished the task wave + i * nwaves
+    if (lane < rows_done) {
+      const int t = wave + lane * nwaves, j = t >> 6, u = t & 63;
+      const int c = ((u & 15) << 2) | (((u >> 4) + slice) & 3);
+      float r[NM];
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) r[mm] = keep[mm] * 16777216.0f;
+      uint16_t* HL = HLs + j * SW;
+      uint16_t* HP = HPs + j * SW;
+      switch (tabp[sel_e[j]].bits) {
+        case 2: mx1_store_h<2, SWIGLU, NM>(c, r, HL, HP); break;
+        case 4: mx1_store_h<4, SWIGLU, NM>(c, r, HL, HP); break;
+        default: mx1_store_h<8, SWIGLU, NM>(c, r, HL, HP); break;
+      }
     }
     // ---- phase 2: one list of register sets through all chosen experts; the first set is requested ahead
     // of the barrier between the phases
