@@ -138,6 +138,19 @@ moeq_status moe_layer_forward(const moeq_layer *layer, const void *x, int32_t n_
                               int32_t *topk_idx_opt, float *topk_gate_opt, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* The layer with the routing GIVEN by the caller instead of computed by the router: static-routing
+ * layers (Section 3.1, "Applicability": hash layers, expert-choice layers - the experts of a token
+ * follow from the input tokens, not from its hidden state):
+ * y[t] = sum_j topk_gate[t][j] * FFN_{topk_idx[t][j]}(x[t]).
+ * topk_idx: dev [n_tokens][top_k] int32; topk_gate: dev [n_tokens][top_k] fp32; both read-only and
+ * 4-byte aligned. The layer's router weights are not read. A pair whose expert index is outside
+ * [0, n_experts) contributes nothing (the arrays live on the device, so no error can be raised for
+ * it); the same expert may appear more than once for a token. Workspace, limits, alignment and
+ * errors as for moe_layer_forward. */
+moeq_status moe_layer_forward_routed(const moeq_layer *layer, const void *x, int32_t n_tokens,
+                                     const int32_t *topk_idx, const float *topk_gate, float *y,
+                                     void *ws, size_t ws_bytes, void *stream);
+
 /* ---- compression primitives (offline side of the path, Section 3.2) ---------------------- */
 
 /* Quantize and pack on the device: w dev [rows][cols] fp32 -> codes (q_out) and fp16 scales (s_out)

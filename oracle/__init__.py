@@ -178,3 +178,18 @@ def layer_forward(experts, d, f, g, act, k, renorm, Wr, bias, x):
                                  C.c_int32(act), C.c_int32(k), C.c_int32(int(renorm)), _p(Wr), _p(b),
                                  _p(x), C.c_int32(T), _p(y), _p(idx), _p(gate)), "layer_forward")
     return y, idx, gate
+
+
+def layer_forward_routed(experts, d, f, g, act, k, x, idx, gate):
+    """The layer for a routing that is already decided: idx [T][k] int32, gate [T][k] fp32. Returns y [T][d]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    gate = np.ascontiguousarray(gate, dtype=np.float32)
+    T = x.shape[0]
+    E = len(experts)
+    arr = (_Expert * E)(*[e.c_struct() for e in experts])
+    y = np.empty((T, d), np.float32)
+    _chk(lib().orc_layer_forward_routed(arr, C.c_int32(E), C.c_int32(d), C.c_int32(f), C.c_int32(g),
+                                        C.c_int32(act), C.c_int32(k), _p(x), C.c_int32(T), _p(idx), _p(gate),
+                                        _p(y)), "layer_forward_routed")
+    return y

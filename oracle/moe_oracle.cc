@@ -252,16 +252,15 @@ int orc_expert_ffn(const orc_expert* ex, int32_t d, int32_t f, int32_t g, int32_
   return 0;
 }
 
-// ---------------------------------------------------------------- whole layer
-// router -> top-k -> each chosen expert's FFN -> y[t] = sum_j gate[t,j] * y_{idx[t,j]}[t].
-// Each activated expert is decompressed once per call and applied to the tokens
-// routed to it (for one token this is exactly: decompress the chosen expert, run
-// it); the k results of a token are then summed in top-k order.
-int orc_layer_forward(const orc_expert* experts, int32_t E, int32_t d, int32_t f, int32_t g,
-                      int32_t act, int32_t k, int32_t renorm, const float* Wr, const float* bias,
-                      const float* x, int32_t T, float* y, int32_t* idx, float* gate) {
-  if (orc_router_topk(x, T, d, Wr, bias, E, k, renorm, idx, gate, nullptr, nullptr)) return 1;
-  std::vector<float> ye((size_t)T * k * d);  // ye[(t*k+j)*d + i] = FFN_{idx[t,j]}(x[t])[i]
+// ---------------------------------------------------------------- given routing
+// Static-routing layers (Section 3.1, "Applicability"): the experts of a token are known from the
+// input, no router runs.
+// y[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(x[t]) for a routing that is already decided. A pair whose
+// index is outside [0, E) contributes nothing.
+int orc_layer_forward_routed(const orc_expert* experts, int32_t E, int32_t d, int32_t f, int32_t g,
+                             int32_t act, int32_t k, const float* x, int32_t T, const int32_t* idx,
+                             const float* gate, float* y) {
+  std::vector<float> ye((size_t)T * k * d, 0.0f);  // ye[(t*k+j)*d + i] = FFN_{idx[t,j]}(x[t])[i]
   for (int32_t e = 0; e < E; ++e) {
     std::vector<int64_t> slots;
     for (int64_t s = 0; s < (int64_t)T * k; ++s)
@@ -278,11 +277,26 @@ int orc_layer_forward(const orc_expert* experts, int32_t E, int32_t d, int32_t f
   for (int32_t t = 0; t < T; ++t)
     for (int32_t i = 0; i < d; ++i) {
       double acc = 0.0;
-      for (int32_t j = 0; j < k; ++j)
-        acc += (double)gate[(int64_t)t * k + j] * (double)ye[((size_t)t * k + j) * d + i];
+      for (int32_t j = 0; j < k; ++j) {
+        const int64_t s = (int64_t)t * k + j;
+        if (idx[s] < 0 || idx[s] >= E) continue;
+        acc += (double)gate[s] * (double)ye[(size_t)s * d + i];
+      }
       y[(int64_t)t * d + i] = (float)acc;
     }
   return 0;
+}
+
+// ---------------------------------------------------------------- whole layer
+// router -> top-k -> each chosen expert's FFN -> y[t] = sum_j gate[t,j] * y_{idx[t,j]}[t].
+// Each activated expert is decompressed once per call and applied to the tokens
+// routed to it (for one token this is exactly: decompress the chosen expert, run
+// it); the k results of a token are then summed in top-k order.
+int orc_layer_forward(const orc_expert* experts, int32_t E, int32_t d, int32_t f, int32_t g,
+                      int32_t act, int32_t k, int32_t renorm, const float* Wr, const float* bias,
+                      const float* x, int32_t T, float* y, int32_t* idx, float* gate) {
+  if (orc_router_topk(x, T, d, Wr, bias, E, k, renorm, idx, gate, nullptr, nullptr)) return 1;
+  return orc_layer_forward_routed(experts, E, d, f, g, act, k, x, T, idx, gate, y);
 }
 
 int orc_num_threads() {

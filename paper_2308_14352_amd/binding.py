@@ -72,6 +72,8 @@ def lib():
     L.moe_expert_ffn_q.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, sz, vp]
     L.moe_layer_forward.restype = C.c_int
     L.moe_layer_forward.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.moe_layer_forward_routed.restype = C.c_int
+    L.moe_layer_forward_routed.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.moe_quantize_pack.restype = C.c_int
     L.moe_quantize_pack.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
     L.moe_unpack_codes.restype = C.c_int
@@ -87,7 +89,7 @@ def lib():
 
 EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
            "moe_layer_destroy", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
-           "moe_layer_forward", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
+           "moe_layer_forward", "moe_layer_forward_routed", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
            "moe_unprepare_out"]
 
 
@@ -282,3 +284,15 @@ def moe_layer_forward(layer, x, y=None, want_routing=False, ws=None, stream=None
     _check(lib().moe_layer_forward(layer.handle, _ptr(x), T, _ptr(y), _ptr(idx), _ptr(gate), _ptr(ws), ws.numel(),
                                    _stream(stream)), "moe_layer_forward")
     return (y, idx, gate) if want_routing else y
+
+
+def moe_layer_forward_routed(layer, x, idx, gate, y=None, ws=None, stream=None):
+    """The layer with the routing given by the caller: idx [T][top_k] int32, gate [T][top_k] fp32 (device)."""
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, layer.d_model), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = layer.workspace(T)
+    _check(lib().moe_layer_forward_routed(layer.handle, _ptr(x), T, _ptr(idx), _ptr(gate), _ptr(y), _ptr(ws),
+                                          ws.numel(), _stream(stream)), "moe_layer_forward_routed")
+    return y

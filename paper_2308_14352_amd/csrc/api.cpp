@@ -219,7 +219,8 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   hipStream_t st = (hipStream_t)stream;
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     float* part = (float*)((char*)ws + w.part_off);
-    if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert, gate_opt,
+    if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert, gate_opt, nullptr,
+                          nullptr,
                           layer->bits[(size_t)expert], x, n_tokens, part, nullptr, nullptr, st) != hipSuccess)
       return MOEQ_EDEVICE;
     return dev(launch_reduce_partials(part, layer->plan.n_slices, layer->dims.d_model, n_tokens, accumulate ? 1 : 0,
@@ -234,9 +235,10 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
                             n_tokens, y, st));
 }
 
-moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_tokens, float* y,
-                              int32_t* topk_idx_opt, float* topk_gate_opt, void* ws, size_t ws_bytes,
-                              void* stream) {
+// The layer with the routing computed here (given_idx == nullptr) or supplied by the caller.
+static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, int32_t n_tokens, float* y,
+                                      int32_t* topk_idx_opt, float* topk_gate_opt, const int32_t* given_idx,
+                                      const float* given_gate, void* ws, size_t ws_bytes, void* stream) {
   if (!layer || n_tokens < 0) return MOEQ_EINVAL;
   if (n_tokens == 0) return MOEQ_OK;
   if (!x || !y || ((uintptr_t)x & 15u) || ((uintptr_t)y & 3u)) return MOEQ_EINVAL;
@@ -245,14 +247,17 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
   const WsLayout w = ws_layout(layer, n_tokens);
   if (!ws || ws_bytes < w.total) return MOEQ_EWORKSPACE;
   if ((uintptr_t)ws & 255u) return MOEQ_EINVAL;
+  const bool given = given_idx != nullptr;
   int32_t* idx = topk_idx_opt ? topk_idx_opt : (int32_t*)((char*)ws + w.idx_off);
   float* gate = topk_gate_opt ? topk_gate_opt : (float*)((char*)ws + w.gate_off);
   hipStream_t st = (hipStream_t)stream;
   float* logits = (float*)((char*)ws + w.logits_off);
+  if (given && launch_take_routing(given_idx, given_gate, n_tokens * L.top_k, L.n_experts, idx, gate, st) != hipSuccess)
+    return MOEQ_EDEVICE;
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     // one streaming kernel for the whole layer, then the ordered sum of its partial output vectors
     const float* lg = nullptr;
-    if (L.n_experts > inline_router_max()) {
+    if (!given && L.n_experts > inline_router_max()) {
       if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
         return MOEQ_EDEVICE;
       lg = logits;
@@ -261,31 +266,50 @@ moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_
     {
       ScopedEvents ev(MOEQ_KERNEL_FUSED, st);
       if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias, lg, -1, nullptr,
-                            layer->bits_mask, x, n_tokens, part, idx, gate, st) != hipSuccess)
+                            given ? idx : nullptr, given ? gate : nullptr, layer->bits_mask, x, n_tokens, part,
+                            given ? nullptr : idx, given ? nullptr : gate, st) != hipSuccess)
         return MOEQ_EDEVICE;
     }
     return dev(launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n_tokens, 0, y, st));
   }
   if (use_prefill(layer, n_tokens)) {
     // batched path: router kernels, then the pairs grouped by expert through two quantized GEMMs
-    if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
-      return MOEQ_EDEVICE;
-    if (launch_topk(L, logits, n_tokens, idx, gate, nullptr, st) != hipSuccess) return MOEQ_EDEVICE;
+    if (!given) {
+      if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
+        return MOEQ_EDEVICE;
+      if (launch_topk(L, logits, n_tokens, idx, gate, nullptr, st) != hipSuccess) return MOEQ_EDEVICE;
+    }
     const PrefillWs pw = prefill_ws(L, n_tokens);
     return dev(launch_prefill(L, layer->table, x, n_tokens, idx, gate, (char*)ws + w.prefill_off, pw, y, st));
   }
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
   DevExpert* sel_tab = (DevExpert*)((char*)ws + w.sel_off);
-  if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
+  if (!given && launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
   {
     ScopedEvents ev(MOEQ_KERNEL_FFN_IN, st);
-    if (launch_ffn_in(L, layer->table, logits, idx, gate, sel_tab, -1, x, n_tokens, h, hp, st) != hipSuccess)
+    if (launch_ffn_in(L, layer->table, given ? nullptr : logits, idx, gate, sel_tab, -1, x, n_tokens, h, hp, st) !=
+        hipSuccess)
       return MOEQ_EDEVICE;
   }
   ScopedEvents ev(MOEQ_KERNEL_FFN_OUT, st);
   return dev(launch_ffn_out(L, layer->table, sel_tab, gate, -1, 0, h, hp, n_tokens, y, st));
+}
+
+moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_tokens, float* y,
+                              int32_t* topk_idx_opt, float* topk_gate_opt, void* ws, size_t ws_bytes,
+                              void* stream) {
+  return layer_forward_impl(layer, x, n_tokens, y, topk_idx_opt, topk_gate_opt, nullptr, nullptr, ws, ws_bytes,
+                            stream);
+}
+
+moeq_status moe_layer_forward_routed(const moeq_layer* layer, const void* x, int32_t n_tokens,
+                                     const int32_t* topk_idx, const float* topk_gate, float* y, void* ws,
+                                     size_t ws_bytes, void* stream) {
+  if (n_tokens > 0 && (!topk_idx || !topk_gate)) return MOEQ_EINVAL;
+  if (((uintptr_t)topk_idx | (uintptr_t)topk_gate) & 3u) return MOEQ_EINVAL;
+  return layer_forward_impl(layer, x, n_tokens, y, nullptr, nullptr, topk_idx, topk_gate, ws, ws_bytes, stream);
 }
 
 moeq_status moe_profile_kernel(int32_t which, void* start_event, void* stop_event) {

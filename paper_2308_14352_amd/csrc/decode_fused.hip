@@ -57,6 +57,8 @@ struct FusedParams {
   const float* logits;    // non-null: router logits [T][E] computed beforehand; null: computed here
   int32_t fixed_expert;   // >= 0: every token uses this expert (no routing)
   const float* gate_in;   // fixed-expert mode: [T] or null (= 1)
+  const int32_t* route_idx;   // non-null: the routing is given, [T][k] expert indices (validated) ...
+  const float* route_gate;    // ... and gates; no router runs
   const void* x;          // [T][d] in the layer's dtype
   float* part;            // [T][n_slices][d] partial outputs
   int32_t* idx_out;       // [T][k] or null
@@ -695,7 +697,8 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   uint32_t* LAY = (uint32_t*)(Y + d / 4);          // [#bitwidths][lay_words] staged activations
   const char* xt = (const char*)P.x + (size_t)token * d * (bf16 ? 2 : 4);
   const bool routed = P.fixed_expert < 0;
-  const bool inline_router = routed && !P.logits;
+  const bool given = routed && P.route_idx != nullptr;
+  const bool inline_router = routed && !P.logits && !given;
   const bool tab_in_lds = routed && E <= kTabLds;
 
   // ---- everything that depends on nothing but the inputs is requested at once: the activations, the
@@ -750,7 +753,12 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   // ---- wavefront 0 turns the router sums into the top-k while the others stage the activations for
   // every bitwidth the layer holds (the staging does not depend on the routing)
   auto route = [&]() __attribute__((always_inline)) {
-    if (routed) {
+    if (given) {
+      if (lane < k) {
+        sel_e[lane] = P.route_idx[(size_t)token * k + lane];
+        sel_g[lane] = P.route_gate[(size_t)token * k + lane];
+      }
+    } else if (routed) {
       if (inline_router) {
         float* lg = rpart + E * n_seg;            // the logits go behind the partial sums
         if (lane < E) {
@@ -784,7 +792,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     }
   };
   auto publish_routing = [&]() __attribute__((always_inline)) {
-    if (routed && slice == 0 && (int)threadIdx.x < k) {
+    if (routed && !given && slice == 0 && (int)threadIdx.x < k) {
       if (P.idx_out) P.idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
       if (P.gate_out) P.gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
     }
@@ -1096,15 +1104,17 @@ int fused_inline_router_max() { return kInlineMaxE; }
 
 hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const DevExpert* table, const float* router_w,
                              const float* router_bias, const float* logits, int32_t fixed_expert,
-                             const float* gate_in, int32_t bits_mask, const void* x, int32_t T, float* part,
-                             int32_t* idx_out, float* gate_out, hipStream_t st) {
+                             const float* gate_in, const int32_t* route_idx, const float* route_gate,
+                             int32_t bits_mask, const void* x, int32_t T, float* part, int32_t* idx_out,
+                             float* gate_out, hipStream_t st) {
   if (!plan.SW || T < 1 || T > 65535 || !(bits_mask & 14)) return hipErrorInvalidValue;
-  if (!logits && fixed_expert < 0 && L.n_experts > kInlineMaxE) return hipErrorInvalidValue;
+  if (!logits && !route_idx && fixed_expert < 0 && L.n_experts > kInlineMaxE) return hipErrorInvalidValue;
+  if ((route_idx != nullptr) != (route_gate != nullptr)) return hipErrorInvalidValue;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
   const int n_layouts = ((bits_mask >> 1) & 1) + ((bits_mask >> 2) & 1) + ((bits_mask >> 3) & 1);
   const size_t lds = fused_lds_bytes(L, k, plan.SW, n_layouts);
-  FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, x, part, idx_out, gate_out, plan.SW,
-                bits_mask};
+  FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, route_idx, route_gate, x, part,
+                idx_out, gate_out, plan.SW, bits_mask};
   static size_t granted[4] = {0, 0, 0, 0};
   const bool sw = L.act == MOEQ_ACT_SWIGLU, mx = plan.mx != 0;
   const int v = (sw ? 1 : 0) + (mx ? 2 : 0);

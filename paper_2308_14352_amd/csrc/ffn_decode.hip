@@ -18,6 +18,20 @@ __global__ __launch_bounds__(64) void k_topk(LayerDims L, const float* __restric
                    probs ? probs + (size_t)t * L.n_experts : nullptr);
 }
 
+// Caller-supplied routing (static-routing layers, Section 3.1 "Applicability": the experts of a token are
+// known from the input, no router runs): copies idx / gate of the n = T * k pairs to the workspace; a pair
+// whose expert index is outside [0, E) becomes expert 0 with gate 0, i.e. contributes nothing, so that the
+// kernels behind can trust what they read.
+__global__ __launch_bounds__(256) void k_take_routing(const int32_t* __restrict__ idx_in, const float* __restrict__ gate_in,
+                                                      int32_t n, int32_t E, int32_t* __restrict__ idx, float* __restrict__ gate) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int32_t e = idx_in[i];
+  const bool ok = e >= 0 && e < E;
+  idx[i] = ok ? e : 0;
+  gate[i] = ok ? gate_in[i] : 0.f;
+}
+
 // ---------------------------------------------------------------------------------------------
 template <int BITS, bool SWIGLU, typename Stage>
 __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
@@ -168,11 +182,16 @@ __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* _
   const size_t xbytes = L.x_bf16 ? 2 : 4;
   copy_x_to_lds((const char*)x + (size_t)token * d * xbytes, L.x_bf16 ? X_BF16 : X_F32, d, threadIdx.x, blockDim.x, RAW);
   if (fixed_expert < 0) {
-    if (threadIdx.x < 64) topk_from_logits(logits + (size_t)token * L.n_experts, L.n_experts, k, L.renorm,
-                                           threadIdx.x, sel_e, sel_g, nullptr);
+    if (logits) {
+      if (threadIdx.x < 64) topk_from_logits(logits + (size_t)token * L.n_experts, L.n_experts, k, L.renorm,
+                                             threadIdx.x, sel_e, sel_g, nullptr);
+    } else if (threadIdx.x < k) {   // the routing is given: idx_out / gate_out already hold it
+      sel_e[threadIdx.x] = idx_out[(size_t)token * k + threadIdx.x];
+      sel_g[threadIdx.x] = gate_out[(size_t)token * k + threadIdx.x];
+    }
     __syncthreads();
     load_selected(sel_x, table, sel_e, -1, k);
-    if (blockIdx.x == 0 && threadIdx.x < k) {
+    if (logits && blockIdx.x == 0 && threadIdx.x < k) {
       idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
       gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
     }
@@ -431,6 +450,12 @@ hipError_t allow_lds(K kernel, size_t lds, size_t& granted) {
 hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32_t* idx, float* gate, float* probs,
                        hipStream_t st) {
   hipLaunchKernelGGL(k_topk, dim3(T), dim3(64), 0, st, L, logits, idx, gate, probs);
+  return hipGetLastError();
+}
+
+hipError_t launch_take_routing(const int32_t* idx_in, const float* gate_in, int32_t n, int32_t E, int32_t* idx,
+                               float* gate, hipStream_t st) {
+  hipLaunchKernelGGL(k_take_routing, dim3((n + 255) / 256), dim3(256), 0, st, idx_in, gate_in, n, E, idx, gate);
   return hipGetLastError();
 }
 

@@ -33,11 +33,16 @@ hipError_t launch_router_logits(const LayerDims& L, const float* router_w, const
 hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32_t* idx, float* gate,
                        float* probs, hipStream_t st);
 
+// idx[i], gate[i] = the caller's routing of pair i, or (0, 0.0f) when its expert index is not in [0, E).
+hipError_t launch_take_routing(const int32_t* idx_in, const float* gate_in, int32_t n, int32_t E, int32_t* idx,
+                               float* gate, hipStream_t st);
+
 // Phase 1 of the expert FFN: h[slot][f] = act(W_in x [, W_gate x]), stored as binary16 twice: linear
 // (h) and in the staged order phase 2 reads (hp).
 // fixed_expert >= 0: every token uses that expert (slot == token). Otherwise each workgroup derives
 // the token's top-k from `logits`, the routing is written to idx_out/gate_out, the chosen experts'
-// table records to sel_tab[slot], and slot = token * top_k + j.
+// table records to sel_tab[slot], and slot = token * top_k + j; with logits == nullptr the routing is
+// READ from idx_out/gate_out instead (caller-supplied routing, already validated).
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits,
                          int32_t* idx_out, float* gate_out, DevExpert* sel_tab, int32_t fixed_expert,
                          const void* x, int32_t T, uint16_t* h, uint16_t* hp, hipStream_t st);
@@ -56,12 +61,14 @@ FusedPlan plan_fused(const LayerDims& L);
 
 // Router (inline when logits == nullptr: at most fused_inline_router_max() experts) + top-k + both FFN
 // phases of every (slice, token); writes the partial outputs part[T][n_slices][d]. fixed_expert >= 0: that
-// expert for every token, gate_in[T] or 1. bits_mask: bitwidths the call can meet (2 | 4 | 8 or-ed).
+// expert for every token, gate_in[T] or 1. route_idx / route_gate non-null: the routing is given ([T][k],
+// validated), no router runs. bits_mask: bitwidths the call can meet (2 | 4 | 8 or-ed).
 int fused_inline_router_max();
 hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const DevExpert* table,
                              const float* router_w, const float* router_bias, const float* logits,
-                             int32_t fixed_expert, const float* gate_in, int32_t bits_mask, const void* x,
-                             int32_t T, float* part, int32_t* idx_out, float* gate_out, hipStream_t st);
+                             int32_t fixed_expert, const float* gate_in, const int32_t* route_idx,
+                             const float* route_gate, int32_t bits_mask, const void* x, int32_t T, float* part,
+                             int32_t* idx_out, float* gate_out, hipStream_t st);
 // y[t] (+)= sum_s part[t][s], fixed order.
 hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_t T, int accumulate,
                                   float* y, hipStream_t st);

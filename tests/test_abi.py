@@ -111,6 +111,8 @@ def test_compute_entry_points_reject_null_handles_and_shapes():
     L = B.lib()
     assert L.moe_router_topk(None, None, 1, None, None, None, None, 0, None) == B.MOEQ_EINVAL
     assert L.moe_layer_forward(None, None, 1, None, None, None, None, 0, None) == B.MOEQ_EINVAL
+    assert L.moe_layer_forward_routed(None, None, 1, C.c_void_p(256), C.c_void_p(256), None, None, 0, None) == B.MOEQ_EINVAL
+    assert L.moe_layer_forward_routed(None, None, 1, None, None, None, None, 0, None) == B.MOEQ_EINVAL
     assert L.moe_expert_ffn_q(None, 0, None, 1, None, 0, None, None, 0, None) == B.MOEQ_EINVAL
     assert L.moe_quantize_pack(None, 1, 64, 4, 32, None, None, None) == B.MOEQ_EINVAL
     assert L.moe_quantize_pack(C.c_void_p(256), 1, 64, 5, 32, C.c_void_p(256), C.c_void_p(256), None) == B.MOEQ_EINVAL

@@ -192,6 +192,39 @@ def test_layer_forward_small(base, d, f, E, T, columns):
     moeq.moe_layer_forward(layer, x[:0])
 
 
+# ------------------------------------------------------------------ routing given by the caller (static routing)
+@pytest.mark.parametrize("base,d,f,E,T", [
+    ("c1", 256, 512, 8, 5), ("c3", 512, 1024, 32, 8), ("c4", 512, 1792, 8, 3), ("c4", 4096, 512, 8, 2),
+    ("c5", 512, 1024, 8, 40),
+])
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_layer_forward_routed_small(base, d, f, E, T, columns):
+    """moe_layer_forward_routed against the oracle on a seeded routing that names some experts twice and holds
+    indices outside [0, E); then with the router's own decision it must reproduce moe_layer_forward bit for bit."""
+    cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    k = cfg.top_k
+    rng = np.random.default_rng(1000 + T + E)
+    idx = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    idx[0, 0] = -1
+    idx[T - 1, k - 1] = E
+    if k > 1:
+        idx[1, 1] = idx[1, 0]
+    gate = rng.uniform(0.05, 1.2, size=(T, k)).astype(np.float32)
+    y = moeq.moe_layer_forward_routed(layer, x, torch.from_numpy(idx).to(DEV), torch.from_numpy(gate).to(DEV))
+    torch.cuda.synchronize()
+    y_ref = oracle.layer_forward_routed(orc_experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), k,
+                                        x.float().cpu().numpy(), idx, gate)
+    scale = np.abs(y_ref).max()
+    assert np.abs(y.cpu().numpy() - y_ref).max() < TOL * scale
+    y_l, idx_l, gate_l = moeq.moe_layer_forward(layer, x, want_routing=True)
+    y_r = moeq.moe_layer_forward_routed(layer, x, idx_l, gate_l)
+    torch.cuda.synchronize()
+    assert torch.equal(y_l, y_r)
+    moeq.moe_layer_forward_routed(layer, x[:0], idx_l[:0], gate_l[:0])
+
+
 def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
     """Oracle-side experts for the activated ones only; the rest are never dereferenced."""
     dummy = oracle.Expert(4, np.zeros(1, np.uint8), np.zeros(1, np.uint16), np.zeros(1, np.uint8),
@@ -225,6 +258,18 @@ def test_layer_forward_full_size(cfg_id, layer_id, T, columns):
     e = int(idx_ref[0, 0])
     assert np.array_equal(layer.canonical[e].q_in.cpu().numpy(), experts[e].q_in)
     assert np.array_equal(s16(layer.canonical[e].s_out), experts[e].s_out)
+    # the same routing handed back through the static-routing entry gives the same bits, and another
+    # routing (the experts of the next token) what the oracle computes for it
+    y_r = moeq.moe_layer_forward_routed(layer, x, idx, gate)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_r)
+    idx2 = np.roll(idx_ref, 1, axis=0).astype(np.int32)
+    gate2 = np.full_like(gate_ref, 0.75)
+    y2 = moeq.moe_layer_forward_routed(layer, x, torch.from_numpy(idx2).to(DEV), torch.from_numpy(gate2).to(DEV))
+    torch.cuda.synchronize()
+    y2_ref = oracle.layer_forward_routed(experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), cfg.top_k,
+                                         x.float().cpu().numpy(), idx2, gate2)
+    assert rel_err(y2.cpu().numpy(), y2_ref).max() < TOL
 
 
 @pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))

@@ -278,3 +278,35 @@ def test_layer_handles_zero_tokens():
     experts, _, Wr = build_layer(rng, 32, 64, 3, 32, False)
     y, idx, gate = oracle.layer_forward(experts, 32, 64, 32, 0, 1, False, Wr, None, np.zeros((0, 32), np.float32))
     assert y.shape == (0, 32) and idx.shape == (0, 1)
+
+
+# ------------------------------------------------------------------ routing given by the caller
+@pytest.mark.parametrize("swiglu", (False, True))
+def test_given_routing_equals_gate_weighted_sum_of_dense_ffns_on_lossless_weights(swiglu):
+    """Section 3.1 ("Applicability"), static routing: the experts of a token are given. On losslessly
+    quantizable weights the result is the plain gate-weighted sum of textbook dense FFNs; an index outside
+    [0, E) contributes nothing, an expert named twice counts twice."""
+    rng = np.random.default_rng(40)
+    d, f, E, g, T, k = 64, 96, 6, 32, 6, 2
+    experts, dense, _ = build_layer(rng, d, f, E, g, swiglu, lossless=True)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    idx = np.array([[0, 5], [3, 3], [2, -1], [E, 1], [4, 0], [7, -3]], np.int32)
+    gate = rng.uniform(0.1, 1.5, size=(T, k)).astype(np.float32)
+    y = oracle.layer_forward_routed(experts, d, f, g, int(swiglu), k, x, idx, gate)
+    for t in range(T):
+        ref = np.zeros(d)
+        for j in range(k):
+            if 0 <= idx[t, j] < E:
+                ref += np.float64(gate[t, j]) * dense_ffn(*dense[idx[t, j]], x[t:t + 1])[0][0]
+        assert np.allclose(y[t], ref, rtol=1e-5, atol=1e-6 * max(np.abs(ref).max(), 1e-3))
+    assert np.all(y[5] == 0.0)
+
+
+def test_given_routing_with_the_routers_own_decision_reproduces_the_layer():
+    rng = np.random.default_rng(41)
+    d, f, E, g, T, k = 64, 96, 5, 32, 5, 2
+    experts, _, Wr = build_layer(rng, d, f, E, g, True, lossless=False)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    y, idx, gate = oracle.layer_forward(experts, d, f, g, 1, k, True, Wr, None, x)
+    y2 = oracle.layer_forward_routed(experts, d, f, g, 1, k, x, idx, gate)
+    assert np.array_equal(y, y2)
