@@ -22,7 +22,8 @@ namespace moeq {
 namespace {
 
 constexpr int kTB = 64;        // tokens per work item
-constexpr int kGemmThreads = 256;
+constexpr int kGemmThreads = 512;
+constexpr int kGemmWaves = kGemmThreads / 64;
 
 // ---------------------------------------------------------------------------------------------
 // grouping
@@ -169,7 +170,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   constexpr int NQ = BITS == 8 ? 2 : 4;           // instructions per step, stream and token block
   constexpr int NS = 4;                           // streams per wavefront
   constexpr int RBW = NS / NM;                    // row blocks per wavefront and matrix
-  constexpr int BN = 4 * RBW * 16;                // rows per workgroup
+  constexpr int BN = kGemmWaves * RBW * 16;       // rows per workgroup
   constexpr int APAD = 65;                        // tokens per (q, kb) line of the LDS tile, padded
   using TileT = std::conditional_t<BITS == 2, uint2, uint4>;
   const int K = PHASE == 0 ? G.L.d_model : G.L.d_ff;
@@ -244,8 +245,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
 #pragma unroll
     for (int t4 = 0; t4 < 4; ++t4) acc[s][t4] = zero;
 
-  auto compute = [&](const BSet& B, int buf) __attribute__((always_inline)) {
-    half8_t Bop[NS][NQ];
+  // The arithmetic of a step is split in two so that the raw tiles' registers can take the next step's
+  // loads as soon as the codes are unpacked: one set of tile registers serves the whole loop.
+  half8_t Bop[NS][NQ];
+  float sc[NS];
+  auto unpack = [&](const BSet& B) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       if constexpr (BITS == 4) {
@@ -257,17 +261,18 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
         Bop[s][0] = codes8<2, 0>(B.t[s].x, 0u); Bop[s][1] = codes8<2, 1>(B.t[s].x, 0u);
         Bop[s][2] = codes8<2, 0>(B.t[s].y, 0u); Bop[s][3] = codes8<2, 1>(B.t[s].y, 0u);
       }
+      sc[s] = f16_bits_to_f32(B.sc[s]);
     }
-    float sc[NS];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) sc[s] = f16_bits_to_f32(B.sc[s]);
+  };
+  auto multiply = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int t4 = 0; t4 < 4; ++t4) {
+      // the accumulation starts at the negated offset terms of the lane's four tokens
       const float4 k4 = *(const float4*)(Ks + buf * kTB + 16 * t4 + 4 * kb);
-      const float4_t kv = {k4.x, k4.y, k4.z, k4.w};
+      const float4_t kv = {-k4.x, -k4.y, -k4.z, -k4.w};
       float4_t D[NS];
 #pragma unroll
-      for (int s = 0; s < NS; ++s) D[s] = zero;
+      for (int s = 0; s < NS; ++s) D[s] = kv;
 #pragma unroll
       for (int q = 0; q < NQ; ++q) {
         const half8_t A = as_half8(As[(buf * NQ * 4 + q * 4 + kb) * APAD + 16 * t4 + n]);
@@ -275,28 +280,23 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
         for (int s = 0; s < NS; ++s) D[s] = mfma16(A, Bop[s][q], D[s]);
       }
 #pragma unroll
-      for (int s = 0; s < NS; ++s) acc[s][t4] += sc[s] * (D[s] - kv);
+      for (int s = 0; s < NS; ++s) acc[s][t4] += sc[s] * D[s];
     }
   };
 
-  BSet B0, B1;
+  BSet B;
   ASet A0;
   load_a(A0, 0);
-  load_b(B0, 0);
+  load_b(B, 0);
   store_a(A0, 0);
   __syncthreads();
-  for (int step = 0; step < n_steps; step += 2) {
-    // even step: tiles in B0 / LDS buffer 0; odd step: B1 / buffer 1
-    if (step + 1 < n_steps) { load_a(A0, step + 1); load_b(B1, step + 1); }
-    compute(B0, 0);
-    if (step + 1 < n_steps) store_a(A0, 1);
+  for (int step = 0; step < n_steps; ++step) {
+    const int buf = step & 1;
+    unpack(B);
+    if (step + 1 < n_steps) { load_a(A0, step + 1); load_b(B, step + 1); }
+    multiply(buf);
+    if (step + 1 < n_steps) store_a(A0, buf ^ 1);
     __syncthreads();
-    if (step + 1 < n_steps) {
-      if (step + 2 < n_steps) { load_a(A0, step + 2); load_b(B0, step + 2); }
-      compute(B1, 1);
-      if (step + 2 < n_steps) store_a(A0, 0);
-      __syncthreads();
-    }
   }
 
   // D element i of lane (n, kb) belongs to token 16*t4 + 4*kb + i and row n of the stream
@@ -415,13 +415,13 @@ hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void
   GemmArgs G{L, table, blocks, nblk, poff, XA, (int64_t)w.a_pair_words, HA, (int64_t)w.h_pair_words, Ypair};
   const unsigned nb = (unsigned)w.max_blocks;
   if (L.act == MOEQ_ACT_SWIGLU)
-    hipLaunchKernelGGL((k_gemm_q<2, 0>), dim3((L.d_ff + 127) / 128, nb), dim3(kGemmThreads), 0, st, G);
+    hipLaunchKernelGGL((k_gemm_q<2, 0>), dim3((L.d_ff + kGemmWaves * 32 - 1) / (kGemmWaves * 32), nb), dim3(kGemmThreads), 0, st, G);
   else
-    hipLaunchKernelGGL((k_gemm_q<1, 0>), dim3((L.d_ff + 255) / 256, nb), dim3(kGemmThreads), 0, st, G);
+    hipLaunchKernelGGL((k_gemm_q<1, 0>), dim3((L.d_ff + kGemmWaves * 64 - 1) / (kGemmWaves * 64), nb), dim3(kGemmThreads), 0, st, G);
   hipLaunchKernelGGL(k_h_sums, dim3(M), dim3(256), 0, st, L, table, gexp, HA, (int64_t)w.h_pair_words);
   G.A = HA;
   G.a_pair_words = (int64_t)w.h_pair_words;
-  hipLaunchKernelGGL((k_gemm_q<1, 1>), dim3((L.d_model + 255) / 256, nb), dim3(kGemmThreads), 0, st, G);
+  hipLaunchKernelGGL((k_gemm_q<1, 1>), dim3((L.d_model + kGemmWaves * 64 - 1) / (kGemmWaves * 64), nb), dim3(kGemmThreads), 0, st, G);
   hipLaunchKernelGGL(k_combine, dim3(T), dim3(256), 0, st, Ypair, ginv, gate, L.top_k, L.d_model, y);
   return hipGetLastError();
 }
