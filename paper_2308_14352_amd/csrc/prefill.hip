@@ -235,7 +235,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
       const int akb = item & 3, tok = (item >> 2) & 63, q = item >> 8;
       As[(buf * NQ * 4 + q * 4 + akb) * APAD + tok] = A.v[r];
     }
-    if (threadIdx.x < kTB) Ks[buf * kTB + threadIdx.x] = A.ks;
+    if (threadIdx.x < kTB) Ks[buf * kTB + threadIdx.x] = -A.ks;   // negated: the accumulations start there
   };
 
   float4_t acc[NS][4];
@@ -269,7 +269,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
     for (int t4 = 0; t4 < 4; ++t4) {
       // the accumulation starts at the negated offset terms of the lane's four tokens
       const float4 k4 = *(const float4*)(Ks + buf * kTB + 16 * t4 + 4 * kb);
-      const float4_t kv = {-k4.x, -k4.y, -k4.z, -k4.w};
+      const float4_t kv = {k4.x, k4.y, k4.z, k4.w};
       float4_t D[NS];
 #pragma unroll
       for (int s = 0; s < NS; ++s) D[s] = kv;
@@ -284,20 +284,39 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
     }
   };
 
+  // Step s multiplies the A tile in LDS buffer s & 1 with the B tiles unpacked at its start. The A tile of
+  // step s + 1 was requested during step s - 1 and goes to the other LDS buffer at the start of step s (all
+  // wavefronts are past the barrier that ended the last reads of that buffer); then the B tiles of step
+  // s + 1 and the A tile of step s + 2 are requested: every load has a whole step to arrive. The last two
+  // steps are peeled so that the loop body holds no condition on the step number.
   BSet B;
   ASet A0;
   load_a(A0, 0);
   load_b(B, 0);
   store_a(A0, 0);
+  if (n_steps > 1) load_a(A0, 1);
   __syncthreads();
-  for (int step = 0; step < n_steps; ++step) {
+  int step = 0;
+  for (; step + 2 < n_steps; ++step) {
     const int buf = step & 1;
     unpack(B);
-    if (step + 1 < n_steps) { load_a(A0, step + 1); load_b(B, step + 1); }
+    load_b(B, step + 1);
+    store_a(A0, buf ^ 1);
+    load_a(A0, step + 2);
     multiply(buf);
-    if (step + 1 < n_steps) store_a(A0, buf ^ 1);
     __syncthreads();
   }
+  if (step + 1 < n_steps) {
+    const int buf = step & 1;
+    unpack(B);
+    load_b(B, step + 1);
+    store_a(A0, buf ^ 1);
+    multiply(buf);
+    __syncthreads();
+    ++step;
+  }
+  unpack(B);
+  multiply(step & 1);
 
   // D element i of lane (n, kb) belongs to token 16*t4 + 4*kb + i and row n of the stream
   if constexpr (PHASE == 0) {
