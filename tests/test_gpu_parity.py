@@ -345,3 +345,48 @@ def test_prefill_full_size_mixtral_layer_on_sampled_tokens():
     y_ref, _, _ = oracle_layer(cfg, experts, Wr, bias, x[sample])
     assert rel_err(y.cpu().numpy()[sample], y_ref).max() < PREFILL_TOL
     assert torch.isfinite(y).all()
+
+
+# ------------------------------------------------------------------ bitwidth-sensitivity harness (synthetic data)
+def test_sensitivity_harness_matches_the_oracle_and_orders_bitwidths():
+    """Section 3.2 ("Profiling expert importance", "Selecting expert-wise bitwidths") with the output error in
+    place of accuracy: the per-expert errors computed through the library equal those computed from the
+    oracle's quantized FFN and a float64 numpy dense FFN; lower bitwidths lose more; the selection lowers
+    experts in the order of the list and stops at the tolerated loss."""
+    from paper_2308_14352_amd import sensitivity as S
+    cfg = gen.tiny_config("c4", 256, 512, n_experts=6, n_layers=1)
+    weights = [gen.expert_weights(cfg, 0, e, DEV) for e in range(cfg.n_experts)]
+    # make the experts differ in how well they quantize: heavier tails in some
+    for e in (1, 4):
+        for k in weights[e]:
+            w = weights[e][k]
+            w[:, ::37] *= 6.0
+    x = gen.normal((24, cfg.d_model), 1.0, 4242, DEV)
+    err = S.expert_errors(weights, x, cfg.group, cfg.swiglu, (2, 4, 8))
+    assert np.all(err[:, 0] > err[:, 1]) and np.all(err[:, 1] > err[:, 2]) and np.all(err[:, 2] > 0)
+    xh = x.cpu().numpy()
+    for e in (0, 4):
+        host = {k: v.cpu().numpy() for k, v in weights[e].items()}
+        a = xh.astype(np.float64) @ host["w_in"].astype(np.float64).T
+        h = a / (1.0 + np.exp(-a)) * (xh.astype(np.float64) @ host["w_gate"].astype(np.float64).T)
+        ref = h @ host["w_out"].astype(np.float64).T
+        for i, b in enumerate((2, 4, 8)):
+            y = oracle.expert_ffn(pack_expert_oracle(weights[e], b, cfg.group), cfg.d_model, cfg.d_ff, cfg.group,
+                                  int(cfg.swiglu), xh)
+            want = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+            assert abs(err[e, i] - want) < 2e-3 * want + 1e-6
+    order = S.importance_order(err[:, 0])
+    assert sorted(order) == list(range(cfg.n_experts))
+    assert all(err[order[i], 0] <= err[order[i + 1], 0] for i in range(len(order) - 1))
+    Wr, bias = gen.router_weights(cfg, 0, DEV)
+    base = S.layer_loss(weights, [4] * cfg.n_experts, x, cfg.top_k, cfg.group, cfg.swiglu, cfg.renorm, Wr, bias)
+    full = S.layer_loss(weights, [2] * cfg.n_experts, x, cfg.top_k, cfg.group, cfg.swiglu, cfg.renorm, Wr, bias)
+    assert 0 < base < full
+    goal = 0.5 * (base + full)
+    table, K, loss, tried = S.select_bitwidths(weights, x, cfg.top_k, cfg.group, cfg.swiglu, cfg.renorm, Wr, bias,
+                                               goal, 2, 4, order)
+    assert 0 <= K < cfg.n_experts and loss <= goal and len(tried) == K + 1
+    assert [e for e in range(cfg.n_experts) if table[e] == 2] == sorted(order[:K])
+    nxt = list(table)
+    nxt[order[K]] = 2
+    assert S.layer_loss(weights, nxt, x, cfg.top_k, cfg.group, cfg.swiglu, cfg.renorm, Wr, bias) > goal
