@@ -993,39 +993,58 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
 }
 
 // y[t][r] (+)= sum over the slices of part[t][s][r], in a fixed order. Workgroup = 16 outputs x 64 slice
-// teams: team g sums the slices g, g+64, ... for its 4 outputs, then the 64 team sums are added pairwise in
-// a fixed tree. Small workgroups on many compute units: the kernel is one memory round trip long.
+// teams: team g sums the slices g, g+64, ... for its 4 outputs, then the 64 team sums are added in a fixed
+// tree (a butterfly over the lanes of a wavefront, then the wavefronts in order). Small workgroups on many
+// compute units: the kernel is one memory round trip long.
 __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ part, int n_slices, int d,
                                                          int accumulate, float* __restrict__ y) {
-  __shared__ float4 red[64][4];
+  __shared__ float4 red[4][4];
   const int token = blockIdx.y;
   const int rq = threadIdx.x & 3, sg = threadIdx.x >> 2;
-  const int r0 = blockIdx.x * 16 + rq * 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool in_range = (int)blockIdx.x * 16 + rq * 4 < d;     // d is a multiple of 8, not always of 16
+  const int r0 = min((int)blockIdx.x * 16 + rq * 4, d - 4);   // clamped columns are summed but not written
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (r0 < d) {
-    const float* p = part + (size_t)token * n_slices * d + r0;
-    for (int s = sg; s < n_slices; s += 64) {
-      const float4 v = *(const float4*)(p + (size_t)s * d);
-      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+  const float* p = part + (size_t)token * n_slices * d + r0;
+  // four slices per pass, requested together (one memory round trip per pass); slices past the end read the
+  // last one and are weighted with zero, so that the loads need no condition
+  for (int s0 = sg; s0 < n_slices; s0 += 256) {
+    float4 v[4];
+    float w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int s = s0 + 64 * u;
+      w[u] = s < n_slices ? 1.f : 0.f;
+      v[u] = *(const float4*)(p + (size_t)min(s, n_slices - 1) * d);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a.x = fmaf(v[u].x, w[u], a.x); a.y = fmaf(v[u].y, w[u], a.y);
+      a.z = fmaf(v[u].z, w[u], a.z); a.w = fmaf(v[u].w, w[u], a.w);
     }
   }
-  red[sg][rq] = a;
+  // the 16 teams of a wavefront (lanes 4 apart hold the same columns) in a fixed butterfly, then the four
+  // wavefronts in order
+#pragma unroll
+  for (int off = 4; off < 64; off <<= 1) {
+    a.x += __shfl_xor(a.x, off); a.y += __shfl_xor(a.y, off);
+    a.z += __shfl_xor(a.z, off); a.w += __shfl_xor(a.w, off);
+  }
+  if (lane < 4) red[wave][lane] = a;
   __syncthreads();
-  for (int half = 32; half >= 1; half >>= 1) {
-    if (sg < half) {
-      const float4 v = red[sg + half][rq];
-      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
-      red[sg][rq] = a;
+  if (threadIdx.x < 4 && in_range) {
+    float4 t = red[0][rq];
+#pragma unroll
+    for (int wv = 1; wv < 4; ++wv) {
+      const float4 v = red[wv][rq];
+      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
     }
-    __syncthreads();
-  }
-  if (sg == 0 && r0 < d) {
     float4* o = (float4*)(y + (size_t)token * d + r0);
     if (accumulate) {
       const float4 v = *o;
-      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
     }
-    *o = a;
+    *o = t;
   }
 }
 
