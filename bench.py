@@ -181,8 +181,8 @@ class HipEvents:
 
 
 def dominant_kernel_events(stack, steps, idx):
-    """Eager pass over `steps` steps with a HIP event pair recorded by the library around the
-    dominant kernel of every layer call, on the stream the kernel runs on: k_moe_decode (the whole layer
+    """Eager pass over `steps` steps with a HIP event pair the library attaches to the dominant kernel
+    of every layer call (begin and end of the kernel's execution on its stream): k_moe_decode (the whole layer
     but the final sum of partial vectors) with W_out in columns, else k_ffn_in (phase 1, about two thirds
     of the bytes). Returns (mean duration in ms, mean algorithmic bytes of that kernel)."""
     import numpy as np

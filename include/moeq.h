@@ -179,8 +179,10 @@ moeq_status moe_unprepare_out(const void *q_cols, const void *s_cols, int64_t ro
 /* Measurement aid. While `which` names a kernel, every moe_layer_forward
  * call records start_event just before and stop_event just after that kernel on the call's stream
  * (hipEvent_t handles created by the caller with timing enabled), so a benchmark can time the
- * dominant kernel alone. which = 0 turns it off. Process-wide, not thread-safe; do not use under
- * stream capture. */
+ * dominant kernel alone. For MOEQ_KERNEL_FUSED the two events are attached to the kernel launch
+ * itself and receive the begin and end of the kernel's execution (what a kernel trace reports),
+ * without the dispatch before it. which = 0 turns it off. Process-wide, not thread-safe; do not
+ * use under stream capture. */
 #define MOEQ_KERNEL_FFN_IN 1  /* phase 1: top-k + W_in / W_gate GEMVs (Section 3.2, dequantize-fused) */
 #define MOEQ_KERNEL_FFN_OUT 2 /* phase 2: W_out GEMVs + gate-weighted combine                          */
 #define MOEQ_KERNEL_FUSED 3   /* the one-kernel path: router, top-k and both phases of every d_ff slice */

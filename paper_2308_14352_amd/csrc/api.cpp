@@ -264,10 +264,12 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
     }
     float* part = (float*)((char*)ws + w.part_off);
     {
-      ScopedEvents ev(MOEQ_KERNEL_FUSED, st);
+      // the profiling events, when asked for, bracket the kernel's own execution (not its dispatch)
+      const bool prof = g_profile.which == MOEQ_KERNEL_FUSED && g_profile.start && g_profile.stop;
       if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias, lg, -1, nullptr,
                             given ? idx : nullptr, given ? gate : nullptr, layer->bits_mask, x, n_tokens, part,
-                            given ? nullptr : idx, given ? nullptr : gate, st) != hipSuccess)
+                            given ? nullptr : idx, given ? nullptr : gate, st, prof ? g_profile.start : nullptr,
+                            prof ? g_profile.stop : nullptr) != hipSuccess)
         return MOEQ_EDEVICE;
     }
     return dev(launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n_tokens, 0, y, st));

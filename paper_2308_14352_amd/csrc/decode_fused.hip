@@ -18,6 +18,8 @@
 // lanes read consecutive addresses, and the partial dot products need no cross-lane reduction at all.
 #include <cstdlib>
 
+#include <hip/hip_ext.h>
+
 #include "decode_core.h"
 
 namespace moeq {
@@ -1125,7 +1127,7 @@ hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const De
                              const float* router_bias, const float* logits, int32_t fixed_expert,
                              const float* gate_in, const int32_t* route_idx, const float* route_gate,
                              int32_t bits_mask, const void* x, int32_t T, float* part, int32_t* idx_out,
-                             float* gate_out, hipStream_t st) {
+                             float* gate_out, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (!plan.SW || T < 1 || T > 65535 || !(bits_mask & 14)) return hipErrorInvalidValue;
   if (!logits && !route_idx && fixed_expert < 0 && L.n_experts > kInlineMaxE) return hipErrorInvalidValue;
   if ((route_idx != nullptr) != (route_gate != nullptr)) return hipErrorInvalidValue;
@@ -1144,7 +1146,10 @@ hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const De
     if (e != hipSuccess) return e;
     granted[v] = lds;
   }
-  hipLaunchKernelGGL(kernel, dim3(plan.n_slices, T), dim3(plan.threads), lds, st, P);
+  if (ev_start && ev_stop)
+    hipExtLaunchKernelGGL(kernel, dim3(plan.n_slices, T), dim3(plan.threads), lds, st, ev_start, ev_stop, 0, P);
+  else
+    hipLaunchKernelGGL(kernel, dim3(plan.n_slices, T), dim3(plan.threads), lds, st, P);
   return hipGetLastError();
 }
 

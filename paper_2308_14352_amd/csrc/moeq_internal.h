@@ -62,13 +62,15 @@ FusedPlan plan_fused(const LayerDims& L);
 // Router (inline when logits == nullptr: at most fused_inline_router_max() experts) + top-k + both FFN
 // phases of every (slice, token); writes the partial outputs part[T][n_slices][d]. fixed_expert >= 0: that
 // expert for every token, gate_in[T] or 1. route_idx / route_gate non-null: the routing is given ([T][k],
-// validated), no router runs. bits_mask: bitwidths the call can meet (2 | 4 | 8 or-ed).
+// validated), no router runs. bits_mask: bitwidths the call can meet (2 | 4 | 8 or-ed). ev_start / ev_stop
+// (both or none): events that receive the begin and end of the kernel's own execution.
 int fused_inline_router_max();
 hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const DevExpert* table,
                              const float* router_w, const float* router_bias, const float* logits,
                              int32_t fixed_expert, const float* gate_in, const int32_t* route_idx,
                              const float* route_gate, int32_t bits_mask, const void* x, int32_t T, float* part,
-                             int32_t* idx_out, float* gate_out, hipStream_t st);
+                             int32_t* idx_out, float* gate_out, hipStream_t st, hipEvent_t ev_start = nullptr,
+                             hipEvent_t ev_stop = nullptr);
 // y[t] (+)= sum_s part[t][s], fixed order.
 hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_t T, int accumulate,
                                   float* y, hipStream_t st);
