@@ -856,16 +856,22 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       take(wave);                     // n_tasks >= 64 > wave
       issue(A, ta);
       issue(B, tb);
-      while (ta.valid) {
-        // priority by the tasks still ahead (n_tasks / nwaves = 4k at the start)
-        const int left = (n_tasks - ta.t) / nwaves;
-        if (left >= 6) __builtin_amdgcn_s_setprio(3);
-        else if (left >= 4) __builtin_amdgcn_s_setprio(2);
-        else if (left >= 2) __builtin_amdgcn_s_setprio(1);
+      // priority by the tasks still ahead, finest near the end of the list where the drift would show
+      auto prio = [&](int t) __attribute__((always_inline)) {
+        const int left = (n_tasks - 1 - t) / nwaves;      // tasks after this one
+        if (left >= 3) __builtin_amdgcn_s_setprio(3);
+        else if (left == 2) __builtin_amdgcn_s_setprio(2);
+        else if (left == 1) __builtin_amdgcn_s_setprio(1);
         else __builtin_amdgcn_s_setprio(0);
+      };
+      while (ta.valid) {
+        prio(ta.t);
         compute(A, ta);
         issue(A, ta);
-        if (tb.valid) compute(B, tb);
+        if (tb.valid) {
+          prio(tb.t);
+          compute(B, tb);
+        }
         issue(B, tb);
       }
       __builtin_amdgcn_s_setprio(0);
@@ -926,20 +932,32 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       MxSet2 A, B;
       issue2(A);                      // ns >= 1
       __syncthreads();                // the h slices of all chosen experts are complete in LDS
+      // as in phase 1, a wavefront's priority falls with the sets it has left
+      auto prio2 = [&](int left) __attribute__((always_inline)) {
+        if (left >= 3) __builtin_amdgcn_s_setprio(3);
+        else if (left == 2) __builtin_amdgcn_s_setprio(2);
+        else if (left == 1) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+      };
       int b = 0;
       for (; b + 2 < ns; b += 2) {
         issue2(B);
+        prio2(ns - 1 - b);
         compute2(A);
         issue2(A);
+        prio2(ns - 2 - b);
         compute2(B);
       }
       if (b + 1 < ns) {
         issue2(B);
+        prio2(1);
         compute2(A);
+        prio2(0);
         compute2(B);
       } else {
         compute2(A);
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();   // Y was written by the lanes that hold the instruction results, it is read by all
   } else {
