@@ -542,8 +542,9 @@ __device__ __forceinline__ void mx1_store_h(int c, const float (&r)[NM], uint16_
 }
 
 // One requested burst: the arithmetic, and, when it completes a row, the sum of the lanes' shares over the
-// wavefront; lane i keeps the sums of the wavefront's i-th finished row (rows_done counts them), and the
-// activation is applied to all of them at once when the list is through.
+// 16-lane rows of the wavefront; the lanes i, 16 + i, 32 + i, 48 + i keep these four partial sums of the
+// wavefront's i-th finished row (rows_done counts them, at most 16), and the caller adds them and applies the
+// activation to all rows at once (every 16 rows and when the list is through).
 template <int BITS, bool SWIGLU>
 __device__ __forceinline__ void mx1_compute(const MxSet1& S, const MxTag1& tag, int d, int lane, const float (&dm)[4],
                                             const uint32_t* XP, const float* KS, float (&acc)[SWIGLU ? 2 : 1],
@@ -557,8 +558,13 @@ __device__ __forceinline__ void mx1_compute(const MxSet1& S, const MxTag1& tag, 
   if (tag.jb + 1 == tag.JB) {
 #pragma unroll
     for (int mm = 0; mm < NM; ++mm) {
-      const float r = wave_sum(acc[mm]);
-      keep[mm] = lane == rows_done ? r : keep[mm];
+      // sums over the four 16-lane rows of the wavefront; the four of them are added when the rows are flushed
+      float r = acc[mm];
+      r += dpp<kDppXor1>(r);
+      r += dpp<kDppXor2>(r);
+      r += dpp<kDppRor4>(r);
+      r += dpp<kDppRor8>(r);
+      keep[mm] = (lane & 15) == rows_done ? r : keep[mm];
     }
     ++rows_done;
   }
@@ -682,6 +688,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
+  __shared__ int sel_b[8];                                // bitwidths of the chosen experts
   __shared__ float rpart[kInlineMaxE * (kMaxSegs + 1)];   // router partial sums, unit u = e * n_seg + seg
   __shared__ DevExpert tab[kTabLds];
   const LayerDims& L = P.L;
@@ -802,8 +809,12 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
 
   if constexpr (MX) {
     constexpr int NM = SWIGLU ? 2 : 1;
-    if (wave == 0) route();
-    else stage_layouts(threadIdx.x - 64, nthreads - 64);
+    if (wave == 0) {
+      route();
+      if (lane < k) sel_b[lane] = (tab_in_lds ? tab[sel_e[lane]] : P.table[sel_e[lane]]).bits;
+    } else {
+      stage_layouts(threadIdx.x - 64, nthreads - 64);
+    }
     __syncthreads();  // layouts, sel_e, sel_g are complete
     publish_routing();
     const DevExpert* tabp = tab_in_lds ? tab : P.table;
@@ -840,7 +851,33 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     float acc[NM], keep[NM];
 #pragma unroll
     for (int mm = 0; mm < NM; ++mm) keep[mm] = 0.f;
-    int rows_done = 0;
+    int rows_done = 0, rows_flushed = 0;
+    // the activation of the wavefront's parked rows: lane i holds the task wave + (rows_flushed + i) * nwaves
+    auto flush_rows = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) {
+        keep[mm] += __shfl_xor(keep[mm], 16);
+        keep[mm] += __shfl_xor(keep[mm], 32);
+      }
+      if (lane < rows_done) {
+        const int t = wave + (rows_flushed + lane) * nwaves, j = t >> 6, u = t & 63;
+        const int c = ((u & 15) << 2) | (((u >> 4) + slice) & 3);
+        float r[NM];
+#pragma unroll
+        for (int mm = 0; mm < NM; ++mm) r[mm] = keep[mm] * 16777216.0f;
+        uint16_t* HL = HLs + j * SW;
+        uint16_t* HP = HPs + j * SW;
+        switch (sel_b[j]) {
+          case 2: mx1_store_h<2, SWIGLU, NM>(c, r, HL, HP); break;
+          case 4: mx1_store_h<4, SWIGLU, NM>(c, r, HL, HP); break;
+          default: mx1_store_h<8, SWIGLU, NM>(c, r, HL, HP); break;
+        }
+      }
+      rows_flushed += rows_done;
+      rows_done = 0;
+#pragma unroll
+      for (int mm = 0; mm < NM; ++mm) keep[mm] = 0.f;
+    };
     auto compute = [&](const MxSet1& S, const MxTag1& tag) __attribute__((always_inline)) {
       const uint32_t* XP = LAY + layout_slot(P.bits_mask, tag.bits) * lay_words;
       const float* KS = (const float*)(XP + d / 2);
@@ -849,6 +886,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
         case 4: mx1_compute<4, SWIGLU>(S, tag, d, lane, dm, XP, KS, acc, keep, rows_done); break;
         default: mx1_compute<8, SWIGLU>(S, tag, d, lane, dm, XP, KS, acc, keep, rows_done); break;
       }
+      if (rows_done == 16) flush_rows();
     };
     {
       MxSet1 A, B;
@@ -876,21 +914,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       }
       __builtin_amdgcn_s_setprio(0);
     }
-    // the activation of the wavefront's rows: lane i finished the task wave + i * nwaves
-    if (lane < rows_done) {
-      const int t = wave + lane * nwaves, j = t >> 6, u = t & 63;
-      const int c = ((u & 15) << 2) | (((u >> 4) + slice) & 3);
-      float r[NM];
-#pragma unroll
-      for (int mm = 0; mm < NM; ++mm) r[mm] = keep[mm] * 16777216.0f;
-      uint16_t* HL = HLs + j * SW;
-      uint16_t* HP = HPs + j * SW;
-      switch (tabp[sel_e[j]].bits) {
-        case 2: mx1_store_h<2, SWIGLU, NM>(c, r, HL, HP); break;
-        case 4: mx1_store_h<4, SWIGLU, NM>(c, r, HL, HP); break;
-        default: mx1_store_h<8, SWIGLU, NM>(c, r, HL, HP); break;
-      }
-    }
+    if (rows_done > 0) flush_rows();
     // ---- phase 2: one list of register sets through all chosen experts; the first set is requested ahead
     // of the barrier between the phases
     MxWalk2 vi, vc;
