@@ -238,19 +238,52 @@ __device__ __forceinline__ void offset_terms(const uint16_t* lin, int cols, int 
 template <int BITS>
 __device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS);
 
+// Two binary16 halves of two registers as one pair register: (lo of a, lo of b) or (hi of a, hi of b).
+__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+// Both halves of a pair register times a power of two (one packed multiply; exact, or the single rounding to
+// a binary16 subnormal that a widened multiply followed by a conversion gives as well).
+__device__ __forceinline__ uint32_t pair_scale(uint32_t p, float s) {
+  const half2_t v = __builtin_bit_cast(half2_t, p) * (half2_t){(_Float16)s, (_Float16)s};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// The staged layout, written with 16-byte accesses: the four pair registers of a quad (pair_pos) are made of
+// eight (2-bit codes: sixteen) consecutive activations, so one work item turns one or two 16-byte reads of
+// RAW into one or two 16-byte writes: quad q of chunk c goes to XP4[q * C + c].
 template <int BITS, bool RANGES = false>
 __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int group, int tid, int nthreads,
                                           uint32_t* XP, float* XK) {
-  constexpr int WPC = Fmt<BITS>::WPC, PPC = Fmt<BITS>::PPC;
+  constexpr int WPC = Fmt<BITS>::WPC;
   const int C = cols / WPC;
-  for (int i = tid; i < cols / 2; i += nthreads) {
-    const int c = i / PPC, pi = i % PPC;
-    int lo, hi;
-    float ps;
-    pair_pos<BITS>(pi, lo, hi, ps);
-    const uint32_t bl = f32_to_f16_bits(f16_bits_to_f32(RAW[c * WPC + lo]) * ps);
-    const uint32_t bh = f32_to_f16_bits(f16_bits_to_f32(RAW[c * WPC + hi]) * ps);
-    XP[((pi >> 2) * C + c) * 4 + (pi & 3)] = bl | (bh << 16);
+  const uint4* R4 = (const uint4*)RAW;
+  uint4* X4 = (uint4*)XP;
+  if constexpr (BITS == 4) {
+    // chunk = 32 activations = 4 reads; quad d = dword d of the codes: pairs (k, k+4), odd k pre-divided by 16
+    for (int i = tid; i < 4 * C; i += nthreads) {
+      const int q = i / C, c = i - q * C;
+      const uint4 v = R4[c * 4 + q];
+      X4[i] = make_uint4(pair_lo(v.x, v.z), pair_scale(pair_hi(v.x, v.z), 0.0625f), pair_lo(v.y, v.w),
+                         pair_scale(pair_hi(v.y, v.w), 0.0625f));
+    }
+  } else if constexpr (BITS == 8) {
+    // chunk = 16 activations = 2 reads; quad q = dwords 2q, 2q+1 of the codes: pairs (k, k+2)
+    for (int i = tid; i < 2 * C; i += nthreads) {
+      const int q = i / C, c = i - q * C;
+      const uint4 v = R4[c * 2 + q];
+      X4[i] = make_uint4(pair_lo(v.x, v.y), pair_hi(v.x, v.y), pair_lo(v.z, v.w), pair_hi(v.z, v.w));
+    }
+  } else {
+    // chunk = 64 activations = 8 reads; dword d of the codes: pairs (j, j+8), j = 0..7, in the quads 2d
+    // (j = 0..3, pre-divided by 1, 4, 16, 64) and 2d+1 (j = 4..7, pre-divided by 256, 1, 4, 16)
+    for (int i = tid; i < 4 * C; i += nthreads) {
+      const int dd = i / C, c = i - dd * C;
+      const uint4 a = R4[c * 8 + 2 * dd], b = R4[c * 8 + 2 * dd + 1];
+      X4[(2 * dd) * C + c] = make_uint4(pair_lo(a.x, b.x), pair_scale(pair_hi(a.x, b.x), 0.25f),
+                                        pair_scale(pair_lo(a.y, b.y), 0.0625f), pair_scale(pair_hi(a.y, b.y), 0.015625f));
+      X4[(2 * dd + 1) * C + c] = make_uint4(pair_scale(pair_lo(a.z, b.z), 0.00390625f), pair_hi(a.z, b.z),
+                                            pair_scale(pair_lo(a.w, b.w), 0.25f), pair_scale(pair_hi(a.w, b.w), 0.0625f));
+    }
   }
   if constexpr (RANGES) range_offset_terms<BITS>(RAW, cols, tid, nthreads, XK);
   else offset_terms<BITS>(RAW, cols, group, tid, nthreads, XK);
