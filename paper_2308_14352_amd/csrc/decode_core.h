@@ -614,9 +614,39 @@ __device__ __forceinline__ void topk_impl(const float* __restrict__ lg, int E, i
     }
 }
 
+// The same for at most 64 experts (one logit per lane), written as one short dependent chain: the kernels
+// that route inside a streaming workgroup wait for exactly this. The probabilities use the hardware
+// exponential (relative error of a few 1e-7, far inside what the gates are compared with); the order of the
+// experts is decided on the logits, so it is exact.
+__device__ __forceinline__ void topk_small(const float* __restrict__ lg, int E, int k, int renorm, int lane, int* sel_e,
+                                           float* sel_g, float* __restrict__ probs) {
+  float v = lane < E ? lg[lane] : -INFINITY;
+  const float m = wave_max(v);
+  const float p = lane < E ? __expf(v - m) : 0.f;
+  const float z = wave_sum(p);
+  if (probs && lane < E) probs[lane] = p / z;
+  float sum = 0.f, my_p = 0.f;
+  int my_e = 0;
+  for (int r = 0; r < k; ++r) {                              // lane r keeps the r-th choice
+    const float bv = wave_max(v);
+    const unsigned long long mask = __ballot(v == bv && lane < E);
+    const int be = __ffsll((long long)mask) - 1;             // ties: the lowest expert index
+    const float pe = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), be));
+    if (lane == be) v = -INFINITY;
+    my_e = lane == r ? be : my_e;
+    my_p = lane == r ? pe : my_p;
+    sum += pe;
+  }
+  const float inv = 1.0f / (renorm ? sum : z);
+  if (lane < k) {
+    sel_e[lane] = my_e;
+    sel_g[lane] = my_p * inv;
+  }
+}
+
 __device__ __forceinline__ void topk_from_logits(const float* __restrict__ lg, int E, int k, int renorm, int lane,
                                                  int* sel_e, float* sel_g, float* __restrict__ probs) {
-  if (E <= 64) topk_impl<1>(lg, E, k, renorm, lane, sel_e, sel_g, probs);
+  if (E <= 64) topk_small(lg, E, k, renorm, lane, sel_e, sel_g, probs);
   else if (E <= 128) topk_impl<2>(lg, E, k, renorm, lane, sel_e, sel_g, probs);
   else topk_impl<16>(lg, E, k, renorm, lane, sel_e, sel_g, probs);
 }
