@@ -272,6 +272,31 @@ def test_layer_forward_full_size(cfg_id, layer_id, T, columns):
     assert rel_err(y2.cpu().numpy(), y2_ref).max() < TOL
 
 
+@pytest.mark.parametrize("top_k", (3, 5))
+def test_layer_forward_mixtral_shape_many_choices_all_bitwidths(top_k):
+    """The one-kernel path at the Mixtral layer shape with more choices per token than the paper's models
+    use and 2-, 4- and 8-bit experts in one call: the wavefronts' lists then mix experts of different row
+    lengths (one or two bursts per row) and, with five choices, hold more rows than one flush of the parked
+    row sums takes."""
+    from dataclasses import replace
+    cfg = replace(gen.CONFIGS["c4"], top_k=top_k)
+    bits_table = [8, 4, 2, 8, 2, 4, 8, 2]
+    layer, _, Wr, bias = build_layer_pair(cfg, 1, DEV, bits_table, want_oracle=False, columns=True)
+    x = gen.hidden(cfg, 1, 0, 2, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, _ = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(),
+                                              None if bias is None else bias.cpu().numpy(), cfg.top_k, cfg.renorm)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(2) if t not in skip]
+    assert len(keep) >= 1
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    experts = _lazy_oracle_experts(cfg, 1, bits_table, set(idx_ref.flatten().tolist()))
+    y_ref, _, _ = oracle_layer(cfg, experts, Wr, bias, x)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+
+
 @pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
 def test_layer_forward_batch8_switch_large_and_workspace_errors(columns):
     cfg = gen.tiny_config("c3", 1024, 4096, n_experts=16, n_layers=1)
