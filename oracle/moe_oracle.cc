@@ -15,7 +15,7 @@
 //   * Section 1 / Section 2.1: a router sends each token to its top-K experts
 //     (K = 1 or 2), each expert an independent FFN.
 //
-// Readings taken where the paper is silent (all listed in the design document):
+// Readings taken where the paper is silent:
 //   qmax = 2^(b-1)-1, codes symmetric in [-qmax, qmax], stored offset-binary
 //   u = q + 2^(b-1); element i of a row sits in byte floor(i*b/8) at bit offset
 //   (i*b mod 8); scale = fp16(absmax/qmax) rounded to nearest even and moved one
