@@ -168,7 +168,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   constexpr int WPC = 128 / BITS;
   constexpr int SC = BITS == 8 ? 64 : 128;        // columns per K step
   constexpr int NQ = BITS == 8 ? 2 : 4;           // instructions per step, stream and token block
-  constexpr int NS = 4;                           // streams per wavefront
+  // streams (row blocks of 16 rows) per wavefront; GEMM 2 has few rows (d_model): with two streams per
+  // wavefront its grid has twice the workgroups and fills the compute units more evenly
+  constexpr int NS = PHASE == 1 ? 2 : 4;
   constexpr int RBW = NS / NM;                    // row blocks per wavefront and matrix
   constexpr int BN = kGemmWaves * RBW * 16;       // rows per workgroup
   constexpr int APAD = 65;                        // tokens per (q, kb) line of the LDS tile, padded
@@ -440,7 +442,7 @@ hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void
   hipLaunchKernelGGL(k_h_sums, dim3(M), dim3(256), 0, st, L, table, gexp, HA, (int64_t)w.h_pair_words);
   G.A = HA;
   G.a_pair_words = (int64_t)w.h_pair_words;
-  hipLaunchKernelGGL((k_gemm_q<1, 1>), dim3((L.d_model + kGemmWaves * 64 - 1) / (kGemmWaves * 64), nb), dim3(kGemmThreads), 0, st, G);
+  hipLaunchKernelGGL((k_gemm_q<1, 1>), dim3((L.d_model + kGemmWaves * 32 - 1) / (kGemmWaves * 32), nb), dim3(kGemmThreads), 0, st, G);
   hipLaunchKernelGGL(k_combine, dim3(T), dim3(256), 0, st, Ypair, ginv, gate, L.top_k, L.d_model, y);
   return hipGetLastError();
 }
