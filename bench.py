@@ -41,8 +41,8 @@ def parse():
                          "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--layout", default="auto", choices=["auto", "columns", "canonical"],
                     help="W_out layout: columns = one streaming kernel per layer call, canonical = the "
-                         "two-kernel path on the boundary format, auto = columns for the Mixtral-sized "
-                         "experts (bandwidth-bound), canonical for the Switch-sized ones (latency-bound)")
+                         "two-kernel path on the boundary format, auto = columns for single-token steps and "
+                         "for the Mixtral-sized experts, canonical for small layers with several tokens")
     return ap.parse_args()
 
 
@@ -353,7 +353,10 @@ def main():
     use_graph = not args.no_graph
     def use_columns(workload):
         c = gen.CONFIGS[WORKLOADS[workload][0]]
-        return args.layout == "columns" or (args.layout == "auto" and c.d_model * c.d_ff >= (1 << 24))
+        batch = WORKLOADS[workload][1]
+        # auto: the one-kernel path for single-token steps (measured faster on every configuration) and for
+        # the large layers; small layers with several tokens per step run faster on the two-kernel path
+        return args.layout == "columns" or (args.layout == "auto" and (batch == 1 or c.d_model * c.d_ff >= (1 << 24)))
     columns = use_columns(name)
     stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers, columns=columns)
     cfg = stack.cfg

@@ -202,14 +202,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
     qrow[s] = row * row_bytes;
     srow[s] = row * ng2;
   }
-  struct BSet { TileT t[NS]; uint32_t sc[NS]; };
+  struct BSet { TileT t[NS]; };
   auto load_b = [&](BSet& B, int step) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const uint8_t* q = qs[s / RBW];
       if constexpr (BITS == 2) B.t[s] = gload_u32x2(q + (qrow[s] + (uint32_t)step * 32u + (uint32_t)kb * 8u));
       else B.t[s] = gload_u32x4(q + (qrow[s] + (uint32_t)step * 64u + (uint32_t)kb * 16u));
-      B.sc[s] = gload_u16(ss[s / RBW] + (srow[s] + (((uint32_t)step * (uint32_t)SC) / (uint32_t)group) * 2u));
     }
   };
   // A tile of a step: thread -> (kb, token, q) items; 4 consecutive threads read 64 contiguous bytes
@@ -251,7 +250,14 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   // loads as soon as the codes are unpacked: one set of tile registers serves the whole loop.
   half8_t Bop[NS][NQ];
   float sc[NS];
-  auto unpack = [&](const BSet& B) __attribute__((always_inline)) {
+  uint32_t scx[NS], scy[NS];                      // a stream's scales of the current block of four groups
+#pragma unroll
+  for (int s = 0; s < NS; ++s) scx[s] = scy[s] = 0u;
+  auto unpack = [&](const BSet& B, int step) __attribute__((always_inline)) {
+    // the step's scale among the four of the block held in scb
+    const uint32_t gi = ((uint32_t)step * (uint32_t)SC) / (uint32_t)group;
+    const bool sel = (gi & 2u) != 0;
+    const uint32_t sh = (gi & 1u) * 16u;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       if constexpr (BITS == 4) {
@@ -263,7 +269,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
         Bop[s][0] = codes8<2, 0>(B.t[s].x, 0u); Bop[s][1] = codes8<2, 1>(B.t[s].x, 0u);
         Bop[s][2] = codes8<2, 0>(B.t[s].y, 0u); Bop[s][3] = codes8<2, 1>(B.t[s].y, 0u);
       }
-      sc[s] = f16_bits_to_f32(B.sc[s]);
+      sc[s] = f16_bits_to_f32((sel ? scy[s] : scx[s]) >> sh);   // (the conversion takes the low 16 bits)
     }
   };
   auto multiply = [&](int buf) __attribute__((always_inline)) {
@@ -291,8 +297,23 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   // wavefronts are past the barrier that ended the last reads of that buffer); then the B tiles of step
   // s + 1 and the A tile of step s + 2 are requested: every load has a whole step to arrive. The last two
   // steps are peeled so that the loop body holds no condition on the step number.
+  // The scales are not fetched with every tile: a 2-byte read per lane from 16 different rows costs the
+  // memory system as much as the tile itself. A stream's scales of four consecutive groups are 8 contiguous
+  // bytes (the plan makes rows of scales multiples of 8 bytes); they are read together, once per block of
+  // blk_steps = 4 * group / SC steps, right after the last step of the previous block has taken its scale.
+  const int blk_steps = 4 * group / SC;
+  auto load_scales = [&](int step) __attribute__((always_inline)) {
+    const uint32_t gi = ((uint32_t)step * (uint32_t)SC) / (uint32_t)group;     // a multiple of 4 here
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const uint2 v = gload_u32x2(ss[s / RBW] + (srow[s] + gi * 2u));
+      scx[s] = v.x;
+      scy[s] = v.y;
+    }
+  };
   BSet B;
   ASet A0;
+  load_scales(0);
   load_a(A0, 0);
   load_b(B, 0);
   store_a(A0, 0);
@@ -301,7 +322,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   int step = 0;
   for (; step + 2 < n_steps; ++step) {
     const int buf = step & 1;
-    unpack(B);
+    unpack(B, step);
+    if ((step + 1) % blk_steps == 0) load_scales(step + 1);
     load_b(B, step + 1);
     store_a(A0, buf ^ 1);
     load_a(A0, step + 2);
@@ -310,14 +332,15 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   }
   if (step + 1 < n_steps) {
     const int buf = step & 1;
-    unpack(B);
+    unpack(B, step);
+    if ((step + 1) % blk_steps == 0) load_scales(step + 1);
     load_b(B, step + 1);
     store_a(A0, buf ^ 1);
     multiply(buf);
     __syncthreads();
     ++step;
   }
-  unpack(B);
+  unpack(B, step);
   multiply(step & 1);
 
   // D element i of lane (n, kb) belongs to token 16*t4 + 4*kb + i and row n of the stream
@@ -393,7 +416,8 @@ inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 }  // namespace
 
 bool prefill_supported(const LayerDims& L) {
-  return L.group % 128 == 0 && L.d_model % 256 == 0 && L.d_ff % 256 == 0 && L.d_model <= 16384 && L.n_experts <= 1024;
+  return L.group % 128 == 0 && L.d_model % 256 == 0 && L.d_ff % 256 == 0 &&
+         (L.d_model / L.group) % 4 == 0 && (L.d_ff / L.group) % 4 == 0 && L.d_model <= 16384 && L.n_experts <= 1024;
 }
 
 PrefillWs prefill_ws(const LayerDims& L, int64_t T) {
