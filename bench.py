@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="run only a plain elementwise pass over 1 GiB (reads 1 GiB, writes 1 GiB) and exit: the "
                          "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="run only the c5 prefill layer call (the run its rocprofv3 summaries are made from), "
+                         "print its figures as one JSON line and exit")
     ap.add_argument("--layout", default="auto", choices=["auto", "columns", "canonical"],
                     help="W_out layout: columns = one streaming kernel per layer call, canonical = the "
                          "two-kernel path on the boundary format, auto = columns for single-token steps and "
@@ -347,6 +350,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "torch.add over 2^28 fp32", "read_bytes": a.numel() * 4,
                           "write_bytes": b.numel() * 4}))
+        return
+    if args.prefill_only:
+        print(json.dumps({"c5_prefill": run_prefill(dev, reps=args.steps or 5)}))
         return
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]

@@ -110,19 +110,39 @@ __global__ __launch_bounds__(256) void k_stage_x(LayerDims L, const DevExpert* _
   else { permute_x<8>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<8>(RAW, d, threadIdx.x, blockDim.x, KS); }
 }
 
-// Offset terms of the K steps of GEMM 2 from the staged h of one pair (values back from the pair order).
+// Offset terms of the K steps of GEMM 2 from the staged h of one pair. The 16-byte pieces of a step (16 at 2
+// and 4 bits, 8 at 8 bits) go to consecutive lanes: 64-byte runs of the staged vector per instruction, the
+// pre-divisions undone per word, and the lanes of a step summed with shuffles.
 template <int BITS>
-__device__ __forceinline__ void h_step_sums(const uint16_t* HP, int f, int tid, int nthreads, float* KS) {
+__device__ __forceinline__ void h_step_sums(const uint4* HP, int f, int tid, int nthreads, float* KS) {
   constexpr int SC = BITS == 8 ? 64 : 128;
-  const int C = f / Fmt<BITS>::WPC;
-  for (int st = tid; st < f / SC; st += nthreads) {
-    float a = 0.f;
-    for (int i = 0; i < SC; ++i) {
-      float ps;
-      const int si = staged_index<BITS>(st * SC + i, C, ps);
-      a += f16_bits_to_f32(HP[si]) / ps;
+  constexpr int U = BITS == 8 ? 8 : 16;            // 16-byte pieces per step
+  constexpr int CPS = SC / Fmt<BITS>::WPC;         // chunks per step
+  const int C = f / Fmt<BITS>::WPC, n_steps = f / SC;
+  const int u = tid % U;
+  const int Q = u / CPS, cc = u % CPS;
+  float wgt[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (BITS == 8) wgt[w] = 1.0f;
+    else if (BITS == 4) wgt[w] = (w & 1) ? 16.0f : 1.0f;
+    else {
+      const int j = 4 * (Q & 1) + w, e = j < 5 ? j : j - 5;
+      wgt[w] = (float)(1 << (2 * e));
     }
-    KS[st] = a * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+  }
+  for (int st0 = 0; st0 < n_steps; st0 += nthreads / U) {
+    const int st = st0 + tid / U;                  // uniform over the U lanes of a step
+    float a = 0.f;
+    if (st < n_steps) {
+      const uint4 v = HP[Q * C + st * CPS + cc];
+      const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) a += (f16_bits_to_f32(wv[w]) + f16_bits_to_f32(wv[w] >> 16)) * wgt[w];
+    }
+#pragma unroll
+    for (int m = 1; m < U; m <<= 1) a += __shfl_xor(a, m);
+    if (st < n_steps && u == 0) KS[st] = a * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
   }
 }
 __global__ __launch_bounds__(256) void k_h_sums(LayerDims L, const DevExpert* __restrict__ table,
@@ -133,9 +153,9 @@ __global__ __launch_bounds__(256) void k_h_sums(LayerDims L, const DevExpert* __
   const int bits = table[gexp[g]].bits;
   uint32_t* HPw = HA + (size_t)g * pair_words;
   float* KS = (float*)(HPw + f / 2);
-  if (bits == 2) h_step_sums<2>((const uint16_t*)HPw, f, threadIdx.x, blockDim.x, KS);
-  else if (bits == 4) h_step_sums<4>((const uint16_t*)HPw, f, threadIdx.x, blockDim.x, KS);
-  else h_step_sums<8>((const uint16_t*)HPw, f, threadIdx.x, blockDim.x, KS);
+  if (bits == 2) h_step_sums<2>((const uint4*)HPw, f, threadIdx.x, blockDim.x, KS);
+  else if (bits == 4) h_step_sums<4>((const uint4*)HPw, f, threadIdx.x, blockDim.x, KS);
+  else h_step_sums<8>((const uint4*)HPw, f, threadIdx.x, blockDim.x, KS);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -272,24 +292,56 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
       sc[s] = f16_bits_to_f32((sel ? scy[s] : scx[s]) >> sh);   // (the conversion takes the low 16 bits)
     }
   };
+  // The A operands of a step are read from LDS two instructions groups ahead of the matrix-core instructions
+  // that use them (three register slots): the latency of a read is covered by the eight to sixteen
+  // instructions in between instead of being waited for in front of every group.
+  constexpr int NI = 4 * NQ;                      // (token block, q) items of a step
+  auto read_a = [&](int buf, int idx) __attribute__((always_inline)) {
+    return As[(buf * NQ * 4 + (idx % NQ) * 4 + kb) * APAD + 16 * (idx / NQ) + n];
+  };
+  auto read_k = [&](int buf, int t4) __attribute__((always_inline)) {
+    // the accumulation starts at the negated offset terms of the lane's four tokens
+    const float4 k4 = *(const float4*)(Ks + buf * kTB + 16 * t4 + 4 * kb);
+    const float4_t kv = {k4.x, k4.y, k4.z, k4.w};
+    return kv;
+  };
+  // Without this the compiler sinks the unpacking below the next tiles' loads (its results are used only
+  // by the multiplications): the raw tiles then stay live beside the new ones and are copied at the end of
+  // every step. An empty statement that names the operands keeps the unpacking where it is written, so the
+  // loads reuse the raw tiles' registers.
+  auto pin_operands = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(Bop[s][q]));
+  };
   auto multiply = [&](int buf) __attribute__((always_inline)) {
+    uint4 af[3];
+    af[0] = read_a(buf, 0);
+    af[1] = read_a(buf, 1);
+    float4_t kv = read_k(buf, 0);
+    // two sets of results: the scaling of a token block's results waits for its last matrix-core
+    // instructions, so it is issued behind the first instructions of the next token block
+    float4_t D[2][NS];
 #pragma unroll
-    for (int t4 = 0; t4 < 4; ++t4) {
-      // the accumulation starts at the negated offset terms of the lane's four tokens
-      const float4 k4 = *(const float4*)(Ks + buf * kTB + 16 * t4 + 4 * kb);
-      const float4_t kv = {k4.x, k4.y, k4.z, k4.w};
-      float4_t D[NS];
+    for (int idx = 0; idx < NI; ++idx) {
+      const int t4 = idx / NQ, q = idx % NQ, d = t4 & 1;
+      if (idx + 2 < NI) af[(idx + 2) % 3] = read_a(buf, idx + 2);
+      if (q == 0) {
 #pragma unroll
-      for (int s = 0; s < NS; ++s) D[s] = kv;
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const half8_t A = as_half8(As[(buf * NQ * 4 + q * 4 + kb) * APAD + 16 * t4 + n]);
-#pragma unroll
-        for (int s = 0; s < NS; ++s) D[s] = mfma16(A, Bop[s][q], D[s]);
+        for (int s = 0; s < NS; ++s) D[d][s] = kv;
+        if (t4 + 1 < 4) kv = read_k(buf, t4 + 1);
       }
+      const half8_t A = as_half8(af[idx % 3]);
 #pragma unroll
-      for (int s = 0; s < NS; ++s) acc[s][t4] += sc[s] * D[s];
+      for (int s = 0; s < NS; ++s) D[d][s] = mfma16(A, Bop[s][q], D[d][s]);
+      if (q == 0 && t4 > 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) acc[s][t4 - 1] += sc[s] * D[d ^ 1][s];
+      }
     }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) acc[s][3] += sc[s] * D[1][s];
   };
 
   // Step s multiplies the A tile in LDS buffer s & 1 with the B tiles unpacked at its start. The A tile of
@@ -323,6 +375,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   for (; step + 2 < n_steps; ++step) {
     const int buf = step & 1;
     unpack(B, step);
+    pin_operands();
     if ((step + 1) % blk_steps == 0) load_scales(step + 1);
     load_b(B, step + 1);
     store_a(A0, buf ^ 1);
