@@ -297,6 +297,46 @@ def test_layer_forward_mixtral_shape_many_choices_all_bitwidths(top_k):
     assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
 
 
+@pytest.mark.parametrize("base,d,f,g,k,bits_table", [
+    ("c1", 4096, 12288, 128, 1, [2, 4, 8, 4]),      # ReLU, fp32 hidden states, one choice
+    ("c4", 4096, 12288, 256, 2, [4, 2, 8, 4]),      # scale groups of 256 columns
+    ("c4", 4096, 12288, 1024, 2, [8, 4, 2, 2]),     # the largest scale group the variant takes
+    ("c4", 8192, 12288, 128, 2, [4, 8, 2, 4]),      # rows of two bursts at 2 and 4 bits, four at 8 bits
+], ids=("relu-f32", "group256", "group1024", "d8192"))
+def test_layer_forward_matrix_core_variant_shapes(base, d, f, g, k, bits_table):
+    """The shapes other than the Mixtral one that the one-kernel path's matrix-core variant accepts (d_model a
+    multiple of 4096, 64-column slices, scale groups of 128 to 1024 columns, either activation): each against
+    the oracle at full width, with 2-, 4- and 8-bit experts in the layer."""
+    from dataclasses import replace
+    cfg = replace(gen.tiny_config(base, d, f, n_experts=len(bits_table), n_layers=1, group=g), top_k=k)
+    layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, want_oracle=False, columns=True)
+    T = 3
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, _ = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(),
+                                              None if bias is None else bias.cpu().numpy(), cfg.top_k, cfg.renorm)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 1
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    experts = _lazy_oracle_experts(cfg, 0, bits_table, set(idx_ref.flatten().tolist()))
+    y_ref, _, _ = oracle_layer(cfg, experts, Wr, bias, x)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+    # every expert once, alone, through the static-routing entry (the router may not choose them all)
+    for e in range(len(bits_table)):
+        idx_e = np.full((1, k), e, dtype=np.int32)
+        gate_e = np.full((1, k), 1.0 / k, dtype=np.float32)
+        y_e = moeq.moe_layer_forward_routed(layer, x[:1], torch.from_numpy(idx_e).to(DEV),
+                                            torch.from_numpy(gate_e).to(DEV))
+        torch.cuda.synchronize()
+        ex = _lazy_oracle_experts(cfg, 0, bits_table, {e})
+        y_e_ref = oracle.layer_forward_routed(ex, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), k,
+                                              x[:1].float().cpu().numpy(), idx_e, gate_e)
+        assert rel_err(y_e.cpu().numpy(), y_e_ref).max() < TOL, (e, bits_table[e])
+
+
 @pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
 def test_layer_forward_batch8_switch_large_and_workspace_errors(columns):
     cfg = gen.tiny_config("c3", 1024, 4096, n_experts=16, n_layers=1)
