@@ -108,6 +108,17 @@ void moe_layer_destroy(moeq_layer *layer);
 /* Workspace bytes needed by any compute call on `layer` with up to max_tokens tokens. */
 size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);
 
+/* Which kernels moe_layer_forward / moe_layer_forward_routed run for a call with n_tokens tokens on
+ * `layer` (the choice depends on the layer's shape and W_out layout and on the token count only, so a
+ * caller or a test can know it beforehand). The three paths compute the same layer (Section 3.1, the
+ * MoE layer: router, top-k experts, gate-weighted sum). Returns -1 for a null layer or n_tokens < 1.
+ * Host-only. */
+#define MOEQ_PATH_TWO_KERNELS 0    /* canonical layout: router, phase-1 and phase-2 GEMV kernels          */
+#define MOEQ_PATH_ONE_KERNEL 1     /* columns layout: one streaming kernel per call, vector instructions  */
+#define MOEQ_PATH_ONE_KERNEL_MX 2  /* columns layout: the same with matrix-core instructions              */
+#define MOEQ_PATH_GROUPED_GEMM 3   /* canonical layout, 32 tokens or more: pairs grouped by expert, GEMMs */
+int32_t moe_layer_path(const moeq_layer *layer, int32_t n_tokens);
+
 /* Codes bytes of a packed [rows][cols] matrix; *scale_bytes_opt receives the bytes of its scales.
  * Returns 0 when the arguments are not a valid packed shape. Host-only arithmetic. */
 size_t moe_packed_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group,

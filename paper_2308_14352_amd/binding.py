@@ -66,6 +66,8 @@ def lib():
     L.moe_profile_kernel.argtypes = [i32, vp, vp]
     L.moe_workspace_bytes.restype = sz
     L.moe_workspace_bytes.argtypes = [vp, i32]
+    L.moe_layer_path.restype = i32
+    L.moe_layer_path.argtypes = [vp, i32]
     L.moe_router_topk.restype = C.c_int
     L.moe_router_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.moe_expert_ffn_q.restype = C.c_int
@@ -88,7 +90,7 @@ def lib():
 
 
 EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
-           "moe_layer_destroy", "moe_workspace_bytes", "moe_router_topk", "moe_expert_ffn_q",
+           "moe_layer_destroy", "moe_workspace_bytes", "moe_layer_path", "moe_router_topk", "moe_expert_ffn_q",
            "moe_layer_forward", "moe_layer_forward_routed", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
            "moe_unprepare_out"]
 
@@ -113,6 +115,7 @@ def _stream(stream):
 
 
 MOEQ_KERNEL_FFN_IN, MOEQ_KERNEL_FFN_OUT, MOEQ_KERNEL_FUSED = 1, 2, 3
+MOEQ_PATH_TWO_KERNELS, MOEQ_PATH_ONE_KERNEL, MOEQ_PATH_ONE_KERNEL_MX, MOEQ_PATH_GROUPED_GEMM = 0, 1, 2, 3
 
 
 def moe_profile_kernel(which, start_event=None, stop_event=None):
@@ -238,6 +241,10 @@ class Layer:
 
     def workspace_bytes(self, max_tokens):
         return int(lib().moe_workspace_bytes(self._h, max_tokens))
+
+    def path(self, n_tokens):
+        """MOEQ_PATH_* constant: the kernels a layer call with n_tokens tokens runs."""
+        return int(lib().moe_layer_path(self._h, n_tokens))
 
     def workspace(self, n_tokens):
         need = self.workspace_bytes(n_tokens)

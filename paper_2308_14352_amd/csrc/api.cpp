@@ -314,6 +314,12 @@ moeq_status moe_layer_forward_routed(const moeq_layer* layer, const void* x, int
   return layer_forward_impl(layer, x, n_tokens, y, nullptr, nullptr, topk_idx, topk_gate, ws, ws_bytes, stream);
 }
 
+int32_t moe_layer_path(const moeq_layer* layer, int32_t n_tokens) {
+  if (!layer || n_tokens < 1) return -1;
+  if (layer->out_layout == MOEQ_OUT_COLUMNS) return layer->plan.mx ? MOEQ_PATH_ONE_KERNEL_MX : MOEQ_PATH_ONE_KERNEL;
+  return use_prefill(layer, n_tokens) ? MOEQ_PATH_GROUPED_GEMM : MOEQ_PATH_TWO_KERNELS;
+}
+
 moeq_status moe_profile_kernel(int32_t which, void* start_event, void* stop_event) {
   if (which < 0 || which > MOEQ_KERNEL_FUSED) return MOEQ_EINVAL;
   if (which != 0 && (!start_event || !stop_event)) return MOEQ_EINVAL;

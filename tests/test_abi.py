@@ -120,6 +120,7 @@ def test_compute_entry_points_reject_null_handles_and_shapes():
     assert L.moe_unpack_codes(C.c_void_p(256), 1, 64, 3, C.c_void_p(256), None) == B.MOEQ_EINVAL
     assert L.moe_dequantize(C.c_void_p(256), C.c_void_p(256), 1, 64, 4, 48, C.c_void_p(256), None) == B.MOEQ_EINVAL
     assert L.moe_workspace_bytes(None, 4) == 0
+    assert L.moe_layer_path(None, 4) == -1
     assert B.moe_layer_table_bytes(8) == 8 * 64 and B.moe_layer_table_bytes(0) == 0
     p = C.c_void_p(256)
     q = C.c_void_p(4096)

@@ -310,6 +310,7 @@ def test_layer_forward_matrix_core_variant_shapes(base, d, f, g, k, bits_table):
     from dataclasses import replace
     cfg = replace(gen.tiny_config(base, d, f, n_experts=len(bits_table), n_layers=1, group=g), top_k=k)
     layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, want_oracle=False, columns=True)
+    assert layer.path(1) == moeq.MOEQ_PATH_ONE_KERNEL_MX
     T = 3
     x = gen.hidden(cfg, 0, 0, T, DEV)
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
@@ -360,13 +361,16 @@ PREFILL_TOL = 2e-2   # the bar for the matrix-core path
 
 @pytest.mark.parametrize("base,d,f,E,g,T", [
     ("c5", 512, 1024, 8, 128, 300),     # SwiGLU, 4/8-bit experts, ragged groups (not multiples of 64 tokens)
-    ("c4", 256, 768, 4, 128, 97),       # SwiGLU, 2/4-bit experts
-    ("c1", 256, 512, 4, 128, 130),      # ReLU, top-1, 2/4/8-bit experts
+    ("c4", 512, 1536, 4, 128, 97),      # SwiGLU, 2/4-bit experts
+    ("c1", 512, 512, 4, 128, 130),      # ReLU, top-1, 2/4/8-bit experts
+    ("c5", 1024, 2048, 8, 256, 150),    # scale groups of 256 columns: two K steps per group (four at 8 bits)
+    ("c1", 2048, 2048, 4, 512, 70),     # ReLU, scale groups of 512 columns
 ])
 def test_prefill_layer_matches_oracle(base, d, f, E, g, T):
     cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1, group=g)
     layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
     x = gen.hidden(cfg, 0, 0, T, DEV)
+    assert layer.path(T) == moeq.MOEQ_PATH_GROUPED_GEMM and layer.path(8) == moeq.MOEQ_PATH_TWO_KERNELS
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
     torch.cuda.synchronize()
     y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
@@ -395,6 +399,7 @@ def test_prefill_full_size_mixtral_layer_on_sampled_tokens():
     bits_table = gen.bitwidth_table(cfg, 0)
     layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, want_oracle=False)
     x = gen.hidden(cfg, 0, 0, T, DEV)
+    assert layer.path(T) == moeq.MOEQ_PATH_GROUPED_GEMM
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
     torch.cuda.synchronize()
     idx_ref, gate_ref, _ = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(), bias.cpu().numpy(), cfg.top_k,
