@@ -231,7 +231,7 @@ class Layer:
 
     def __del__(self):
         h = getattr(self, "_h", None)
-        if h:
+        if h and callable(lib):          # at interpreter shutdown the module's names may already be gone
             lib().moe_layer_destroy(h)
             self._h = None
 
