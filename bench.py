@@ -290,6 +290,53 @@ def run_prefill(dev, reps=5):
             "packed_GB": st.packed_bytes / 1e9, "bitwidths": st.bits[0]}
 
 
+def run_unfused_comparison(dev, reps=10):
+    """One Mixtral-shaped 4-bit expert at batch 1: the fused kernels against the paper's own flow (Section 3.2:
+    decompress the activated expert to FP32, then a dense FP32 FFN), the decompression by the library's
+    kernel into a preallocated buffer, the dense FFN by fp32 matrix products (rocBLAS through torch)."""
+    import torch
+    import gen
+    import paper_2308_14352_amd as moeq
+    from paper_2308_14352_amd import unfused
+    cfg = gen.CONFIGS["c4"]
+    w = gen.expert_weights(cfg, 0, 0, dev)
+    q_in, s_in = moeq.moe_quantize_pack(w["w_in"], 4, cfg.group)
+    q_out, s_out = moeq.moe_quantize_pack(w["w_out"], 4, cfg.group)
+    q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], 4, cfg.group)
+    del w
+    ex = moeq.PackedExpert(4, q_in, s_in, q_out, s_out, q_g, s_g)
+    Wr, bias = gen.router_weights(cfg, 0, dev)
+    layer = moeq.Layer(cfg.d_model, cfg.d_ff, 1, cfg.group, moeq.MOEQ_ACT_SWIGLU, cfg.renorm, moeq.MOEQ_BF16,
+                       Wr[:1].contiguous(), None, [ex.with_out_columns(cfg.d_ff, cfg.group)], moeq.MOEQ_OUT_COLUMNS)
+    x = gen.hidden(cfg, 0, 0, 1, dev)
+    buf = {"w_in": torch.empty((cfg.d_ff, cfg.d_model), dtype=torch.float32, device=dev),
+           "w_gate": torch.empty((cfg.d_ff, cfg.d_model), dtype=torch.float32, device=dev),
+           "w_out": torch.empty((cfg.d_model, cfg.d_ff), dtype=torch.float32, device=dev)}
+    y = torch.empty((1, cfg.d_model), dtype=torch.float32, device=dev)
+    ws = layer.workspace(1)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e3
+
+    fused_ms = timed(lambda: moeq.moe_expert_ffn_q(layer, 0, x, y=y, ws=ws))
+    deq_ms = timed(lambda: unfused.dequantize_expert(ex, cfg.d_model, cfg.d_ff, cfg.group, buf))
+    dense_ms = timed(lambda: unfused.dense_ffn_fp32(buf, x))
+    y_f = moeq.moe_expert_ffn_q(layer, 0, x)
+    y_u = unfused.expert_ffn_unfused(ex, cfg.d_model, cfg.d_ff, cfg.group, x, buf)
+    torch.cuda.synchronize()
+    diff = float((y_f - y_u).abs().max() / y_u.abs().max())
+    return {"expert": "c4 shape, 4 bits, one token", "fused_ms": fused_ms, "decompress_ms": deq_ms,
+            "dense_fp32_ffn_ms": dense_ms, "unfused_over_fused": (deq_ms + dense_ms) / fused_ms,
+            "max_rel_diff": diff, "fp32_copy_GB": 3 * cfg.d_model * cfg.d_ff * 4 / 1e9}
+
+
 WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8), "c4": ("c4", 1)}
 DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
 
@@ -409,6 +456,7 @@ def main():
             del st
             torch.cuda.empty_cache()
         extras["c5_prefill"] = run_prefill(dev)
+        extras["c4_expert_fused_vs_unfused"] = run_unfused_comparison(dev)
         out["other_workloads"] = extras
     print(json.dumps(out))
 

@@ -98,9 +98,10 @@ __global__ __launch_bounds__(256) void k_unpack_codes(const uint8_t* __restrict_
   codes[i] = (int8_t)((int)u - (1 << (bits - 1)));
 }
 
-__global__ __launch_bounds__(256) void k_dequantize(const uint8_t* __restrict__ q, const uint16_t* __restrict__ s,
-                                                    int64_t n, int64_t cols, int bits, int group,
-                                                    float* __restrict__ w) {
+// One weight per thread: any byte-aligned row length and any pointer alignment.
+__global__ __launch_bounds__(256) void k_dequantize_any(const uint8_t* __restrict__ q, const uint16_t* __restrict__ s,
+                                                        int64_t n, int64_t cols, int bits, int group,
+                                                        float* __restrict__ w) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   const int64_t bit = i * bits;
@@ -108,6 +109,39 @@ __global__ __launch_bounds__(256) void k_dequantize(const uint8_t* __restrict__ 
   const int64_t row = i / cols, col = i % cols;
   const float sc = f16_bits_to_f32(s[row * (cols / group) + col / group] & 0x7fffu);
   w[i] = sc * (float)((int)u - (1 << (bits - 1)));
+}
+
+// W^[row][col] = scale[row][col / group] * (code - 2^(bits-1)) as fp32 (Section 3.2: the decompression of
+// an activated expert). A thread takes one 32-bit word of codes (32 / bits weights of one row: rows are
+// multiples of 16 bytes) and writes its weights as 16-byte stores; one scale serves the word when the group
+// size is a multiple of the weights per word, else every weight looks its scale up.
+template <int BITS>
+__global__ __launch_bounds__(256) void k_dequantize(const uint32_t* __restrict__ q, const uint16_t* __restrict__ s,
+                                                    int64_t n_words, uint32_t words_per_row, uint32_t group,
+                                                    float* __restrict__ w) {
+  constexpr int WPW = 32 / BITS;                  // weights per word
+  constexpr uint32_t MASK = (1u << BITS) - 1u;
+  constexpr int OFF = 1 << (BITS - 1);
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_words) return;
+  const int64_t row = i / words_per_row;
+  const uint32_t wc = (uint32_t)(i - row * words_per_row), col0 = wc * WPW;
+  const uint32_t cols = words_per_row * WPW, groups = cols / group;
+  const uint16_t* srow = s + row * groups;
+  const uint32_t u = q[i];
+  float v[WPW];
+  if (group % WPW == 0) {
+    const float sc = f16_bits_to_f32(srow[col0 / group] & 0x7fffu);
+#pragma unroll
+    for (int e = 0; e < WPW; ++e) v[e] = sc * (float)((int)((u >> (e * BITS)) & MASK) - OFF);
+  } else {
+#pragma unroll
+    for (int e = 0; e < WPW; ++e)
+      v[e] = f16_bits_to_f32(srow[(col0 + e) / group] & 0x7fffu) * (float)((int)((u >> (e * BITS)) & MASK) - OFF);
+  }
+  float4* o = (float4*)(w + row * cols + col0);
+#pragma unroll
+  for (int e = 0; e < WPW; e += 4) o[e / 4] = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
 }
 
 }  // namespace
@@ -139,9 +173,21 @@ hipError_t launch_unpack_codes(const uint8_t* q, int64_t rows, int64_t cols, int
 
 hipError_t launch_dequantize(const uint8_t* q, const uint16_t* s, int64_t rows, int64_t cols, int bits, int group,
                              float* w, hipStream_t st) {
-  const int64_t n = rows * cols, blocks = (n + 255) / 256;
-  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_dequantize, dim3((unsigned)blocks), dim3(256), 0, st, q, s, n, cols, bits, group, w);
+  if ((cols * bits) % 32 || ((uintptr_t)q & 3u) || ((uintptr_t)w & 15u)) {
+    const int64_t n = rows * cols, nb = (n + 255) / 256;
+    if (nb > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_dequantize_any, dim3((unsigned)nb), dim3(256), 0, st, q, s, n, cols, bits, group, w);
+    return hipGetLastError();
+  }
+  const int64_t words_per_row = cols * bits / 32, n_words = rows * words_per_row, blocks = (n_words + 255) / 256;
+  if (blocks > 0x7fffffff || words_per_row > 0x7fffffff) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)blocks), block(256);
+  const uint32_t* qw = (const uint32_t*)q;
+  switch (bits) {
+    case 2: hipLaunchKernelGGL(k_dequantize<2>, grid, block, 0, st, qw, s, n_words, (uint32_t)words_per_row, (uint32_t)group, w); break;
+    case 4: hipLaunchKernelGGL(k_dequantize<4>, grid, block, 0, st, qw, s, n_words, (uint32_t)words_per_row, (uint32_t)group, w); break;
+    default: hipLaunchKernelGGL(k_dequantize<8>, grid, block, 0, st, qw, s, n_words, (uint32_t)words_per_row, (uint32_t)group, w); break;
+  }
   return hipGetLastError();
 }
 

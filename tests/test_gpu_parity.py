@@ -24,7 +24,7 @@ def s16(t):
 # ------------------------------------------------------------------ compression primitives
 @pytest.mark.parametrize("bits", (2, 4, 8))
 @pytest.mark.parametrize("rows,cols,group", [(37, 256, 32), (5, 768, 64), (3, 1024, 128), (2, 3072, 3072), (1, 64, 64),
-                                             (300, 4096, 128)])
+                                             (300, 4096, 128), (3, 64, 4), (5, 128, 8)])
 def test_quantize_pack_codes_and_scales_bit_exact(bits, rows, cols, group):
     if bits == 2 and cols * bits % 128:
         pytest.skip("row is not a whole number of 16-byte chunks")
@@ -353,6 +353,31 @@ def test_layer_forward_batch8_switch_large_and_workspace_errors(columns):
     assert ei.value.status == moeq.binding.MOEQ_EWORKSPACE
     with pytest.raises(moeq.MoeqError):
         moeq.moe_expert_ffn_q(layer, 99, x)
+
+
+# ------------------------------------------------------------------ the paper's unfused flow as a yardstick
+@pytest.mark.parametrize("base,d,f,g", [("c1", 256, 512, 32), ("c4", 512, 1024, 128)])
+def test_decompress_then_dense_ffn_agrees_with_the_fused_kernels(base, d, f, g):
+    """Section 3.2: an activated expert is decompressed to FP32 and then computed with as a dense FFN. That
+    flow (the library's decompress kernel, then fp32 matrix products) and the fused kernels compute the same
+    function of the packed expert: both must match the oracle, for every bitwidth."""
+    from paper_2308_14352_amd import unfused
+    cfg = gen.tiny_config(base, d, f, n_experts=3, n_layers=1, group=g)
+    bits_table = [2, 4, 8]
+    layer, orc_experts, _, _ = build_layer_pair(cfg, 0, DEV, bits_table)
+    x = gen.hidden(cfg, 0, 0, 5, DEV)
+    for e in range(3):
+        y_fused = moeq.moe_expert_ffn_q(layer, e, x)
+        y_unf = unfused.expert_ffn_unfused(layer.canonical[e], cfg.d_model, cfg.d_ff, cfg.group, x)
+        torch.cuda.synchronize()
+        y_ref = oracle.expert_ffn(orc_experts[e], cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu),
+                                  x.float().cpu().numpy())
+        assert rel_err(y_fused.cpu().numpy(), y_ref).max() < TOL
+        assert rel_err(y_unf.cpu().numpy(), y_ref).max() < TOL
+        # the decompressed copy itself is the oracle's, bit for bit
+        w = unfused.dequantize_expert(layer.canonical[e], cfg.d_model, cfg.d_ff, cfg.group)
+        w_ref = oracle.dequant(orc_experts[e].q_out, orc_experts[e].s_out, cfg.d_ff, bits_table[e], cfg.group)
+        assert np.array_equal(w["w_out"].cpu().numpy(), w_ref)
 
 
 # ------------------------------------------------------------------ batched (prefill) path: grouped GEMMs on the matrix cores
