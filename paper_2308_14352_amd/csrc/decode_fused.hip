@@ -823,7 +823,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     float dm[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) dm[i] = (kb4 == (m16 >> 2) && (m16 & 3) == i) ? 1.f : 0.f;
-    // ---- phase 1: tasks (expert slot t / SW, row t % SW of the slice) from the counter in LDS
+    // ---- phase 1: tasks (expert slot t / SW, row of the slice from t % SW); wavefront w takes w, w + nwaves, ...
     const uint32_t row0 = (uint32_t)(slice * SW);
     const uint32_t ng2 = (uint32_t)(d >> gsh) * 2u;
     const int n_tasks = k * SW;
