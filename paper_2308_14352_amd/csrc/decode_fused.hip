@@ -603,7 +603,7 @@ __device__ __forceinline__ void mx2_enter(MxWalk2& w, const DevExpert* ex, int d
   const int tpr = w.bits == 2 ? 1 : (w.bits == 4 ? 2 : 4), gps = 4 / tpr;
   w.qT_s = uniform_ptr(ex->q_out) + (size_t)(slice * dw) * ((size_t)d * 4);
   w.sT_g = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)((slice * kMxSlice) >> gsh) * ((size_t)d * 2);
-  w.n_sets = d / (64 * gps * nwaves);
+  w.n_sets = (d >> 6) / (gps * nwaves);
   w.set = 0;
   const int n = lane & 15, kb = lane >> 4;
   const uint32_t col_bytes = (uint32_t)d * 4u;           // bytes of a word column
@@ -827,6 +827,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     const uint32_t row0 = (uint32_t)(slice * SW);
     const uint32_t ng2 = (uint32_t)(d >> gsh) * 2u;
     const int n_tasks = k * SW;
+    const int wsh = __builtin_ctz((unsigned)nwaves);           // the plan: nwaves divides 64
     MxWalk1 wi;
     wi.j = -1;
     auto take = [&](int t) __attribute__((always_inline)) {
@@ -896,7 +897,7 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       issue(B, tb);
       // priority by the tasks still ahead, finest near the end of the list where the drift would show
       auto prio = [&](int t) __attribute__((always_inline)) {
-        const int left = (n_tasks - 1 - t) / nwaves;      // tasks after this one
+        const int left = (n_tasks - 1 - t) >> wsh;        // tasks after this one (nwaves is a power of two here)
         if (left >= 3) __builtin_amdgcn_s_setprio(3);
         else if (left == 2) __builtin_amdgcn_s_setprio(2);
         else if (left == 1) __builtin_amdgcn_s_setprio(1);
