@@ -315,6 +315,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
 #pragma unroll
       for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(Bop[s][q]));
   };
+  // two result sets where the registers allow it (not for GEMM 1 with one matrix: it would spill)
+  constexpr bool DBL = NM == 2 || PHASE == 1;
   auto multiply = [&](int buf) __attribute__((always_inline)) {
     uint4 af[3];
     af[0] = read_a(buf, 0);
@@ -325,7 +327,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
     float4_t D[2][NS];
 #pragma unroll
     for (int idx = 0; idx < NI; ++idx) {
-      const int t4 = idx / NQ, q = idx % NQ, d = t4 & 1;
+      const int t4 = idx / NQ, q = idx % NQ, d = DBL ? (t4 & 1) : 0;
       if (idx + 2 < NI) af[(idx + 2) % 3] = read_a(buf, idx + 2);
       if (q == 0) {
 #pragma unroll
@@ -335,13 +337,19 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
       const half8_t A = as_half8(af[idx % 3]);
 #pragma unroll
       for (int s = 0; s < NS; ++s) D[d][s] = mfma16(A, Bop[s][q], D[d][s]);
-      if (q == 0 && t4 > 0) {
+      if (DBL && q == 0 && t4 > 0) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) acc[s][t4 - 1] += sc[s] * D[d ^ 1][s];
       }
-    }
+      if (!DBL && q == NQ - 1) {
 #pragma unroll
-    for (int s = 0; s < NS; ++s) acc[s][3] += sc[s] * D[1][s];
+        for (int s = 0; s < NS; ++s) acc[s][t4] += sc[s] * D[0][s];
+      }
+    }
+    if (DBL) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) acc[s][3] += sc[s] * D[1][s];
+    }
   };
 
   // Step s multiplies the A tile in LDS buffer s & 1 with the B tiles unpacked at its start. The A tile of
