@@ -265,14 +265,15 @@ def cpu_baseline(stack, dev, budget_layers):
                       f"{per_layer * 1e3:.1f} ms per token-layer, scaled to the {stack.L}-layer stack"}
 
 
-def run_prefill(dev, reps=5):
-    """c5: one Mixtral-8x7B-shaped layer, 2048 tokens in one call (grouped GEMMs on the matrix cores)."""
+def run_prefill(dev, reps=5, columns=False):
+    """c5: one Mixtral-8x7B-shaped layer, 2048 tokens in one call (grouped GEMMs on the matrix cores).
+    columns: W_out in the dword-column-major layout the decode kernel wants (GEMM 2 then gathers its words)."""
     import torch
     import gen
     import paper_2308_14352_amd as moeq
     cfg = gen.CONFIGS["c5"]
     T = cfg.prefill_tokens
-    st = Stack(cfg, T, 1, dev, 1, columns=False)
+    st = Stack(cfg, T, 1, dev, 1, columns=columns)
     layer, x = st.layers[0], st.x_all[0, 0]
     y = torch.empty((T, cfg.d_model), dtype=torch.float32, device=dev)
     ws = torch.empty(layer.workspace_bytes(T), dtype=torch.uint8, device=dev)
@@ -287,7 +288,8 @@ def run_prefill(dev, reps=5):
     flops = 2.0 * 3 * cfg.d_model * cfg.d_ff * T * cfg.top_k
     return {"tokens_per_s": T / dt, "ms_per_call": dt * 1e3, "tokens": T, "achieved_TFLOPs": flops / dt / 1e12,
             "mfma_f16_peak_TFLOPs": 2500.0, "frac_of_mfma_peak": flops / dt / 2.5e15,
-            "packed_GB": st.packed_bytes / 1e9, "bitwidths": st.bits[0]}
+            "packed_GB": st.packed_bytes / 1e9, "bitwidths": st.bits[0],
+            "w_out_layout": "columns" if columns else "canonical"}
 
 
 def run_unfused_comparison(dev, reps=10):
@@ -399,7 +401,7 @@ def main():
                           "write_bytes": b.numel() * 4}))
         return
     if args.prefill_only:
-        print(json.dumps({"c5_prefill": run_prefill(dev, reps=args.steps or 5)}))
+        print(json.dumps({"c5_prefill": run_prefill(dev, reps=args.steps or 5, columns=args.layout == "columns")}))
         return
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]

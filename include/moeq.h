@@ -114,9 +114,9 @@ size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);
  * MoE layer: router, top-k experts, gate-weighted sum). Returns -1 for a null layer or n_tokens < 1.
  * Host-only. */
 #define MOEQ_PATH_TWO_KERNELS 0    /* canonical layout: router, phase-1 and phase-2 GEMV kernels          */
-#define MOEQ_PATH_ONE_KERNEL 1     /* columns layout: one streaming kernel per call, vector instructions  */
+#define MOEQ_PATH_ONE_KERNEL 1     /* columns layout: one streaming kernel per 32 tokens, vector instr.   */
 #define MOEQ_PATH_ONE_KERNEL_MX 2  /* columns layout: the same with matrix-core instructions              */
-#define MOEQ_PATH_GROUPED_GEMM 3   /* canonical layout, 32 tokens or more: pairs grouped by expert, GEMMs */
+#define MOEQ_PATH_GROUPED_GEMM 3   /* 32 tokens or more, either layout: pairs grouped by expert, GEMMs   */
 int32_t moe_layer_path(const moeq_layer *layer, int32_t n_tokens);
 
 /* Codes bytes of a packed [rows][cols] matrix; *scale_bytes_opt receives the bytes of its scales.

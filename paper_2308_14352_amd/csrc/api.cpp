@@ -38,9 +38,12 @@ struct WsLayout {
   size_t idx_off, gate_off, logits_off, sel_off, h_off, hp_off, part_off, prefill_off, total;
 };
 
-// Calls with at least this many tokens on a canonical-layout layer run as grouped GEMMs on the matrix cores
-// (when the shape allows); fewer tokens run the streaming decode kernels, token by token.
+// Calls with at least this many tokens run as grouped GEMMs on the matrix cores (when the shape allows);
+// fewer tokens run the streaming decode kernels, token by token.
 constexpr int64_t kPrefillMinTokens = 32;
+// The one-kernel path takes the tokens of a call in launches of at most this many, so that the buffer of
+// partial output vectors (tokens x slices x d_model floats) does not grow with the call.
+constexpr int32_t kDecodeChunk = 32;
 bool use_prefill(const moeq_layer* layer, int64_t T);
 
 WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
@@ -52,8 +55,12 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
   w.logits_off = w.gate_off + align_up(slots * sizeof(float), 256);
   const size_t tail = w.logits_off + align_up((size_t)T * (size_t)L.n_experts * sizeof(float), 256);
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
+    const size_t chunk = (size_t)(T < kDecodeChunk ? T : kDecodeChunk);
+    const size_t part = align_up(chunk * (size_t)layer->plan.n_slices * (size_t)L.d_model * sizeof(float), 256);
     w.part_off = tail;
-    w.total = w.part_off + align_up((size_t)T * (size_t)layer->plan.n_slices * (size_t)L.d_model * sizeof(float), 256);
+    w.prefill_off = tail;           // a call uses one of the two
+    const size_t grouped = use_prefill(layer, T) ? prefill_ws(L, T).total : 0;
+    w.total = tail + (part > grouped ? part : grouped);
   } else {
     w.sel_off = tail;
     w.h_off = w.sel_off + align_up(slots * sizeof(DevExpert), 256);
@@ -69,7 +76,7 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
 
 bool use_prefill(const moeq_layer* layer, int64_t T) {
   static const bool off = [] { const char* v = std::getenv("MOEQ_NO_PREFILL"); return v && v[0] == '1'; }();
-  return !off && T >= kPrefillMinTokens && layer->out_layout == MOEQ_OUT_CANONICAL && prefill_supported(layer->dims);
+  return !off && T >= kPrefillMinTokens && prefill_supported(layer->dims);
 }
 
 // Routers with at most this many experts are evaluated inside the one-kernel path by every workgroup;
@@ -219,12 +226,18 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
   hipStream_t st = (hipStream_t)stream;
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     float* part = (float*)((char*)ws + w.part_off);
-    if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert, gate_opt, nullptr,
-                          nullptr,
-                          layer->bits[(size_t)expert], x, n_tokens, part, nullptr, nullptr, st) != hipSuccess)
-      return MOEQ_EDEVICE;
-    return dev(launch_reduce_partials(part, layer->plan.n_slices, layer->dims.d_model, n_tokens, accumulate ? 1 : 0,
-                                      y, st));
+    const size_t x_row = (size_t)layer->dims.d_model * (layer->dims.x_bf16 ? 2 : 4);
+    for (int32_t t0 = 0; t0 < n_tokens; t0 += kDecodeChunk) {
+      const int32_t n = n_tokens - t0 < kDecodeChunk ? n_tokens - t0 : kDecodeChunk;
+      if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert,
+                            gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr, layer->bits[(size_t)expert],
+                            (const char*)x + (size_t)t0 * x_row, n, part, nullptr, nullptr, st) != hipSuccess)
+        return MOEQ_EDEVICE;
+      if (launch_reduce_partials(part, layer->plan.n_slices, layer->dims.d_model, n, accumulate ? 1 : 0,
+                                 y + (size_t)t0 * layer->dims.d_model, st) != hipSuccess)
+        return MOEQ_EDEVICE;
+    }
+    return MOEQ_OK;
   }
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
@@ -254,6 +267,17 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
   float* logits = (float*)((char*)ws + w.logits_off);
   if (given && launch_take_routing(given_idx, given_gate, n_tokens * L.top_k, L.n_experts, idx, gate, st) != hipSuccess)
     return MOEQ_EDEVICE;
+  if (use_prefill(layer, n_tokens)) {
+    // batched path: router kernels, then the pairs grouped by expert through two quantized GEMMs
+    if (!given) {
+      if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
+        return MOEQ_EDEVICE;
+      if (launch_topk(L, logits, n_tokens, idx, gate, nullptr, st) != hipSuccess) return MOEQ_EDEVICE;
+    }
+    const PrefillWs pw = prefill_ws(L, n_tokens);
+    return dev(launch_prefill(L, layer->table, x, n_tokens, idx, gate, (char*)ws + w.prefill_off, pw, y,
+                              layer->out_layout == MOEQ_OUT_COLUMNS, st));
+  }
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     // one streaming kernel for the whole layer, then the ordered sum of its partial output vectors
     const float* lg = nullptr;
@@ -263,26 +287,23 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
       lg = logits;
     }
     float* part = (float*)((char*)ws + w.part_off);
-    {
+    const size_t x_row = (size_t)L.d_model * (L.x_bf16 ? 2 : 4);
+    for (int32_t t0 = 0; t0 < n_tokens; t0 += kDecodeChunk) {
+      const int32_t n = n_tokens - t0 < kDecodeChunk ? n_tokens - t0 : kDecodeChunk;
+      const size_t s0 = (size_t)t0 * (size_t)L.top_k;
       // the profiling events, when asked for, bracket the kernel's own execution (not its dispatch)
-      const bool prof = g_profile.which == MOEQ_KERNEL_FUSED && g_profile.start && g_profile.stop;
-      if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias, lg, -1, nullptr,
-                            given ? idx : nullptr, given ? gate : nullptr, layer->bits_mask, x, n_tokens, part,
-                            given ? nullptr : idx, given ? nullptr : gate, st, prof ? g_profile.start : nullptr,
-                            prof ? g_profile.stop : nullptr) != hipSuccess)
+      const bool prof = t0 == 0 && g_profile.which == MOEQ_KERNEL_FUSED && g_profile.start && g_profile.stop;
+      if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias,
+                            lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
+                            given ? gate + s0 : nullptr, layer->bits_mask, (const char*)x + (size_t)t0 * x_row, n, part,
+                            given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
+                            prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr) != hipSuccess)
+        return MOEQ_EDEVICE;
+      if (launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n, 0, y + (size_t)t0 * L.d_model, st) !=
+          hipSuccess)
         return MOEQ_EDEVICE;
     }
-    return dev(launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n_tokens, 0, y, st));
-  }
-  if (use_prefill(layer, n_tokens)) {
-    // batched path: router kernels, then the pairs grouped by expert through two quantized GEMMs
-    if (!given) {
-      if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
-        return MOEQ_EDEVICE;
-      if (launch_topk(L, logits, n_tokens, idx, gate, nullptr, st) != hipSuccess) return MOEQ_EDEVICE;
-    }
-    const PrefillWs pw = prefill_ws(L, n_tokens);
-    return dev(launch_prefill(L, layer->table, x, n_tokens, idx, gate, (char*)ws + w.prefill_off, pw, y, st));
+    return MOEQ_OK;
   }
   uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
   uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
@@ -316,8 +337,9 @@ moeq_status moe_layer_forward_routed(const moeq_layer* layer, const void* x, int
 
 int32_t moe_layer_path(const moeq_layer* layer, int32_t n_tokens) {
   if (!layer || n_tokens < 1) return -1;
+  if (use_prefill(layer, n_tokens)) return MOEQ_PATH_GROUPED_GEMM;
   if (layer->out_layout == MOEQ_OUT_COLUMNS) return layer->plan.mx ? MOEQ_PATH_ONE_KERNEL_MX : MOEQ_PATH_ONE_KERNEL;
-  return use_prefill(layer, n_tokens) ? MOEQ_PATH_GROUPED_GEMM : MOEQ_PATH_TWO_KERNELS;
+  return MOEQ_PATH_TWO_KERNELS;
 }
 
 moeq_status moe_profile_kernel(int32_t which, void* start_event, void* stop_event) {

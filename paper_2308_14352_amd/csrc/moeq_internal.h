@@ -89,7 +89,7 @@ PrefillWs prefill_ws(const LayerDims& L, int64_t T);
 // idx / gate: the routing of the T tokens ([T][k], already computed). W_out in the canonical layout.
 hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void* x, int32_t T,
                           const int32_t* idx, const float* gate, char* ws, const PrefillWs& w, float* y,
-                          hipStream_t st);
+                          bool out_columns, hipStream_t st);
 
 hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
                                 uint8_t* q, uint16_t* s, hipStream_t st);

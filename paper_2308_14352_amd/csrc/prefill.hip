@@ -183,7 +183,7 @@ __device__ __forceinline__ int a_src_index(int C, int step, int q, int kb) {
   return q * C + 4 * step + kb;
 }
 
-template <int BITS, int NM, int PHASE>
+template <int BITS, int NM, int PHASE, bool COLS>
 __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex, int e, int tb, uint4* As, float* Ks) {
   constexpr int WPC = 128 / BITS;
   constexpr int SC = BITS == 8 ? 64 : 128;        // columns per K step
@@ -219,16 +219,34 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     const uint32_t row = (uint32_t)min(R0 + (s % RBW) * 16 + n, N - 1);
-    qrow[s] = row * row_bytes;
-    srow[s] = row * ng2;
+    // COLS (GEMM 2 on a W_out in the dword-column-major layout): word w of row r is the 32-bit word
+    // w * N + r, the scale of group g of row r the binary16 value g * N + r
+    qrow[s] = COLS ? row * 4u : row * row_bytes;
+    srow[s] = COLS ? row * 2u : row * ng2;
   }
   struct BSet { TileT t[NS]; };
   auto load_b = [&](BSet& B, int step) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const uint8_t* q = qs[s / RBW];
-      if constexpr (BITS == 2) B.t[s] = gload_u32x2(q + (qrow[s] + (uint32_t)step * 32u + (uint32_t)kb * 8u));
-      else B.t[s] = gload_u32x4(q + (qrow[s] + (uint32_t)step * 64u + (uint32_t)kb * 16u));
+      if constexpr (COLS) {
+        const uint32_t col_bytes = (uint32_t)N * 4u;
+        if constexpr (BITS == 2) {
+          const uint32_t w0 = ((uint32_t)step * 4u + (uint32_t)kb) * 2u;
+          B.t[s].x = gload_u32(q + (w0 * col_bytes + qrow[s]));
+          B.t[s].y = gload_u32(q + ((w0 + 1u) * col_bytes + qrow[s]));
+        } else {
+          const uint32_t w0 = ((uint32_t)step * 4u + (uint32_t)kb) * 4u;
+          B.t[s].x = gload_u32(q + (w0 * col_bytes + qrow[s]));
+          B.t[s].y = gload_u32(q + ((w0 + 1u) * col_bytes + qrow[s]));
+          B.t[s].z = gload_u32(q + ((w0 + 2u) * col_bytes + qrow[s]));
+          B.t[s].w = gload_u32(q + ((w0 + 3u) * col_bytes + qrow[s]));
+        }
+      } else if constexpr (BITS == 2) {
+        B.t[s] = gload_u32x2(q + (qrow[s] + (uint32_t)step * 32u + (uint32_t)kb * 8u));
+      } else {
+        B.t[s] = gload_u32x4(q + (qrow[s] + (uint32_t)step * 64u + (uint32_t)kb * 16u));
+      }
     }
   };
   // A tile of a step: thread -> (kb, token, q) items; 4 consecutive threads read 64 contiguous bytes
@@ -366,9 +384,18 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
     const uint32_t gi = ((uint32_t)step * (uint32_t)SC) / (uint32_t)group;     // a multiple of 4 here
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const uint2 v = gload_u32x2(ss[s / RBW] + (srow[s] + gi * 2u));
-      scx[s] = v.x;
-      scy[s] = v.y;
+      if constexpr (COLS) {
+        const uint8_t* sb = ss[s / RBW];
+        const uint32_t g_bytes = (uint32_t)N * 2u;
+        const uint32_t a0 = gload_u16(sb + (gi * g_bytes + srow[s])), a1 = gload_u16(sb + ((gi + 1u) * g_bytes + srow[s]));
+        const uint32_t a2 = gload_u16(sb + ((gi + 2u) * g_bytes + srow[s])), a3 = gload_u16(sb + ((gi + 3u) * g_bytes + srow[s]));
+        scx[s] = a0 | (a1 << 16);
+        scy[s] = a2 | (a3 << 16);
+      } else {
+        const uint2 v = gload_u32x2(ss[s / RBW] + (srow[s] + gi * 2u));
+        scx[s] = v.x;
+        scy[s] = v.y;
+      }
     }
   };
   BSet B;
@@ -443,7 +470,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   }
 }
 
-template <int NM, int PHASE>
+template <int NM, int PHASE, bool COLS = false>
 __global__ __launch_bounds__(kGemmThreads) void k_gemm_q(GemmArgs G) {
   __shared__ uint4 As[2 * 4 * 4 * 65];
   __shared__ float Ks[2 * kTB];
@@ -451,9 +478,9 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_q(GemmArgs G) {
   const int2 blk = G.blocks[blockIdx.y];
   const DevExpert ex = G.table[blk.x];
   switch (ex.bits) {
-    case 2: gemm_body<2, NM, PHASE>(G, ex, blk.x, blk.y, As, Ks); break;
-    case 4: gemm_body<4, NM, PHASE>(G, ex, blk.x, blk.y, As, Ks); break;
-    default: gemm_body<8, NM, PHASE>(G, ex, blk.x, blk.y, As, Ks); break;
+    case 2: gemm_body<2, NM, PHASE, COLS>(G, ex, blk.x, blk.y, As, Ks); break;
+    case 4: gemm_body<4, NM, PHASE, COLS>(G, ex, blk.x, blk.y, As, Ks); break;
+    default: gemm_body<8, NM, PHASE, COLS>(G, ex, blk.x, blk.y, As, Ks); break;
   }
 }
 
@@ -503,7 +530,8 @@ PrefillWs prefill_ws(const LayerDims& L, int64_t T) {
 }
 
 hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void* x, int32_t T, const int32_t* idx,
-                          const float* gate, char* ws, const PrefillWs& w, float* y, hipStream_t st) {
+                          const float* gate, char* ws, const PrefillWs& w, float* y, bool out_columns,
+                          hipStream_t st) {
   const int M = T * L.top_k;
   int32_t* poff = (int32_t*)(ws + w.poff);
   int32_t* nblk = (int32_t*)(ws + w.nblk);
@@ -527,7 +555,9 @@ hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void
   hipLaunchKernelGGL(k_h_sums, dim3(M), dim3(256), 0, st, L, table, gexp, HA, (int64_t)w.h_pair_words);
   G.A = HA;
   G.a_pair_words = (int64_t)w.h_pair_words;
-  hipLaunchKernelGGL((k_gemm_q<1, 1>), dim3((L.d_model + kGemmWaves * 32 - 1) / (kGemmWaves * 32), nb), dim3(kGemmThreads), 0, st, G);
+  const dim3 grid2((L.d_model + kGemmWaves * 32 - 1) / (kGemmWaves * 32), nb);
+  if (out_columns) hipLaunchKernelGGL((k_gemm_q<1, 1, true>), grid2, dim3(kGemmThreads), 0, st, G);
+  else hipLaunchKernelGGL((k_gemm_q<1, 1, false>), grid2, dim3(kGemmThreads), 0, st, G);
   hipLaunchKernelGGL(k_combine, dim3(T), dim3(256), 0, st, Ypair, ginv, gate, L.top_k, L.d_model, y);
   return hipGetLastError();
 }

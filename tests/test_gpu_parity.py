@@ -355,6 +355,39 @@ def test_layer_forward_batch8_switch_large_and_workspace_errors(columns):
         moeq.moe_expert_ffn_q(layer, 99, x)
 
 
+def test_one_kernel_path_takes_many_tokens_in_chunks():
+    """A layer in the columns layout whose shape the grouped GEMMs do not take (scale groups of 32): calls
+    with more tokens than one launch of the one-kernel path handles are split, and the workspace no longer
+    grows with the call."""
+    cfg = gen.tiny_config("c1", 256, 512, n_experts=4, n_layers=1)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=True)
+    T = 70
+    assert layer.path(T) == moeq.MOEQ_PATH_ONE_KERNEL
+    assert layer.workspace_bytes(4 * T) - layer.workspace_bytes(T) < 4 * T * (cfg.n_experts + 4) * 8
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 2
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+    # the single-expert entry with per-token gates, accumulating onto y
+    g1 = torch.linspace(0.1, 1.0, T, device=DEV)
+    y2 = y.clone()
+    moeq.moe_expert_ffn_q(layer, 2, x, gate=g1, y=y2, accumulate=True)
+    torch.cuda.synchronize()
+    y_e = oracle.expert_ffn(orc_experts[2], cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), x.float().cpu().numpy())
+    ref2 = y.cpu().numpy().astype(np.float64) + g1.cpu().numpy()[:, None].astype(np.float64) * y_e
+    assert rel_err(y2.cpu().numpy(), ref2).max() < TOL
+    # given routing in chunks
+    y_r = moeq.moe_layer_forward_routed(layer, x, idx, gate)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_r)
+
+
 # ------------------------------------------------------------------ the paper's unfused flow as a yardstick
 @pytest.mark.parametrize("base,d,f,g", [("c1", 256, 512, 32), ("c4", 512, 1024, 128)])
 def test_decompress_then_dense_ffn_agrees_with_the_fused_kernels(base, d, f, g):
@@ -391,11 +424,13 @@ PREFILL_TOL = 2e-2   # the bar for the matrix-core path
     ("c5", 1024, 2048, 8, 256, 150),    # scale groups of 256 columns: two K steps per group (four at 8 bits)
     ("c1", 2048, 2048, 4, 512, 70),     # ReLU, scale groups of 512 columns
 ])
-def test_prefill_layer_matches_oracle(base, d, f, E, g, T):
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_prefill_layer_matches_oracle(base, d, f, E, g, T, columns):
     cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1, group=g)
-    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns)
     x = gen.hidden(cfg, 0, 0, T, DEV)
-    assert layer.path(T) == moeq.MOEQ_PATH_GROUPED_GEMM and layer.path(8) == moeq.MOEQ_PATH_TWO_KERNELS
+    assert layer.path(T) == moeq.MOEQ_PATH_GROUPED_GEMM
+    assert layer.path(8) == (moeq.MOEQ_PATH_ONE_KERNEL if columns else moeq.MOEQ_PATH_TWO_KERNELS)
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
     torch.cuda.synchronize()
     y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
@@ -416,13 +451,14 @@ def test_prefill_layer_matches_oracle(base, d, f, E, g, T):
     assert torch.equal(y, y_b)
 
 
-def test_prefill_full_size_mixtral_layer_on_sampled_tokens():
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_prefill_full_size_mixtral_layer_on_sampled_tokens(columns):
     """The prefill configuration at its real shape (2048 tokens, top-2 of 8 SwiGLU experts at 4/8 bits):
     routing of every token against the oracle, outputs of a sample of tokens against the oracle."""
     cfg = gen.CONFIGS["c5"]
     T = cfg.prefill_tokens
     bits_table = gen.bitwidth_table(cfg, 0)
-    layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, want_oracle=False)
+    layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, want_oracle=False, columns=columns)
     x = gen.hidden(cfg, 0, 0, T, DEV)
     assert layer.path(T) == moeq.MOEQ_PATH_GROUPED_GEMM
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
