@@ -421,6 +421,8 @@ def main():
         "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
+        "dtype_note": "codes and activations enter the multipliers as binary16 (codes exactly; bf16 hidden states "
+                      "exactly), every product and sum is fp32; scales and offsets are applied in fp32",
         "config": {"workload": f"{name}: {cfg.name}", "layers": stack.L, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "act": cfg.act, "group": cfg.group,
                    "batch": stack.batch, "x_dtype": cfg.x_dtype, "bitwidths": cfg.bit_rule,
