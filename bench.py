@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # what the counter reads for a plain pass over 1 GiB: factors 2.000 and 1.000), mean over the dispatches of
 # `bench.py --no-extras --no-cpu-baseline --no-graph --layers 4 --steps 6 --warmup 2`, whose algorithmic bytes
 # per launch are 130.4 MB. The summary with the commands is profiles/c4_decode_pmc.md.
-PMC_TRAFFIC_C4 = {"fetch_bytes": 134.5e6, "write_bytes": 3.67e6, "algorithmic_bytes_same_slice": 130.4e6}
+PMC_TRAFFIC_C4 = {"fetch_bytes": 132.7e6, "write_bytes": 3.67e6, "algorithmic_bytes_same_slice": 130.4e6}
 
 
 def parse():
