@@ -94,6 +94,54 @@ def test_topk_ties_go_to_the_lowest_index():
     assert list(idx[0]) == [0, 1, 2]
 
 
+def test_softmax_is_stable_for_logits_far_outside_the_range_of_exp():
+    """Logits of +-1e3 .. 1e4 (exp of them overflows a double): the probabilities still sum to one, are finite,
+    the order follows the logits, and the gates equal the closed form computed on shifted logits."""
+    E, d = 6, 4
+    x = np.array([[1.0, 0.0, 0.0, 0.0], [0.0, 1.0, 0.0, 0.0]], np.float32)
+    Wr = np.zeros((E, d), np.float32)
+    Wr[:, 0] = [1000.0, 9999.0, -5000.0, 9998.0, 10000.0, 0.0]          # token 0: huge positive logits
+    Wr[:, 1] = [-10000.0, -9000.0, -9001.0, -1e4, -9500.0, -9000.5]     # token 1: huge negative logits
+    for renorm in (False, True):
+        idx, gate, probs, logits = oracle.router_topk(x, Wr, None, 2, renorm, want_logits=True)
+        assert np.all(np.isfinite(probs)) and np.all(np.isfinite(gate))
+        assert np.allclose(probs.sum(1), 1.0, atol=1e-6)
+        assert [list(r) for r in idx] == [[4, 1], [1, 5]]
+        for t in range(2):
+            z = logits[t] - logits[t].max()
+            p = np.exp(z) / np.exp(z).sum()
+            want = p[idx[t]] / (p[idx[t]].sum() if renorm else 1.0)
+            assert np.allclose(gate[t], want, rtol=1e-6)
+            assert np.allclose(probs[t], p, rtol=1e-6, atol=1e-30)
+
+
+def test_non_finite_logits_still_give_valid_expert_indices():
+    """A NaN or +Inf hidden state makes the softmax undefined. The routing must stay total all the same (the
+    indices are used as addresses): every index lies in [0, E), the k indices of a token are distinct, a token
+    whose softmax is undefined takes the experts 0 .. k-1 with NaN gates, and the other tokens are untouched."""
+    rng = np.random.default_rng(11)
+    T, d, E, k = 5, 16, 7, 3
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    Wr = rng.standard_normal((E, d)).astype(np.float32)
+    clean = oracle.router_topk(x, Wr, None, k, True)
+    xb = x.copy()
+    xb[1, 3] = np.nan
+    xb[3, 0] = np.inf
+    idx, gate, probs = oracle.router_topk(xb, Wr, None, k, True)
+    assert idx.min() >= 0 and idx.max() < E
+    assert all(len(set(r)) == k for r in idx.tolist())
+    for t in (1, 3):
+        assert list(idx[t]) == [0, 1, 2] and np.all(np.isnan(gate[t]))
+    for t in (0, 2, 4):
+        assert np.array_equal(idx[t], clean[0][t]) and np.array_equal(gate[t], clean[1][t])
+    # logits of -inf only remove experts from the choice; when fewer than k finite ones remain the rest are
+    # taken in index order with probability zero
+    Wb = np.zeros((4, 2), np.float32)
+    Wb[:, 0] = [-np.inf, 2.0, -np.inf, -np.inf]
+    idx, gate, probs = oracle.router_topk(np.array([[1.0, 0.0]], np.float32), Wb, None, 3, False)
+    assert list(idx[0]) == [1, 0, 2] and list(gate[0]) == [1.0, 0.0, 0.0]
+
+
 def test_router_bias_is_added_to_the_logits():
     d, E = 4, 5
     x = np.zeros((1, d), np.float32)

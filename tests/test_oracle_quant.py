@@ -185,6 +185,48 @@ def test_scale_bumped_up_instead_of_clamping():
     assert found > 100
 
 
+def _round_fraction_to_f32(fr):
+    """The float32 nearest to an exact rational (ties to even), found by exact comparison."""
+    from fractions import Fraction
+    c = np.float32(float(fr))
+    cands = [np.nextafter(c, np.float32(-np.inf)), c, np.nextafter(c, np.float32(np.inf))]
+    best = min(cands, key=lambda v: (abs(Fraction(float(v)) - fr), int(np.float32(v).view(np.uint32)) & 1))
+    return np.float32(best)
+
+
+@pytest.mark.parametrize("w_bits,s_bits,code", [
+    # (fp32 bits of w, fp16 bits of the group's scale s, the code the definition gives).
+    # w / s in exact arithmetic lies just off n + 1/2; the correctly rounded fp32 quotient stays on that side,
+    # while w * (1/s) (reciprocal rounded to fp32 first) crosses to the other neighbour:
+    (0x3d3627ff, 0x2797, 1),   # w = 0.0444717..., s = 0.0296478...: quotient just below 1.5 -> 1 (product gives 2)
+    (0x3e786c01, 0x28c7, 7),   # w = 0.2425995..., s = 0.0373230...: quotient just above 6.5 -> 7 (product gives 6)
+    (0x3d756fff, 0x2194, 5),   # w = 0.0599213..., s = 0.0108948...: quotient just below 5.5 -> 5 (product gives 6)
+    (0x3c5ee401, 0x1a31, 5),   # w = 0.0136042..., s = 0.0030231...: quotient just above 4.5 -> 5 (product gives 4)
+])
+def test_codes_come_from_an_fp32_division_not_from_a_reciprocal_multiply(w_bits, s_bits, code):
+    """The reading of Section 3.2 taken here fixes q = rint(w / scale) with an fp32 DIVISION. Groups are built
+    whose scale is a chosen fp16 value (largest element = 7 * s, exactly representable, so absmax / 7 == s with
+    no bump) and that hold one element whose quotient sits next to a rounding boundary."""
+    from fractions import Fraction
+    w = np.array([w_bits], np.uint32).view(np.float32)[0]
+    s = np.array([s_bits], np.uint16).view(np.float16)[0]
+    sf = np.float32(s)
+    # independent derivation of the expected code with exact rationals
+    quot = _round_fraction_to_f32(Fraction(float(w)) / Fraction(float(sf)))
+    assert int(np.rint(quot)) == code
+    recip = _round_fraction_to_f32(1 / Fraction(float(sf)))
+    prod = _round_fraction_to_f32(Fraction(float(w)) * Fraction(float(recip)))
+    assert int(np.rint(prod)) != code, "the case must separate the two formulas"
+    g = 32
+    grp = np.zeros((1, g), np.float32)
+    grp[0, 0] = np.float32(7) * sf
+    grp[0, 1] = w
+    grp[0, 2] = -w
+    q, sc = oracle.quantize(grp, 4, g)
+    assert sc[0, 0] == s_bits
+    assert list(q[0, :3]) == [7, code, -code]
+
+
 # ------------------------------------------------------------------ dequant closed form
 @pytest.mark.parametrize("b", BITS)
 def test_dequant_is_scale_times_code_exactly(b):
