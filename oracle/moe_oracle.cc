@@ -163,9 +163,13 @@ int orc_dequant(const uint8_t* packed, const uint16_t* s, int64_t rows, int64_t 
 }
 
 // ---------------------------------------------------------------- router + top-k
-// logits = Wr x (+bias); p = softmax(logits); the k largest p, ties to the lowest
-// index, in descending order; gate = p[idx], divided by the sum of the selected
-// probabilities when renorm != 0.
+// logits = Wr x (+bias); p = softmax(logits); the k experts with the largest scores,
+// ties to the lowest index, in descending order; gate = p[idx], divided by the sum
+// of the selected probabilities when renorm != 0. The order is taken on the logits:
+// softmax is strictly increasing, so this IS the order of the probabilities, and it
+// stays so where exp() underflows and would make distinct scores look tied.
+// When the softmax is undefined (a NaN or +Inf logit, or no finite logit) the token
+// takes the experts 0 .. k-1 with NaN gates, so that the indices stay valid.
 int orc_router_topk(const float* x, int32_t T, int32_t d, const float* Wr, const float* bias,
                     int32_t E, int32_t k, int32_t renorm, int32_t* idx, float* gate,
                     float* probs_opt, double* logits_opt) {
@@ -186,11 +190,15 @@ int orc_router_topk(const float* x, int32_t T, int32_t d, const float* Wr, const
     for (int32_t e = 0; e < E; ++e) { p[e] = std::exp(lg[e] - m); Z += p[e]; }
     for (int32_t e = 0; e < E; ++e) { p[e] /= Z; taken[e] = 0; }
     if (probs_opt) for (int32_t e = 0; e < E; ++e) probs_opt[(int64_t)t * E + e] = (float)p[e];
+    if (!(Z >= 1.0 && Z < INFINITY)) {  // undefined softmax (the largest logit alone contributes exp(0) = 1)
+      for (int32_t j = 0; j < k; ++j) { idx[(int64_t)t * k + j] = j; gate[(int64_t)t * k + j] = NAN; }
+      continue;
+    }
     double sel = 0.0;
     for (int32_t j = 0; j < k; ++j) {
       int32_t best = -1;
       for (int32_t e = 0; e < E; ++e)
-        if (!taken[e] && (best < 0 || p[e] > p[best])) best = e;  // strict '>' keeps the lowest index on ties
+        if (!taken[e] && (best < 0 || lg[e] > lg[best])) best = e;  // strict '>' keeps the lowest index on ties
       taken[best] = 1;
       idx[(int64_t)t * k + j] = best;
       sel += p[best];

@@ -98,16 +98,20 @@ def test_softmax_is_stable_for_logits_far_outside_the_range_of_exp():
     """Logits of +-1e3 .. 1e4 (exp of them overflows a double): the probabilities still sum to one, are finite,
     the order follows the logits, and the gates equal the closed form computed on shifted logits."""
     E, d = 6, 4
-    x = np.array([[1.0, 0.0, 0.0, 0.0], [0.0, 1.0, 0.0, 0.0]], np.float32)
+    x = np.array([[1.0, 0.0, 0.0, 0.0], [0.0, 1.0, 0.0, 0.0], [0.0, 0.0, 1.0, 0.0]], np.float32)
     Wr = np.zeros((E, d), np.float32)
     Wr[:, 0] = [1000.0, 9999.0, -5000.0, 9998.0, 10000.0, 0.0]          # token 0: huge positive logits
     Wr[:, 1] = [-10000.0, -9000.0, -9001.0, -1e4, -9500.0, -9000.5]     # token 1: huge negative logits
+    # token 2: every probability but the largest underflows to zero; the second choice is still the second
+    # largest SCORE (the router's order, Section 2.1), not the lowest index among the zeros
+    Wr[:, 2] = [-3000.0, 0.0, -2000.0, -1000.0, -4000.0, -1500.0]
     for renorm in (False, True):
         idx, gate, probs, logits = oracle.router_topk(x, Wr, None, 2, renorm, want_logits=True)
         assert np.all(np.isfinite(probs)) and np.all(np.isfinite(gate))
         assert np.allclose(probs.sum(1), 1.0, atol=1e-6)
-        assert [list(r) for r in idx] == [[4, 1], [1, 5]]
-        for t in range(2):
+        assert [list(r) for r in idx] == [[4, 1], [1, 5], [1, 3]]
+        assert list(gate[2]) == [1.0, 0.0]
+        for t in range(3):
             z = logits[t] - logits[t].max()
             p = np.exp(z) / np.exp(z).sum()
             want = p[idx[t]] / (p[idx[t]].sum() if renorm else 1.0)
