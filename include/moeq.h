@@ -22,6 +22,17 @@
  *     problems as a status code; nothing throws, nothing aborts.
  *   - Calls that share a workspace, and all compute calls on one layer handle, must be ordered on
  *     one stream (or otherwise serialised).
+ *   - Range of the hidden states (Section 4.1, "Baselines": the decompressed weights are used in FP32
+ *     arithmetic, so the path's range is fp32's). The kernels multiply in binary16 x integer code and
+ *     accumulate in fp32; before that, every token's hidden state - and every intermediate vector h -
+ *     is multiplied by a power of two of its own that brings its largest magnitude to about 2^14, and
+ *     the result is scaled back in fp32. Accuracy therefore does not depend on the scale of a token as
+ *     long as its largest magnitude lies in [2^-96, 2^124] and the exact results fit fp32; elements more
+ *     than 2^29 times smaller than the token's largest one lose relative precision. A token that holds
+ *     a NaN or an infinity gets the experts 0 .. top_k-1, NaN gates and a non-finite output; other tokens
+ *     of the call are not affected and no invalid address is formed.
+ *   - Token limits: moe_router_topk and moe_expert_ffn_q take at most 65535 tokens per call,
+ *     moe_layer_forward(_routed) at most 65535 / top_k (else MOEQ_EUNSUPPORTED).
  *
  * Packed weight format (the boundary format; "canonical")
  *   A matrix W[rows][cols] (row = output channel, cols = input dimension) at b bits with group

@@ -33,9 +33,9 @@ inline bool group_ok(int32_t g, int32_t bits) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Workspace carving. Both paths keep idx, gate and logits; the two-kernel path adds the chosen experts'
-// records and the two copies of h, the one-kernel path the partial output vectors.
+// records and h (fp32), the one-kernel path the partial output vectors.
 struct WsLayout {
-  size_t idx_off, gate_off, logits_off, sel_off, h_off, hp_off, part_off, prefill_off, total;
+  size_t idx_off, gate_off, logits_off, sel_off, h_off, part_off, prefill_off, total;
 };
 
 // Calls with at least this many tokens run as grouped GEMMs on the matrix cores (when the shape allows);
@@ -64,9 +64,8 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
   } else {
     w.sel_off = tail;
     w.h_off = w.sel_off + align_up(slots * sizeof(DevExpert), 256);
-    w.hp_off = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
-    w.total = w.hp_off + align_up(slots * (size_t)L.d_ff * sizeof(uint16_t), 256);
-    if (use_prefill(layer, T)) {      // moe_layer_forward takes the grouped path; the single-expert call keeps h/hp
+    w.total = w.h_off + align_up(slots * (size_t)L.d_ff * sizeof(float), 256);
+    if (use_prefill(layer, T)) {      // moe_layer_forward takes the grouped path; the single-expert call keeps h
       w.prefill_off = w.total;
       w.total = w.prefill_off + prefill_ws(L, T).total;
     }
@@ -239,13 +238,12 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
     }
     return MOEQ_OK;
   }
-  uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
-  uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
+  float* h = (float*)((char*)ws + w.h_off);
   hipError_t e = launch_ffn_in(layer->dims, layer->table, nullptr, nullptr, nullptr, nullptr, expert, x, n_tokens, h,
-                               hp, st);
+                               st);
   if (e != hipSuccess) return MOEQ_EDEVICE;
-  return dev(launch_ffn_out(layer->dims, layer->table, nullptr, gate_opt, expert, accumulate ? 1 : 0, h, hp,
-                            n_tokens, y, st));
+  return dev(launch_ffn_out(layer->dims, layer->table, nullptr, gate_opt, expert, accumulate ? 1 : 0, h, n_tokens, y,
+                            st));
 }
 
 // The layer with the routing computed here (given_idx == nullptr) or supplied by the caller.
@@ -305,19 +303,18 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
     }
     return MOEQ_OK;
   }
-  uint16_t* h = (uint16_t*)((char*)ws + w.h_off);
-  uint16_t* hp = (uint16_t*)((char*)ws + w.hp_off);
+  float* h = (float*)((char*)ws + w.h_off);
   DevExpert* sel_tab = (DevExpert*)((char*)ws + w.sel_off);
   if (!given && launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
   {
     ScopedEvents ev(MOEQ_KERNEL_FFN_IN, st);
-    if (launch_ffn_in(L, layer->table, given ? nullptr : logits, idx, gate, sel_tab, -1, x, n_tokens, h, hp, st) !=
+    if (launch_ffn_in(L, layer->table, given ? nullptr : logits, idx, gate, sel_tab, -1, x, n_tokens, h, st) !=
         hipSuccess)
       return MOEQ_EDEVICE;
   }
   ScopedEvents ev(MOEQ_KERNEL_FFN_OUT, st);
-  return dev(launch_ffn_out(L, layer->table, sel_tab, gate, -1, 0, h, hp, n_tokens, y, st));
+  return dev(launch_ffn_out(L, layer->table, sel_tab, gate, -1, 0, h, n_tokens, y, st));
 }
 
 moeq_status moe_layer_forward(const moeq_layer* layer, const void* x, int32_t n_tokens, float* y,

@@ -184,35 +184,89 @@ __device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Activation staging. Phase 1 (copy_x_to_lds): the activation vector goes to LDS as linear binary16
-// (RAW) with 16-byte accesses. Phase 2 (permute_x): pair register pi of chunk c goes to word
-// ((pi/4) * C + c) * 4 + pi%4 of XP, so a lane's 128-bit reads of consecutive chunks are
-// conflict-free, and XK[c * spc + j] = 2^(b-1) * 2^-24 * (sum of the activations of scale slice j of
-// chunk c). Callers put a barrier between the phases and after phase 2.
-enum XKind { X_F32 = 0, X_BF16 = 1, X_F16 = 2 };
+// Activation staging. An activation vector (hidden states, or the intermediate h of an FFN) enters the
+// multipliers as binary16, so it is first brought into binary16's range: the vector is multiplied by the power
+// of two 2^-e that puts its largest magnitude into [2^14, 2^15), converted (round to nearest even), and the
+// consumer multiplies its fp32 results by 2^e again. Both scalings are exact, so the staged values carry
+// 11 significant bits at every magnitude a float can hold, and elements down to 2^-29 of the largest one stay
+// normal numbers even after the pre-divisions of the pair order (Section 4.1, "Baselines": the decompressed
+// weights are used in FP32 arithmetic - the input range of the path is fp32's, not binary16's).
+// Step 1 (stage_normalised): the vector goes to LDS as linear binary16 (RAW) with 16-byte accesses. Step 2
+// (permute_x): pair register pi of chunk c goes to word ((pi/4) * C + c) * 4 + pi%4 of XP, so a lane's
+// 128-bit reads of consecutive chunks are conflict-free, and XK[c * spc + j] = 2^(b-1) * 2^-24 * (sum of the
+// activations of scale slice j of chunk c). Callers put a barrier between the steps and after step 2.
+enum XKind { X_F32 = 0, X_BF16 = 1 };
 
-__device__ __forceinline__ void copy_x_to_lds(const void* __restrict__ x, int kind, int cols, int tid, int nthreads,
-                                              uint16_t* RAW) {
-  uint4* RAW4 = (uint4*)RAW;
-  for (int i = tid; i < cols / 8; i += nthreads) {
-    uint4 o;
-    if (kind == X_F16) {
-      o = ((const uint4*)x)[i];
-    } else if (kind == X_BF16) {
-      const uint4 v = ((const uint4*)x)[i];
-      const uint32_t in[4] = {v.x, v.y, v.z, v.w};
-      uint32_t out[4];
+__device__ __forceinline__ float wave_max(float v);   // defined with the other cross-lane helpers below
+
+struct XItem { float v[8]; };
+
+__device__ __forceinline__ XItem load_x_item(const void* __restrict__ x, int kind, int i) {
+  XItem it;
+  if (kind == X_BF16) {
+    const uint4 v = ((const uint4*)x)[i];
+    const uint32_t in[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        out[k] = f32_to_f16_bits(bf16_bits_to_f32(in[k] & 0xffffu)) | (f32_to_f16_bits(bf16_bits_to_f32(in[k] >> 16)) << 16);
-      o = make_uint4(out[0], out[1], out[2], out[3]);
-    } else {
-      const float4 a = ((const float4*)x)[2 * i], b = ((const float4*)x)[2 * i + 1];
-      o = make_uint4(f32_to_f16_bits(a.x) | (f32_to_f16_bits(a.y) << 16), f32_to_f16_bits(a.z) | (f32_to_f16_bits(a.w) << 16),
-                     f32_to_f16_bits(b.x) | (f32_to_f16_bits(b.y) << 16), f32_to_f16_bits(b.z) | (f32_to_f16_bits(b.w) << 16));
+    for (int k = 0; k < 4; ++k) {
+      it.v[2 * k] = bf16_bits_to_f32(in[k] & 0xffffu);
+      it.v[2 * k + 1] = bf16_bits_to_f32(in[k] >> 16);
     }
-    RAW4[i] = o;
+  } else {
+    const float4 a = ((const float4*)x)[2 * i], b = ((const float4*)x)[2 * i + 1];
+    it.v[0] = a.x; it.v[1] = a.y; it.v[2] = a.z; it.v[3] = a.w;
+    it.v[4] = b.x; it.v[5] = b.y; it.v[6] = b.z; it.v[7] = b.w;
   }
+  return it;
+}
+__device__ __forceinline__ float item_absmax(const XItem& it) {
+  float m = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(it.v[k]));      // a NaN element is skipped by fmaxf
+  return m;
+}
+__device__ __forceinline__ uint4 item_to_f16(const XItem& it, float dn) {
+  uint32_t o[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    o[k] = f32_to_f16_bits(it.v[2 * k] * dn) | (f32_to_f16_bits(it.v[2 * k + 1] * dn) << 16);
+  return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// The exponent e of the normalisation for a vector whose largest magnitude is m: m * 2^-e lies in
+// [2^14, 2^15). e is kept inside [-110, 110] so that both 2^e and 2^-e are normal floats: vectors whose
+// largest magnitude is below 2^-96 lose precision gradually, above 2^124 they overflow to infinity. m == 0,
+// infinite or NaN gives e = 0.
+__device__ __forceinline__ int norm_exponent(float m) {
+  int e = 0;
+  if (m > 0.f && m < INFINITY) e = __builtin_amdgcn_frexp_expf(m) - 1 - 14;   // frexp: m = f * 2^exp, f in [0.5, 1)
+  return min(max(e, -110), 110);
+}
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }   // |e| <= 126
+
+// Step 1, called by EVERY thread of the workgroup at one place (it holds a barrier): x (cols values in the
+// format `kind`) -> RAW (cols binary16 values, normalised). Returns 2^e, the factor that undoes the
+// normalisation. red: nthreads/64 floats of LDS. The first 8 values of a thread stay in registers across the
+// barrier, further ones (long vectors on small workgroups) are read again from the caches.
+__device__ __forceinline__ float stage_normalised(const void* __restrict__ x, int kind, int cols, int tid, int nthreads,
+                                                  uint16_t* RAW, float* red) {
+  uint4* RAW4 = (uint4*)RAW;
+  const int n = cols / 8;
+  XItem first;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) first.v[k] = 0.f;
+  if (tid < n) first = load_x_item(x, kind, tid);
+  float m = item_absmax(first);
+  for (int i = tid + nthreads; i < n; i += nthreads) m = fmaxf(m, item_absmax(load_x_item(x, kind, i)));
+  m = wave_max(m);
+  if ((tid & 63) == 0) red[tid >> 6] = m;
+  __syncthreads();
+  float M = 0.f;
+  for (int w = 0; w < (nthreads >> 6); ++w) M = fmaxf(M, red[w]);
+  const int e = norm_exponent(M);
+  const float dn = pow2f(-e);
+  if (tid < n) RAW4[tid] = item_to_f16(first, dn);
+  for (int i = tid + nthreads; i < n; i += nthreads) RAW4[i] = item_to_f16(load_x_item(x, kind, i), dn);
+  return pow2f(e);
 }
 
 // XK from a linear binary16 vector (LDS or global memory).
@@ -561,6 +615,10 @@ __host__ __device__ inline int pick_nrm(int rows_in_wg, int RW, int nwaves, int 
 // ---------------------------------------------------------------------------------------------
 // softmax + top-k of one token from its logits, by ONE wavefront (all 64 lanes call this). E <= 64*MPL.
 // Lane 0 writes sel_e[0..k), sel_g[0..k); all lanes write probs (may be null).
+// The selection is total: every index it writes lies in [0, E) and the k indices are distinct, whatever the
+// logits hold (the kernels behind use them as addresses). When the softmax is undefined (a NaN or +Inf
+// logit, or no finite logit at all) the token takes the experts 0 .. k-1 with NaN gates; logits of -Inf
+// have probability zero and are chosen, in index order, only when fewer than k other experts remain.
 template <int MPL>
 __device__ __forceinline__ void topk_impl(const float* __restrict__ lg, int E, int k, int renorm, int lane, int* sel_e,
                                           float* sel_g, float* __restrict__ probs) {
@@ -578,39 +636,49 @@ __device__ __forceinline__ void topk_impl(const float* __restrict__ lg, int E, i
   for (int j = 0; j < MPL; ++j)
     if (lane + 64 * j < E) z += expf(v[j] - m);
   z = wave_sum(z);
+  const bool defined = z >= 1.0f && z < INFINITY;      // the largest logit contributes exp(0) = 1
   const float inv_z = 1.0f / z;
   if (probs) {
 #pragma unroll
     for (int j = 0; j < MPL; ++j)
       if (lane + 64 * j < E) probs[lane + 64 * j] = expf(v[j] - m) * inv_z;
   }
-  // k selection passes on the logits (same order as on the probabilities): the largest value, ties to
-  // the lowest expert index = the lowest (j, lane) holding that value.
+  // k selection passes on the logits (same order as on the probabilities): the largest value among the
+  // experts not yet taken, ties to the lowest expert index = the lowest (j, lane) holding that value.
   float sp[8];
   int se[8];
   float sum = 0.f;
+  uint32_t taken = 0;                                  // bit j: this lane's expert lane + 64*j is chosen
   for (int r = 0; r < k; ++r) {
     float bv = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < MPL; ++j) bv = fmaxf(bv, v[j]);
+    for (int j = 0; j < MPL; ++j)
+      if (!((taken >> j) & 1u)) bv = fmaxf(bv, v[j]);
     bv = wave_max(bv);
     int be = -1;
 #pragma unroll
     for (int j = 0; j < MPL; ++j) {
-      const unsigned long long mask = __ballot(v[j] == bv && (lane + 64 * j) < E);
+      const unsigned long long mask = __ballot(v[j] == bv && (lane + 64 * j) < E && !((taken >> j) & 1u));
       if (be < 0 && mask != 0ull) be = 64 * j + (__ffsll((long long)mask) - 1);
+    }
+    if (be < 0) {                                      // only with undefined values: the lowest free expert
+#pragma unroll
+      for (int j = 0; j < MPL; ++j) {
+        const unsigned long long mask = __ballot((lane + 64 * j) < E && !((taken >> j) & 1u));
+        if (be < 0 && mask != 0ull) be = 64 * j + (__ffsll((long long)mask) - 1);
+      }
     }
 #pragma unroll
     for (int j = 0; j < MPL; ++j)
-      if (lane + 64 * j == be) v[j] = -INFINITY;
+      if (lane + 64 * j == be) taken |= 1u << j;
     sp[r] = expf(bv - m) * inv_z;
     se[r] = be;
     sum += sp[r];
   }
   if (lane == 0)
     for (int r = 0; r < k; ++r) {
-      sel_e[r] = se[r];
-      sel_g[r] = renorm ? sp[r] / sum : sp[r];
+      sel_e[r] = defined ? se[r] : r;
+      sel_g[r] = defined ? (renorm ? sp[r] / sum : sp[r]) : __builtin_nanf("");
     }
 }
 
@@ -624,13 +692,17 @@ __device__ __forceinline__ void topk_small(const float* __restrict__ lg, int E, 
   const float m = wave_max(v);
   const float p = lane < E ? __expf(v - m) : 0.f;
   const float z = wave_sum(p);
+  const bool defined = z >= 1.0f && z < INFINITY;      // false: NaN or +Inf among the logits, or none finite
   if (probs && lane < E) probs[lane] = p / z;
   float sum = 0.f, my_p = 0.f;
   int my_e = 0;
+  unsigned long long avail = E >= 64 ? ~0ull : ((1ull << E) - 1ull);   // experts not yet taken
   for (int r = 0; r < k; ++r) {                              // lane r keeps the r-th choice
     const float bv = wave_max(v);
-    const unsigned long long mask = __ballot(v == bv && lane < E);
+    unsigned long long mask = __ballot(v == bv) & avail;
+    if (mask == 0ull) mask = avail;                          // only with undefined values; k <= E keeps avail non-empty
     const int be = __ffsll((long long)mask) - 1;             // ties: the lowest expert index
+    avail &= ~(1ull << be);
     const float pe = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), be));
     if (lane == be) v = -INFINITY;
     my_e = lane == r ? be : my_e;
@@ -639,8 +711,8 @@ __device__ __forceinline__ void topk_small(const float* __restrict__ lg, int E, 
   }
   const float inv = 1.0f / (renorm ? sum : z);
   if (lane < k) {
-    sel_e[lane] = my_e;
-    sel_g[lane] = my_p * inv;
+    sel_e[lane] = defined ? my_e : lane;
+    sel_g[lane] = defined ? my_p * inv : __builtin_nanf("");
   }
 }
 

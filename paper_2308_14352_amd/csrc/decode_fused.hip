@@ -210,25 +210,21 @@ __device__ __forceinline__ void p1_stream(const uint8_t* const (&q)[NM], const u
   }
 }
 
-// Phase 1 of one expert on the SW rows of its slice: h values go to LDS as binary16, once linear (HL)
-// and once in the pair layout of this expert's bitwidth (HP).
+// Phase 1 of one expert on the SW rows of its slice: the h values go to LDS as fp32 (HF); `up` undoes the
+// normalisation of the staged activations.
 template <int BITS, bool SWIGLU>
 __device__ __forceinline__ void fused_in(const DevExpert* ex, int tid, int nwaves, int d, int group, int row_begin,
-                                         int SW, uint16_t* HL, uint16_t* HP, const uint32_t* XP, const float* XK) {
+                                         int SW, float up, float* HF, const uint32_t* XP, const float* XK) {
   constexpr int NM = SWIGLU ? 2 : 1;
   const int C = d / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), J = C / P;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   auto epi = [&](int row, const float (&r)[NM]) __attribute__((always_inline)) {
+    const float a = r[0] * up;
     float v;
-    if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
-    else v = fmaxf(r[0], 0.f);
-    const uint32_t hb = f32_to_f16_bits(v);
-    const int c = row - row_begin;
-    HL[c] = (uint16_t)hb;
-    float ps;
-    const int si = slice_pair_index<BITS>(c, ps);
-    HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+    if constexpr (SWIGLU) v = a / (1.0f + __expf(-a)) * (r[NM - 1] * up);
+    else v = fmaxf(a, 0.f);
+    HF[row - row_begin] = v;
   };
   const uint8_t* q0 = uniform_ptr(ex->q_in);
   const uint8_t* s0 = (const uint8_t*)uniform_ptr(ex->s_in);
@@ -258,6 +254,44 @@ __device__ __forceinline__ void fused_in(const DevExpert* ex, int tid, int nwave
   } else {
     if (P >= RGB1) { run(I1{}, std::integral_constant<int, RGB1>{}); return; }
     run(I1{}, I1{});
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Between the phases (all threads, between two barriers): the h slice of every chosen expert (fp32 in HF) is
+// normalised by its own power of two (stage_normalised's rule, over the SW values of the slice), converted to
+// binary16 and stored linear (HL) and in the pair layout of the expert's bitwidth (HP); uph[j] receives the
+// factor that undoes the normalisation. One wavefront per expert, SW <= 256.
+__device__ __forceinline__ void stage_h_slices(const float* HF, int k, int SW, const DevExpert* tabp, const int* sel_e,
+                                               uint16_t* HLs, uint16_t* HPs, float* uph, int lane, int wave,
+                                               int nwaves) {
+  for (int j = wave; j < k; j += nwaves) {
+    const int bits = __builtin_amdgcn_readfirstlane(tabp[sel_e[j]].bits);
+    float v[4];
+    float m = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = lane + 64 * i;
+      v[i] = c < SW ? HF[j * SW + c] : 0.f;
+      m = fmaxf(m, fabsf(v[i]));
+    }
+    const int e = norm_exponent(wave_max(m));
+    const float dn = pow2f(-e);
+    uint16_t* HL = HLs + j * SW;
+    uint16_t* HP = HPs + j * SW;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = lane + 64 * i;
+      if (c < SW) {
+        const uint32_t hb = f32_to_f16_bits(v[i] * dn);
+        HL[c] = (uint16_t)hb;
+        float ps;
+        const int si = bits == 2 ? slice_pair_index<2>(c, ps) : bits == 4 ? slice_pair_index<4>(c, ps)
+                                                                          : slice_pair_index<8>(c, ps);
+        HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+      }
+    }
+    if (lane == 0) uph[j] = pow2f(e);
   }
 }
 
@@ -304,7 +338,6 @@ __device__ __forceinline__ void fused_out(P2Burst<BITS, DWC>& first, const uint8
   for (int c = lane; c < SW; c += 64) hs += f16_bits_to_f32(HL[c]);
   hs = wave_sum(hs);
   const float K = hs * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
-  const float g24 = gate * 16777216.0f;
   const uint32_t* HPw = (const uint32_t*)HP;
   const int nrb = d / 4;
   const int RB = (nrb + nthreads - 1) / nthreads;
@@ -352,10 +385,12 @@ __device__ __forceinline__ void fused_out(P2Burst<BITS, DWC>& first, const uint8
         const int rb = tid + (i0 + i) * nthreads;
         if (rb < nrb) {
           float4 y = first_expert ? make_float4(0.f, 0.f, 0.f, 0.f) : Y[rb];
-          y.x = fmaf(f16_bits_to_f32(sc[i].x & 0xffffu) * g24, acc[i][0] - K, y.x);
-          y.y = fmaf(f16_bits_to_f32(sc[i].x >> 16) * g24, acc[i][1] - K, y.y);
-          y.z = fmaf(f16_bits_to_f32(sc[i].y & 0xffffu) * g24, acc[i][2] - K, y.z);
-          y.w = fmaf(f16_bits_to_f32(sc[i].y >> 16) * g24, acc[i][3] - K, y.w);
+          // (acc - K) * 2^24 is the sum in the normalised domain; the gate carries the factor that undoes the
+          // normalisation of h
+          y.x = fmaf(f16_bits_to_f32(sc[i].x & 0xffffu) * gate, (acc[i][0] - K) * 16777216.0f, y.x);
+          y.y = fmaf(f16_bits_to_f32(sc[i].x >> 16) * gate, (acc[i][1] - K) * 16777216.0f, y.y);
+          y.z = fmaf(f16_bits_to_f32(sc[i].y & 0xffffu) * gate, (acc[i][2] - K) * 16777216.0f, y.z);
+          y.w = fmaf(f16_bits_to_f32(sc[i].y >> 16) * gate, (acc[i][3] - K) * 16777216.0f, y.w);
           Y[rb] = y;
         }
       }
@@ -363,12 +398,15 @@ __device__ __forceinline__ void fused_out(P2Burst<BITS, DWC>& first, const uint8
   }
 }
 
-// Phase 2 of one expert of one (slice, token). The first expert's call holds the one barrier between the
-// phases; its first burst does not depend on h and is in flight across that barrier.
-template <int BITS, int DWC>
+// Phase 2 of one expert of one (slice, token). The first expert's call holds the barriers between the
+// phases and, between them, the staging of h (`between`); its first burst does not depend on h and is in
+// flight across them. gate: the expert's gate times the factor that undoes the normalisation of its h,
+// read through a pointer because it is known only after the staging.
+template <int BITS, int DWC, typename Between>
 __device__ __forceinline__ void fused_expert_out(const DevExpert* ex, int tid, int nthreads, int d, int group,
-                                                 int slice, int SW, float gate, bool first_expert,
-                                                 const uint16_t* HL, const uint16_t* HP, float4* Y) {
+                                                 int slice, int SW, float gate_j, const float* uph_j,
+                                                 bool first_expert, const uint16_t* HL, const uint16_t* HP, float4* Y,
+                                                 Between between) {
   // first_expert: the call that also waits for phase 1 (of every expert) to be complete
   constexpr int CPD = 32 / BITS;
   // this slice's first word column of the codes, and its scale group, as uniform pointers
@@ -376,8 +414,12 @@ __device__ __forceinline__ void fused_expert_out(const DevExpert* ex, int tid, i
   const uint8_t* sT_g = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)((slice * SW) / group) * ((size_t)d * 2);
   P2Burst<BITS, DWC> first;
   p2_issue<BITS, DWC>(first, qT_s, sT_g, d, d / 4, tid, nthreads, 0, true);
-  if (first_expert) __syncthreads();  // the h slices of all chosen experts are complete in LDS
-  fused_out<BITS, DWC>(first, qT_s, sT_g, tid, nthreads, d, SW, gate, first_expert, HL, HP, Y);
+  if (first_expert) {
+    __syncthreads();  // the h slices of all chosen experts are complete in LDS (fp32)
+    between();        // normalised, converted, put in pair order
+    __syncthreads();
+  }
+  fused_out<BITS, DWC>(first, qT_s, sT_g, tid, nthreads, d, SW, gate_j * *uph_j, first_expert, HL, HP, Y);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -527,18 +569,11 @@ __device__ __forceinline__ void mx1_burst(const MxSet1& S, int jb, int d, int la
   }
 }
 
-// Activation and store of h for the slice column c of one expert: linear for the offset term of phase 2,
-// and in the pair layout of the expert's bitwidth for its dot products.
-template <int BITS, bool SWIGLU, int NM>
-__device__ __forceinline__ void mx1_store_h(int c, const float (&r)[NM], uint16_t* HL, uint16_t* HP) {
-  float v;
-  if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
-  else v = fmaxf(r[0], 0.f);
-  const uint32_t hb = f32_to_f16_bits(v);
-  HL[c] = (uint16_t)hb;
-  float ps;
-  const int si = slice_pair_index<BITS>(c, ps);
-  HP[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+// Activation of one row of the slice (r: its pre-activations, normalisation of x already undone).
+template <bool SWIGLU, int NM>
+__device__ __forceinline__ float mx1_activation(const float (&r)[NM]) {
+  if constexpr (SWIGLU) return r[0] / (1.0f + __expf(-r[0])) * r[NM - 1];
+  else return fmaxf(r[0], 0.f);
 }
 
 // One requested burst: the arithmetic, and, when it completes a row, the sum of the lanes' shares over the
@@ -634,7 +669,7 @@ __device__ __forceinline__ void mx2_issue(MxSet2& S, const MxWalk2& w) {
 
 template <int BITS>
 __device__ __forceinline__ void mx2_compute(const MxSet2& S, const MxWalk2& w, int d, int lane, int wave, int nwaves,
-                                            const uint4* HP4, float K, float g24, float4* Y) {
+                                            const uint4* HP4, float K, float gu, float4* Y) {
   constexpr int TPR = P2Mx<BITS>::TPR, GPS = P2Mx<BITS>::GPS;
   const int n = lane & 15, kb = lane >> 4;
   const float4_t zero = {0.f, 0.f, 0.f, 0.f};
@@ -673,10 +708,11 @@ __device__ __forceinline__ void mx2_compute(const MxSet2& S, const MxWalk2& w, i
       }
       if (lane < 16) {
         float4 y = w.j == 0 ? make_float4(0.f, 0.f, 0.f, 0.f) : Y[16 * g + n];
-        y.x = fmaf(f16_bits_to_f32(S.sc[i].x & 0xffffu) * g24, D[0][0] - K, y.x);
-        y.y = fmaf(f16_bits_to_f32(S.sc[i].x >> 16) * g24, D[1][0] - K, y.y);
-        y.z = fmaf(f16_bits_to_f32(S.sc[i].y & 0xffffu) * g24, D[2][0] - K, y.z);
-        y.w = fmaf(f16_bits_to_f32(S.sc[i].y >> 16) * g24, D[3][0] - K, y.w);
+        // (D - K) * 2^24 is the sum in the normalised domain; gu = gate * the factor that undoes h's normalisation
+        y.x = fmaf(f16_bits_to_f32(S.sc[i].x & 0xffffu) * gu, (D[0][0] - K) * 16777216.0f, y.x);
+        y.y = fmaf(f16_bits_to_f32(S.sc[i].x >> 16) * gu, (D[1][0] - K) * 16777216.0f, y.y);
+        y.z = fmaf(f16_bits_to_f32(S.sc[i].y & 0xffffu) * gu, (D[2][0] - K) * 16777216.0f, y.z);
+        y.w = fmaf(f16_bits_to_f32(S.sc[i].y >> 16) * gu, (D[3][0] - K) * 16777216.0f, y.w);
         Y[16 * g + n] = y;
       }
     }
@@ -691,6 +727,8 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   __shared__ int sel_b[8];                                // bitwidths of the chosen experts
   __shared__ float rpart[kInlineMaxE * (kMaxSegs + 1)];   // router partial sums, unit u = e * n_seg + seg
   __shared__ DevExpert tab[kTabLds];
+  __shared__ float red[16];                               // per-wavefront maxima of |x|
+  __shared__ float uph[8];                                // per chosen expert: undoes the normalisation of its h slice
   const LayerDims& L = P.L;
   const int d = L.d_model, E = L.n_experts, SW = P.SW;
   const int token = blockIdx.y;
@@ -708,7 +746,8 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
   uint16_t* HLs = RAW + d;                         // [k][SW] h of every chosen expert, linear binary16
   uint16_t* HPs = HLs + k * SW;                    // [k][SW] the same in the pair layout of the expert's bitwidth
   float4* Y = (float4*)(HPs + k * SW);             // [d/4] this workgroup's partial output vector
-  uint32_t* LAY = (uint32_t*)(Y + d / 4);          // [#bitwidths][lay_words] staged activations
+  float* HF = (float*)(Y + d / 4);                 // [k][SW] h of every chosen expert as phase 1 leaves it (fp32)
+  uint32_t* LAY = (uint32_t*)(HF + k * SW);        // [#bitwidths][lay_words] staged activations
   const char* xt = (const char*)P.x + (size_t)token * d * (bf16 ? 2 : 4);
   const bool routed = P.fixed_expert < 0;
   const bool given = routed && P.route_idx != nullptr;
@@ -717,9 +756,17 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
 
   // ---- everything that depends on nothing but the inputs is requested at once: the activations, the
   // expert records, the router rows
+  // The activations: a thread's first 8 values stay in registers until the largest magnitude of the vector is
+  // known (stage_normalised's scheme, spread over the prologue so that its loads share a memory round trip with
+  // the router's).
+  const int xkind = bf16 ? X_BF16 : X_F32;
+  const int n_items = d / 8;
+  XItem xit;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) xit.v[q] = 0.f;
   bool staged = false;
   auto stage_inputs = [&]() __attribute__((always_inline)) {
-    copy_x_to_lds(xt, bf16 ? X_BF16 : X_F32, d, threadIdx.x, nthreads, RAW);
+    if ((int)threadIdx.x < n_items) xit = load_x_item(xt, xkind, threadIdx.x);
     if (tab_in_lds && (int)threadIdx.x < E * 4) ((uint4*)tab)[threadIdx.x] = ((const uint4*)P.table)[threadIdx.x];
     staged = true;
   };
@@ -762,7 +809,25 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     }
   }
   if (!staged) stage_inputs();
-  __syncthreads();  // RAW, tab, rpart are complete
+  {
+    float m = item_absmax(xit);
+    for (int i = threadIdx.x + nthreads; i < n_items; i += nthreads) m = fmaxf(m, item_absmax(load_x_item(xt, xkind, i)));
+    m = wave_max(m);
+    if (lane == 0) red[wave] = m;
+  }
+  __syncthreads();  // red, tab, rpart are complete
+  float up;         // undoes the normalisation of the activations
+  {
+    float M = 0.f;
+    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, red[w]);
+    const int e = norm_exponent(M);
+    const float dn = pow2f(-e);
+    up = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, pow2f(e))));   // uniform
+    uint4* RAW4 = (uint4*)RAW;
+    if ((int)threadIdx.x < n_items) RAW4[threadIdx.x] = item_to_f16(xit, dn);
+    for (int i = threadIdx.x + nthreads; i < n_items; i += nthreads) RAW4[i] = item_to_f16(load_x_item(xt, xkind, i), dn);
+  }
+  __syncthreads();  // RAW is complete
 
   // ---- wavefront 0 turns the router sums into the top-k while the others stage the activations for
   // every bitwidth the layer holds (the staging does not depend on the routing)
@@ -788,6 +853,8 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       sel_e[0] = P.fixed_expert;
       sel_g[0] = P.gate_in ? P.gate_in[token] : 1.0f;
     }
+    // the indices become addresses of expert records: whatever produced them, they stay inside the table
+    if (lane < k) sel_e[lane] = min(max(sel_e[lane], 0), E - 1);
   };
   auto stage_layouts = [&](int st, int sn) __attribute__((always_inline)) {
     // behind the staged pairs of a bitwidth: its offset terms (matrix-core variant: negated, per range of
@@ -870,14 +937,8 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
         const int c = ((u & 15) << 2) | (((u >> 4) + slice) & 3);
         float r[NM];
 #pragma unroll
-        for (int mm = 0; mm < NM; ++mm) r[mm] = keep[mm] * 16777216.0f;
-        uint16_t* HL = HLs + j * SW;
-        uint16_t* HP = HPs + j * SW;
-        switch (sel_b[j]) {
-          case 2: mx1_store_h<2, SWIGLU, NM>(c, r, HL, HP); break;
-          case 4: mx1_store_h<4, SWIGLU, NM>(c, r, HL, HP); break;
-          default: mx1_store_h<8, SWIGLU, NM>(c, r, HL, HP); break;
-        }
+        for (int mm = 0; mm < NM; ++mm) r[mm] = keep[mm] * 16777216.0f * up;
+        HF[j * SW + c] = mx1_activation<SWIGLU, NM>(r);
       }
       rows_flushed += rows_done;
       rows_done = 0;
@@ -942,26 +1003,28 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
       mx2_issue(S, vi);
       advance2(vi);
     };
-    float K2 = 0.f, g24 = 0.f;
+    float K2 = 0.f, gu = 0.f;
     auto compute2 = [&](const MxSet2& S) __attribute__((always_inline)) {
       if (vc.set == 0) {
         // offset term of the expert: the sum of its h slice (one value per lane, kMxSlice == 64)
         const float hs = wave_sum(f16_bits_to_f32(HLs[vc.j * SW + lane]));
         K2 = hs * ((float)(1 << (vc.bits - 1)) * 5.9604644775390625e-08f);
-        g24 = sel_g[vc.j] * 16777216.0f;
+        gu = sel_g[vc.j] * uph[vc.j];
       }
       const uint4* HP4 = (const uint4*)(HPs + vc.j * SW);
       switch (vc.bits) {
-        case 2: mx2_compute<2>(S, vc, d, lane, wave, nwaves, HP4, K2, g24, Y); break;
-        case 4: mx2_compute<4>(S, vc, d, lane, wave, nwaves, HP4, K2, g24, Y); break;
-        default: mx2_compute<8>(S, vc, d, lane, wave, nwaves, HP4, K2, g24, Y); break;
+        case 2: mx2_compute<2>(S, vc, d, lane, wave, nwaves, HP4, K2, gu, Y); break;
+        case 4: mx2_compute<4>(S, vc, d, lane, wave, nwaves, HP4, K2, gu, Y); break;
+        default: mx2_compute<8>(S, vc, d, lane, wave, nwaves, HP4, K2, gu, Y); break;
       }
       advance2(vc);
     };
     {
       MxSet2 A, B;
       issue2(A);                      // ns >= 1
-      __syncthreads();                // the h slices of all chosen experts are complete in LDS
+      __syncthreads();                // the h slices of all chosen experts are complete in LDS (fp32)
+      stage_h_slices(HF, k, SW, tabp, sel_e, HLs, HPs, uph, lane, wave, nwaves);
+      __syncthreads();                // ... and staged for phase 2
       // as in phase 1, a wavefront's priority falls with the sets it has left
       auto prio2 = [&](int left) __attribute__((always_inline)) {
         if (left >= 3) __builtin_amdgcn_s_setprio(3);
@@ -1005,12 +1068,17 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     int tid = threadIdx.x;  // opaque copy: keeps the per-bitwidth lane arithmetic inside this iteration
     asm volatile("" : "+v"(tid));
     switch (bits) {
-      case 2: fused_in<2, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
-      case 4: fused_in<4, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
-      default: fused_in<8, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, HLs + j * SW, HPs + j * SW, XP, XK); break;
+      case 2: fused_in<2, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, up, HF + j * SW, XP, XK); break;
+      case 4: fused_in<4, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, up, HF + j * SW, XP, XK); break;
+      default: fused_in<8, SWIGLU>(ex, tid, nwaves, d, L.group, slice * SW, SW, up, HF + j * SW, XP, XK); break;
     }
   }
-  // ---- phase 2 of every chosen expert (the first one's call holds the barrier between the phases)
+  // ---- phase 2 of every chosen expert (the first one's call holds the barriers between the phases and the
+  // staging of h between them)
+  const DevExpert* tabv = tab_in_lds ? tab : P.table;
+  auto between = [&]() __attribute__((always_inline)) {
+    stage_h_slices(HF, k, SW, tabv, sel_e, HLs, HPs, uph, lane, wave, nwaves);
+  };
   for (int j = 0; j < k; ++j) {
     const int e = sel_e[j];
     const DevExpert* ex = tab_in_lds ? &tab[e] : &P.table[e];
@@ -1023,10 +1091,10 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     auto run = [&](auto bits_tag) __attribute__((always_inline)) {
       constexpr int BITS = decltype(bits_tag)::value;
       const int DW = SW * BITS / 32;
-      if (DW >= 8) fused_expert_out<BITS, 8>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
-      else if (DW == 4) fused_expert_out<BITS, 4>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
-      else if (DW == 2) fused_expert_out<BITS, 2>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
-      else fused_expert_out<BITS, 1>(ex, tid, nthreads, d, L.group, slice, SW, gate, j == 0, HL, HP, Y);
+      if (DW >= 8) fused_expert_out<BITS, 8>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      else if (DW == 4) fused_expert_out<BITS, 4>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      else if (DW == 2) fused_expert_out<BITS, 2>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      else fused_expert_out<BITS, 1>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
     };
     switch (bits) {
       case 2: run(std::integral_constant<int, 2>{}); break;
@@ -1127,7 +1195,7 @@ int cu_count() {
 constexpr size_t kFusedLdsBudget = 150 * 1024;
 
 size_t fused_lds_bytes(const LayerDims& L, int k, int SW, int n_layouts) {
-  return (size_t)L.d_model * 2 + (size_t)k * SW * 4 + (size_t)L.d_model * 4 +
+  return (size_t)L.d_model * 2 + (size_t)k * SW * 8 + (size_t)L.d_model * 4 +
          (size_t)n_layouts * ((size_t)L.d_model / 2 + (size_t)L.d_model / 16) * 4;
 }
 

@@ -35,9 +35,8 @@ __global__ __launch_bounds__(256) void k_take_routing(const int32_t* __restrict_
 // ---------------------------------------------------------------------------------------------
 template <int BITS, bool SWIGLU, typename Stage>
 __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
-                                             int row_begin, int row_end, uint16_t* __restrict__ h_out,
-                                             uint16_t* __restrict__ hp_out, const uint32_t* XP, const float* XK,
-                                             Stage stage) {
+                                             int row_begin, int row_end, float up, float* __restrict__ h_out,
+                                             const uint32_t* XP, const float* XK, Stage stage) {
   constexpr int NM = SWIGLU ? 2 : 1;
   const int C = d / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
@@ -48,16 +47,13 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
   const uint16_t* s_in = uniform_ptr(ex.s_in);
   const uint8_t* q_gate = SWIGLU ? uniform_ptr(ex.q_gate) : nullptr;
   const uint16_t* s_gate = SWIGLU ? uniform_ptr(ex.s_gate) : nullptr;
+  // `up` undoes the normalisation of the staged activations; h stays fp32 (phase 2 normalises it for itself)
   auto epi = [&](int row, const float (&r)[NM], int) {
+    const float a = r[0] * up;
     float v;
-    if constexpr (SWIGLU) v = r[0] / (1.0f + __expf(-r[0])) * r[1];
-    else v = fmaxf(r[0], 0.f);
-    // linear copy (for the offset terms of phase 2) and the copy already in phase 2's staged order
-    const uint32_t hb = f32_to_f16_bits(v);
-    h_out[row] = (uint16_t)hb;
-    float ps;
-    const int si = staged_index<BITS>(row, f / Fmt<BITS>::WPC, ps);
-    hp_out[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+    if constexpr (SWIGLU) v = a / (1.0f + __expf(-a)) * (r[NM - 1] * up);
+    else v = fmaxf(a, 0.f);
+    h_out[row] = v;
   };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
@@ -90,26 +86,26 @@ __device__ __forceinline__ void ffn_in_tasks(const DevExpert& ex, int tid, int n
 // Copies the table records of the k chosen experts into LDS (sel_x), so that nothing later in the
 // kernel waits on a chain of dependent global loads. src_idx == nullptr: the single expert `fixed`.
 __device__ __forceinline__ void load_selected(DevExpert* sel_x, const DevExpert* __restrict__ table,
-                                              const int* src_idx, int fixed, int k) {
+                                              const int* src_idx, int fixed, int k, int E) {
   const int t = threadIdx.x;
   if (t < k * 4) {
     const int j = t >> 2, part = t & 3;
-    const int e = src_idx ? src_idx[j] : fixed;
+    const int e = min(max(src_idx ? src_idx[j] : fixed, 0), E - 1);   // an address: kept inside the table
     ((uint4*)&sel_x[j])[part] = ((const uint4*)&table[e])[part];
   }
 }
 
 // Phase 1 of one token for the rows [row_begin, row_end) of d_ff: for each chosen expert
-// h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]); h is kept as binary16 (it is the activation vector
-// of phase 2), once in linear order and once in the staged order phase 2 reads (hp). The activations
-// are already in RAW (LDS, linear binary16) and the chosen experts' records in sel_x (LDS). The k
+// h[slot][r] = act(W_in[r] . x [, W_gate[r] . x]), written as fp32. The activations are already in RAW
+// (LDS, linear binary16, normalised: `up` is the factor that undoes it) and the chosen experts' records in
+// sel_x (LDS). The k
 // experts are handled in passes of `spp`: the activation layouts a pass needs (one per distinct
 // bitwidth) are staged together, then every wavefront streams its tasks of all the pass's experts
 // without a barrier. Called by every thread of the workgroup; the first barrier inside also orders
 // RAW and sel_x.
-__device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert* sel_x, int k, size_t slot0,
-                                            uint16_t* __restrict__ h, uint16_t* __restrict__ hp, int row_begin,
-                                            int row_end, int spp, const uint16_t* RAW, uint32_t* LAY, int nwaves) {
+__device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert* sel_x, int k, size_t slot0, float up,
+                                            float* __restrict__ h, int row_begin, int row_end, int spp,
+                                            const uint16_t* RAW, uint32_t* LAY, int nwaves) {
   const int d = L.d_model, f = L.d_ff;
   const int lay_words = d / 2 + d / 16;         // one layout: d/2 pair words + d/16 offset terms
   const bool sw = L.act == MOEQ_ACT_SWIGLU;
@@ -124,8 +120,7 @@ __device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert*
         if (sel_x[i].bits == ex.bits) li = i;
       const uint32_t* XP = LAY + (li - j0) * lay_words;
       const float* XK = (const float*)(XP + d / 2);
-      uint16_t* h_out = h + (slot0 + j) * f;
-      uint16_t* hp_out = hp + (slot0 + j) * f;
+      float* h_out = h + (slot0 + j) * f;
       // Opaque copy of the thread index: keeps the per-variant lane arithmetic inside this iteration
       // instead of being hoisted (and spilled) ahead of the loop for every bitwidth at once.
       int tid = threadIdx.x;
@@ -150,8 +145,8 @@ __device__ __forceinline__ void phase1_body(const LayerDims& L, const DevExpert*
       };
       auto run = [&](auto bits_tag) {
         constexpr int BITS = decltype(bits_tag)::value;
-        if (sw) ffn_in_tasks<BITS, true>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, hp_out, XP, XK, stage);
-        else ffn_in_tasks<BITS, false>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, h_out, hp_out, XP, XK, stage);
+        if (sw) ffn_in_tasks<BITS, true>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, up, h_out, XP, XK, stage);
+        else ffn_in_tasks<BITS, false>(ex, tid, nwaves, d, f, L.group, row_begin, row_end, up, h_out, XP, XK, stage);
       };
       switch (ex.bits) {
         case 2: run(std::integral_constant<int, 2>{}); break;
@@ -168,19 +163,21 @@ __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* _
                                                  const float* __restrict__ logits, int32_t* __restrict__ idx_out,
                                                  float* __restrict__ gate_out, DevExpert* __restrict__ sel_tab,
                                                  int32_t fixed_expert, const void* __restrict__ x,
-                                                 uint16_t* __restrict__ h, uint16_t* __restrict__ hp,
-                                                 int32_t rows_per_wg, int32_t slots_per_pass) {
+                                                 float* __restrict__ h, int32_t rows_per_wg,
+                                                 int32_t slots_per_pass) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
   __shared__ DevExpert sel_x[8];
+  __shared__ float red[16];
   const int d = L.d_model, f = L.d_ff;
   const int token = blockIdx.y;
   uint16_t* RAW = (uint16_t*)smem;              // d halfs, then the layouts
   uint32_t* LAY = smem + d / 2;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
   const size_t xbytes = L.x_bf16 ? 2 : 4;
-  copy_x_to_lds((const char*)x + (size_t)token * d * xbytes, L.x_bf16 ? X_BF16 : X_F32, d, threadIdx.x, blockDim.x, RAW);
+  const float up = stage_normalised((const char*)x + (size_t)token * d * xbytes, L.x_bf16 ? X_BF16 : X_F32, d,
+                                    threadIdx.x, blockDim.x, RAW, red);
   if (fixed_expert < 0) {
     if (logits) {
       if (threadIdx.x < 64) topk_from_logits(logits + (size_t)token * L.n_experts, L.n_experts, k, L.renorm,
@@ -190,7 +187,7 @@ __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* _
       sel_g[threadIdx.x] = gate_out[(size_t)token * k + threadIdx.x];
     }
     __syncthreads();
-    load_selected(sel_x, table, sel_e, -1, k);
+    load_selected(sel_x, table, sel_e, -1, k, L.n_experts);
     if (logits && blockIdx.x == 0 && threadIdx.x < k) {
       idx_out[(size_t)token * k + threadIdx.x] = sel_e[threadIdx.x];
       gate_out[(size_t)token * k + threadIdx.x] = sel_g[threadIdx.x];
@@ -201,11 +198,11 @@ __global__ __launch_bounds__(1024) void k_ffn_in(LayerDims L, const DevExpert* _
         ((uint4*)&sel_tab[(size_t)token * k])[threadIdx.x] = ((const uint4*)sel_x)[threadIdx.x];
     }
   } else {
-    load_selected(sel_x, table, nullptr, fixed_expert, 1);
+    load_selected(sel_x, table, nullptr, fixed_expert, 1, L.n_experts);
   }
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(f, row_begin + rows_per_wg);
-  phase1_body(L, sel_x, k, fixed_expert >= 0 ? (size_t)token : (size_t)token * k, h, hp, row_begin, row_end,
+  phase1_body(L, sel_x, k, fixed_expert >= 0 ? (size_t)token : (size_t)token * k, up, h, row_begin, row_end,
               slots_per_pass, RAW, LAY, (int)(blockDim.x >> 6));
 }
 
@@ -221,8 +218,8 @@ __host__ __device__ inline int pick_ks(int rows_in_wg, int RW, int nwaves, int J
 
 template <int BITS, typename Stage>
 __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int nwaves, int d, int f, int group,
-                                              float g, int row_begin, int row_end, int rows_per_wg, float* ybuf,
-                                              const uint32_t* XP, const float* XK, Stage stage) {
+                                              float g, const float* up, int row_begin, int row_end, int rows_per_wg,
+                                              float* ybuf, const uint32_t* XP, const float* XK, Stage stage) {
   const int C = f / Fmt<BITS>::WPC;
   const int P = lanes_per_row(C), RW = 64 / P;
   const int lane = tid & 63, wave = tid >> 6;
@@ -232,7 +229,10 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
   const uint8_t* const qq[1] = {uniform_ptr(ex.q_out)};
   const uint16_t* const ss[1] = {uniform_ptr(ex.s_out)};
   // ybuf: [kMaxKs][rows_per_wg] partial sums of this expert; teams beyond ks are zeroed by the caller
-  auto epi = [&](int row, const float (&r)[1], int part) { ybuf[part * rows_per_wg + (row - row_begin)] = g * r[0]; };
+  // *up (LDS, written by stage()) undoes the normalisation of this expert's h
+  auto epi = [&](int row, const float (&r)[1], int part) {
+    ybuf[part * rows_per_wg + (row - row_begin)] = g * (r[0] * *up);
+  };
   auto run = [&](auto nrm_tag, auto two_tag) {
     constexpr int NRM = decltype(nrm_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
@@ -255,20 +255,20 @@ __device__ __forceinline__ void ffn_out_tasks(const DevExpert& ex, int tid, int 
 
 // Phase 2 + combine of one token for the rows [row_begin, row_end) of d_model:
 // y[t][r] (+)= sum_j gate_j * W_out_j[r] . h[slot_j]. Experts are handled in passes of `spp`: their
-// activation vectors (already in staged order in hp) are copied to LDS together, the offset terms are
-// summed from the linear copy h, every wavefront streams its tasks of all of them without a barrier,
+// activation vectors (fp32 in h) are normalised, converted to binary16 and staged in the pair order of
+// their expert's bitwidth, every wavefront streams its tasks of all of them without a barrier,
 // each expert's contribution lands in its own LDS row buffer, and the buffers are summed in top-k order
 // at the end: ordered, no atomics, every output written once.
 // sel_x: the k chosen experts' records (LDS); gate_tok: their gates (LDS or global), may be null (= 1).
 __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert* sel_x, const float* gate_tok, int k,
-                                            int accumulate, size_t slot0, const uint16_t* __restrict__ h,
-                                            const uint16_t* __restrict__ hp, float* __restrict__ y_out,
-                                            int row_begin, int row_end, int rows_per_wg, int spp, uint32_t* smem,
-                                            int nwaves) {
+                                            int accumulate, size_t slot0, const float* __restrict__ h,
+                                            float* __restrict__ y_out, int row_begin, int row_end, int rows_per_wg,
+                                            int spp, uint32_t* smem, float* red, float* s_up, int nwaves) {
   const int d = L.d_model, f = L.d_ff;
   const int lay_words = f / 2 + f / 16;          // pair words + offset terms of one activation vector
   float* ybuf = (float*)smem;                    // [k][kMaxKs][rows_per_wg]
   uint32_t* LAY = smem + k * kMaxKs * rows_per_wg;   // [spp][lay_words]
+  uint16_t* RAW = (uint16_t*)(LAY + spp * lay_words);   // [f] one normalised h vector, linear binary16
   for (int i = threadIdx.x; i < k * kMaxKs * rows_per_wg; i += blockDim.x) ybuf[i] = 0.f;
   __syncthreads();  // sel_x / gates are complete
   for (int j0 = 0; j0 < k; j0 += spp) {
@@ -281,29 +281,28 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
       const float* XK = (const float*)(XP + f / 2);
       int tid = threadIdx.x;       // opaque copy: keeps per-variant lane arithmetic out of the prologue
       asm volatile("" : "+v"(tid));
-      // The first expert of a pass brings, behind its first weight loads, the activation vectors of all
-      // the pass's experts into LDS (already in staged order) and sums their offset terms.
+      // The first expert of a pass stages, behind its first weight loads, the activation vectors of all the
+      // pass's experts: each is normalised into RAW, then put in the pair order of its expert's bitwidth with
+      // its offset terms.
       const bool do_stage = (j == j0);
       auto stage = [&]() {
         if (!do_stage) return;
-        const int per = f / 8, n = (j1 - j0) * per;
-        for (int i = tid; i < n; i += blockDim.x) {
-          const int jj = i / per, r = i - jj * per;
-          ((uint4*)(LAY + jj * lay_words))[r] = ((const uint4*)(hp + (slot0 + j0 + jj) * f))[r];
-        }
         for (int jj = j0; jj < j1; ++jj) {
-          float* XKs = (float*)(LAY + (jj - j0) * lay_words + f / 2);
-          const uint16_t* lin = h + (slot0 + jj) * f;
+          const float u = stage_normalised(h + (slot0 + jj) * f, X_F32, f, tid, blockDim.x, RAW, red);
+          if (tid == 0) s_up[jj] = u;
+          __syncthreads();   // RAW is complete
+          uint32_t* XPs = LAY + (jj - j0) * lay_words;
+          float* XKs = (float*)(XPs + f / 2);
           const int bits = sel_x[jj].bits;
-          if (bits == 2) offset_terms<2>(lin, f, L.group, tid, blockDim.x, XKs);
-          else if (bits == 4) offset_terms<4>(lin, f, L.group, tid, blockDim.x, XKs);
-          else offset_terms<8>(lin, f, L.group, tid, blockDim.x, XKs);
+          if (bits == 2) permute_x<2>(RAW, f, L.group, tid, blockDim.x, XPs, XKs);
+          else if (bits == 4) permute_x<4>(RAW, f, L.group, tid, blockDim.x, XPs, XKs);
+          else permute_x<8>(RAW, f, L.group, tid, blockDim.x, XPs, XKs);
+          __syncthreads();   // the layout and s_up are complete; RAW may be overwritten
         }
-        __syncthreads();
       };
       auto run = [&](auto bits_tag) {
         constexpr int BITS = decltype(bits_tag)::value;
-        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, row_begin, row_end, rows_per_wg,
+        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, s_up + j, row_begin, row_end, rows_per_wg,
                             ybuf + j * kMaxKs * rows_per_wg, XP, XK, stage);
       };
       switch (ex.bits) {
@@ -329,25 +328,27 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
 __global__ __launch_bounds__(1024) void k_ffn_out(LayerDims L, const DevExpert* __restrict__ table,
                                                   const DevExpert* __restrict__ sel_tab, const float* __restrict__ gate,
                                                   int32_t fixed_expert, int32_t accumulate,
-                                                  const uint16_t* __restrict__ h, const uint16_t* __restrict__ hp,
-                                                  float* __restrict__ y, int32_t rows_per_wg, int32_t slots_per_pass) {
+                                                  const float* __restrict__ h, float* __restrict__ y,
+                                                  int32_t rows_per_wg, int32_t slots_per_pass) {
   extern __shared__ uint32_t smem[];
   __shared__ DevExpert sel_x[8];
   __shared__ float sel_g[8];
+  __shared__ float red[16];
+  __shared__ float s_up[8];
   const int d = L.d_model;
   const int token = blockIdx.y;
   const int k = fixed_expert >= 0 ? 1 : L.top_k;
   const size_t slot0 = fixed_expert >= 0 ? (size_t)token : (size_t)token * k;
   if (fixed_expert >= 0) {
-    load_selected(sel_x, table, nullptr, fixed_expert, 1);
+    load_selected(sel_x, table, nullptr, fixed_expert, 1, L.n_experts);
   } else if (threadIdx.x < k * 4) {
     ((uint4*)sel_x)[threadIdx.x] = ((const uint4*)&sel_tab[slot0])[threadIdx.x];
   }
   if (threadIdx.x < k) sel_g[threadIdx.x] = gate ? gate[slot0 + threadIdx.x] : 1.0f;
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(d, row_begin + rows_per_wg);
-  phase2_body(L, sel_x, sel_g, k, accumulate, slot0, h, hp, y + (size_t)token * d, row_begin, row_end, rows_per_wg,
-              slots_per_pass, smem, (int)(blockDim.x >> 6));
+  phase2_body(L, sel_x, sel_g, k, accumulate, slot0, h, y + (size_t)token * d, row_begin, row_end, rows_per_wg,
+              slots_per_pass, smem, red, s_up, (int)(blockDim.x >> 6));
 }
 
 int num_cus() {
@@ -428,11 +429,12 @@ PhaseLds phase1_lds(const LayerDims& L, int k) {
 }
 PhaseLds phase2_lds(const LayerDims& L, int k, int rows_per_wg) {
   const size_t ybuf = (size_t)k * kMaxKs * rows_per_wg * 4;
+  const size_t raw = (size_t)L.d_ff * 2;         // one normalised h vector on its way into the pair order
   const size_t per_slot = ((size_t)L.d_ff / 2 + (size_t)L.d_ff / 16) * 4;
-  int spp = (int)((kLdsBudget - ybuf) / per_slot);
+  int spp = (int)((kLdsBudget - ybuf - raw) / per_slot);
   if (spp > k) spp = k;
   if (spp < 1) spp = 1;
-  return {ybuf + (size_t)spp * per_slot, spp};
+  return {ybuf + raw + (size_t)spp * per_slot, spp};
 }
 
 template <typename K>
@@ -461,27 +463,27 @@ hipError_t launch_take_routing(const int32_t* idx_in, const float* gate_in, int3
 
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits, int32_t* idx_out,
                          float* gate_out, DevExpert* sel_tab, int32_t fixed_expert, const void* x, int32_t T,
-                         uint16_t* h, uint16_t* hp, hipStream_t st) {
+                         float* h, hipStream_t st) {
   const Split sp = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), wgs_per_token(T),
                              L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
   const PhaseLds pl = phase1_lds(L, fixed_expert >= 0 ? 1 : L.top_k);
   static size_t granted = 0;
   if (hipError_t e = allow_lds(k_ffn_in, pl.bytes, granted); e != hipSuccess) return e;
   hipLaunchKernelGGL(k_ffn_in, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, logits, idx_out, gate_out,
-                     sel_tab, fixed_expert, x, h, hp, sp.rows_per_wg, pl.spp);
+                     sel_tab, fixed_expert, x, h, sp.rows_per_wg, pl.spp);
   return hipGetLastError();
 }
 
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevExpert* sel_tab, const float* gate,
-                          int32_t fixed_expert, int32_t accumulate, const uint16_t* h, const uint16_t* hp, int32_t T,
-                          float* y, hipStream_t st) {
+                          int32_t fixed_expert, int32_t accumulate, const float* h, int32_t T, float* y,
+                          hipStream_t st) {
   Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), wgs_per_token(T), kBlock);
   sp.threads = phase2_threads(sp.threads);
   const PhaseLds pl = phase2_lds(L, fixed_expert >= 0 ? 1 : L.top_k, sp.rows_per_wg);
   static size_t granted = 0;
   if (hipError_t e = allow_lds(k_ffn_out, pl.bytes, granted); e != hipSuccess) return e;
   hipLaunchKernelGGL(k_ffn_out, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, sel_tab, gate, fixed_expert,
-                     accumulate, h, hp, y, sp.rows_per_wg, pl.spp);
+                     accumulate, h, y, sp.rows_per_wg, pl.spp);
   return hipGetLastError();
 }
 

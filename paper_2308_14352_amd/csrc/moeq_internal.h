@@ -37,20 +37,19 @@ hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32
 hipError_t launch_take_routing(const int32_t* idx_in, const float* gate_in, int32_t n, int32_t E, int32_t* idx,
                                float* gate, hipStream_t st);
 
-// Phase 1 of the expert FFN: h[slot][f] = act(W_in x [, W_gate x]), stored as binary16 twice: linear
-// (h) and in the staged order phase 2 reads (hp).
+// Phase 1 of the expert FFN: h[slot][f] = act(W_in x [, W_gate x]), stored as fp32.
 // fixed_expert >= 0: every token uses that expert (slot == token). Otherwise each workgroup derives
 // the token's top-k from `logits`, the routing is written to idx_out/gate_out, the chosen experts'
 // table records to sel_tab[slot], and slot = token * top_k + j; with logits == nullptr the routing is
 // READ from idx_out/gate_out instead (caller-supplied routing, already validated).
 hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float* logits,
                          int32_t* idx_out, float* gate_out, DevExpert* sel_tab, int32_t fixed_expert,
-                         const void* x, int32_t T, uint16_t* h, uint16_t* hp, hipStream_t st);
+                         const void* x, int32_t T, float* h, hipStream_t st);
 
 // Phase 2 + combine: y[t] (+)= sum_j gate * W_out h[slot].
 hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevExpert* sel_tab,
                           const float* gate, int32_t fixed_expert, int32_t accumulate,
-                          const uint16_t* h, const uint16_t* hp, int32_t T, float* y, hipStream_t st);
+                          const float* h, int32_t T, float* y, hipStream_t st);
 
 // ---- one-kernel decode path (W_out in the dword-column-major layout) -------------------------------
 // Split of a layer for the fused kernel: slices of SW columns of d_ff, one workgroup of `threads` per
@@ -81,7 +80,7 @@ hipError_t launch_transpose(const void* in, int64_t rows, int64_t cols, int elem
 // ---- batched (prefill) path: pairs grouped by expert, two quantized GEMMs on the matrix cores ----------
 // Byte offsets of the pieces of the prefill workspace (all 256-byte aligned) and the per-pair strides.
 struct PrefillWs {
-  size_t poff, nblk, blocks, gpair, ginv, gexp, xa, ha, ypair, total;
+  size_t poff, nblk, blocks, gpair, ginv, gexp, xa, ha, hf, ypair, total;
   size_t a_pair_words, h_pair_words, max_blocks;
 };
 bool prefill_supported(const LayerDims& L);

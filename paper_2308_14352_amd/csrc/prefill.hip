@@ -5,9 +5,11 @@
 //
 //   grouping : histogram of the pairs per expert, offsets, a list of (expert, block of 64 tokens) work
 //              items, a stable scatter of the pairs into expert order (and its inverse)
-//   staging  : per pair, the token's activations as binary16 in the pair order of its expert's
-//              bitwidth (the order dword_dot / codes8 consume), plus the offset term of every K step
-//   GEMM 1   : H[pair][row] = act(W_in x [, W_gate x]) for 64 tokens x 128 or 256 rows per workgroup
+//   staging  : per pair, the token's activations, normalised by a power of two of their own, as binary16 in
+//              the pair order of its expert's bitwidth (the order dword_dot / codes8 consume), plus the
+//              offset term of every K step
+//   GEMM 1   : H[pair][row] = act(W_in x [, W_gate x]) (fp32) for 64 tokens x 128 or 256 rows per workgroup
+//   staging  : the same for every pair's h
 //   GEMM 2   : Ypair[pair][row] = W_out h for 64 tokens x 256 rows per workgroup
 //   combine  : y[t] = sum_j gate[t][j] * Ypair[pair(t, j)], in top-k order
 //
@@ -33,7 +35,7 @@ __global__ __launch_bounds__(1024) void k_count_pairs(const int32_t* __restrict_
   __shared__ int h[1024];
   for (int e = threadIdx.x; e < E; e += blockDim.x) h[e] = 0;
   __syncthreads();
-  for (int p = threadIdx.x; p < M; p += blockDim.x) atomicAdd(&h[idx[p]], 1);
+  for (int p = threadIdx.x; p < M; p += blockDim.x) atomicAdd(&h[min(max(idx[p], 0), E - 1)], 1);
   __syncthreads();
   if (threadIdx.x == 0) {
     int off = 0, nb = 0;
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict
   int base = poff[e];
   for (int p0 = 0; p0 < M; p0 += 256) {
     const int p = p0 + threadIdx.x;
-    const bool hit = p < M && idx[p] == e;
+    const bool hit = p < M && min(max(idx[p], 0), (int)gridDim.x - 1) == e;   // the same clamp as the histogram
     const unsigned long long mask = __ballot(hit);
     const int before = __popcll(mask & ((1ull << lane) - 1ull));
     if (lane == 0) wcnt[wave] = __popcll(mask);
@@ -78,84 +80,39 @@ __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-// staging of the activations of one pair. Per pair: [K/2 words in pair order][n_steps offset terms].
-template <int BITS>
-__device__ __forceinline__ void step_sums(const uint16_t* RAW, int cols, int tid, int nthreads, float* KS) {
-  constexpr int SC = BITS == 8 ? 64 : 128;
-  for (int st = tid; st < cols / SC; st += nthreads) {
-    float a = 0.f;
-    for (int i = 0; i < SC; ++i) a += f16_bits_to_f32(RAW[st * SC + i]);
-    KS[st] = a * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
-  }
-}
-
-__global__ __launch_bounds__(256) void k_stage_x(LayerDims L, const DevExpert* __restrict__ table,
-                                                 const void* __restrict__ x, const int32_t* __restrict__ gpair,
-                                                 const int32_t* __restrict__ gexp, uint32_t* __restrict__ XA,
-                                                 int64_t pair_words) {
+// Staging of the activation vector of one pair for a GEMM. Per pair: [K/2 words in pair order][K/64 floats:
+// the negated offset term of every K step][the factor 2^e that undoes the normalisation, then 3 unused words].
+// FROM_H = false: the pair's token row of x (GEMM 1); true: row g of the fp32 h that GEMM 1 wrote (GEMM 2).
+// The vector is normalised by its own power of two before the conversion to binary16 (stage_normalised).
+template <bool FROM_H>
+__global__ __launch_bounds__(256) void k_stage(LayerDims L, const DevExpert* __restrict__ table,
+                                               const void* __restrict__ src, const int32_t* __restrict__ gpair,
+                                               const int32_t* __restrict__ gexp, uint32_t* __restrict__ OUT,
+                                               int64_t pair_words) {
   extern __shared__ uint32_t smem[];
+  __shared__ float red[4];
+  const int cols = FROM_H ? L.d_ff : L.d_model;
   uint16_t* RAW = (uint16_t*)smem;
-  const int d = L.d_model;
   const int g = blockIdx.x;
-  const int t = gpair[g] / L.top_k;
   const int bits = table[gexp[g]].bits;
-  const char* xt = (const char*)x + (size_t)t * d * (L.x_bf16 ? 2 : 4);
-  copy_x_to_lds(xt, L.x_bf16 ? X_BF16 : X_F32, d, threadIdx.x, blockDim.x, RAW);
+  const char* row;
+  int kind;
+  if (FROM_H) {
+    row = (const char*)src + (size_t)g * cols * 4;
+    kind = X_F32;
+  } else {
+    row = (const char*)src + (size_t)(gpair[g] / L.top_k) * cols * (L.x_bf16 ? 2 : 4);
+    kind = L.x_bf16 ? X_BF16 : X_F32;
+  }
+  const float up = stage_normalised(row, kind, cols, threadIdx.x, blockDim.x, RAW, red);
   __syncthreads();
-  uint32_t* XP = XA + (size_t)g * pair_words;
-  float* KS = (float*)(XP + d / 2);
-  float* scratch = (float*)(smem + d / 2);     // the per-chunk offset terms permute_x also makes; not kept
-  if (bits == 2) { permute_x<2>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<2>(RAW, d, threadIdx.x, blockDim.x, KS); }
-  else if (bits == 4) { permute_x<4>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<4>(RAW, d, threadIdx.x, blockDim.x, KS); }
-  else { permute_x<8>(RAW, d, L.group, threadIdx.x, blockDim.x, XP, scratch); step_sums<8>(RAW, d, threadIdx.x, blockDim.x, KS); }
-}
-
-// Offset terms of the K steps of GEMM 2 from the staged h of one pair. The 16-byte pieces of a step (16 at 2
-// and 4 bits, 8 at 8 bits) go to consecutive lanes: 64-byte runs of the staged vector per instruction, the
-// pre-divisions undone per word, and the lanes of a step summed with shuffles.
-template <int BITS>
-__device__ __forceinline__ void h_step_sums(const uint4* HP, int f, int tid, int nthreads, float* KS) {
-  constexpr int SC = BITS == 8 ? 64 : 128;
-  constexpr int U = BITS == 8 ? 8 : 16;            // 16-byte pieces per step
-  constexpr int CPS = SC / Fmt<BITS>::WPC;         // chunks per step
-  const int C = f / Fmt<BITS>::WPC, n_steps = f / SC;
-  const int u = tid % U;
-  const int Q = u / CPS, cc = u % CPS;
-  float wgt[4];
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    if (BITS == 8) wgt[w] = 1.0f;
-    else if (BITS == 4) wgt[w] = (w & 1) ? 16.0f : 1.0f;
-    else {
-      const int j = 4 * (Q & 1) + w, e = j < 5 ? j : j - 5;
-      wgt[w] = (float)(1 << (2 * e));
-    }
-  }
-  for (int st0 = 0; st0 < n_steps; st0 += nthreads / U) {
-    const int st = st0 + tid / U;                  // uniform over the U lanes of a step
-    float a = 0.f;
-    if (st < n_steps) {
-      const uint4 v = HP[Q * C + st * CPS + cc];
-      const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int w = 0; w < 4; ++w) a += (f16_bits_to_f32(wv[w]) + f16_bits_to_f32(wv[w] >> 16)) * wgt[w];
-    }
-#pragma unroll
-    for (int m = 1; m < U; m <<= 1) a += __shfl_xor(a, m);
-    if (st < n_steps && u == 0) KS[st] = a * (Fmt<BITS>::OFF * 5.9604644775390625e-08f);
-  }
-}
-__global__ __launch_bounds__(256) void k_h_sums(LayerDims L, const DevExpert* __restrict__ table,
-                                                const int32_t* __restrict__ gexp, uint32_t* __restrict__ HA,
-                                                int64_t pair_words) {
-  const int f = L.d_ff;
-  const int g = blockIdx.x;
-  const int bits = table[gexp[g]].bits;
-  uint32_t* HPw = HA + (size_t)g * pair_words;
-  float* KS = (float*)(HPw + f / 2);
-  if (bits == 2) h_step_sums<2>((const uint4*)HPw, f, threadIdx.x, blockDim.x, KS);
-  else if (bits == 4) h_step_sums<4>((const uint4*)HPw, f, threadIdx.x, blockDim.x, KS);
-  else h_step_sums<8>((const uint4*)HPw, f, threadIdx.x, blockDim.x, KS);
+  uint32_t* XP = OUT + (size_t)g * pair_words;
+  float* KS = (float*)(XP + cols / 2);
+  float* scratch = (float*)(smem + cols / 2);     // the per-chunk offset terms permute_x also makes; not kept
+  if (bits == 2) { permute_x<2>(RAW, cols, L.group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<2>(RAW, cols, threadIdx.x, blockDim.x, KS); }
+  else if (bits == 4) { permute_x<4>(RAW, cols, L.group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<4>(RAW, cols, threadIdx.x, blockDim.x, KS); }
+  else { permute_x<8>(RAW, cols, L.group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<8>(RAW, cols, threadIdx.x, blockDim.x, KS); }
+  if (threadIdx.x == 0) KS[cols / 64] = up;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -169,11 +126,10 @@ struct GemmArgs {
   const int2* blocks;
   const int32_t* n_blocks;
   const int32_t* poff;
-  const uint32_t* A;        // staged activations: per pair [K/2 pair words][K steps of offset terms]
+  const uint32_t* A;        // staged activations: per pair [K/2 pair words][K/64 offset terms][2^e ...]
   int64_t a_pair_words;
-  uint32_t* H;              // phase 1 out: staged h per pair (same structure, K = d_ff)
-  int64_t h_pair_words;
-  float* Y;                 // phase 2 out: [pairs][d_model]
+  float* Hf;                // GEMM 1 out: h per pair, fp32 [pairs][d_ff]
+  float* Y;                 // GEMM 2 out: [pairs][d_model]
 };
 
 // uint4 index, inside a pair's staged words, of A operand q of a K step for k block kb
@@ -274,7 +230,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
       const int akb = item & 3, tok = (item >> 2) & 63, q = item >> 8;
       As[(buf * NQ * 4 + q * 4 + akb) * APAD + tok] = A.v[r];
     }
-    if (threadIdx.x < kTB) Ks[buf * kTB + threadIdx.x] = -A.ks;   // negated: the accumulations start there
+    if (threadIdx.x < kTB) Ks[buf * kTB + threadIdx.x] = A.ks;    // already negated: the accumulations start there
   };
 
   float4_t acc[NS][4];
@@ -431,14 +387,21 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   unpack(B, step);
   multiply(step & 1);
 
-  // D element i of lane (n, kb) belongs to token 16*t4 + 4*kb + i and row n of the stream
+  // D element i of lane (n, kb) belongs to token 16*t4 + 4*kb + i and row n of the stream. The factor of the
+  // subnormal code fields (2^24) and the one that undoes the normalisation of the token's activations are
+  // applied here, in that order.
+  float upt[4][4];
+#pragma unroll
+  for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int tok = min(16 * t4 + 4 * kb + i, ntok - 1);
+      upt[t4][i] = ((const float*)(G.A + (size_t)(g0 + tok) * G.a_pair_words + K / 2))[K / 64];
+    }
   if constexpr (PHASE == 0) {
-    const int Cf = N / WPC;
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
       const int row = R0 + rb * 16 + n;
-      float ps;
-      const int si = staged_index<BITS>(min(row, N - 1), Cf, ps);
 #pragma unroll
       for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
@@ -446,12 +409,10 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
           const int tok = 16 * t4 + 4 * kb + i;
           if (tok < ntok && row < N) {
             float v;
-            const float a = acc[rb][t4][i] * 16777216.0f;
-            if constexpr (NM == 2) v = a / (1.0f + __expf(-a)) * (acc[RBW + rb][t4][i] * 16777216.0f);
+            const float a = acc[rb][t4][i] * 16777216.0f * upt[t4][i];
+            if constexpr (NM == 2) v = a / (1.0f + __expf(-a)) * (acc[RBW + rb][t4][i] * 16777216.0f * upt[t4][i]);
             else v = fmaxf(a, 0.f);
-            const uint32_t hb = f32_to_f16_bits(v);
-            uint16_t* Hp = (uint16_t*)(G.H + (size_t)(g0 + tok) * G.h_pair_words);
-            Hp[si] = (uint16_t)f32_to_f16_bits(f16_bits_to_f32(hb) * ps);
+            G.Hf[(size_t)(g0 + tok) * N + row] = v;
           }
         }
     }
@@ -464,7 +425,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int tok = 16 * t4 + 4 * kb + i;
-          if (tok < ntok && row < N) G.Y[(size_t)(g0 + tok) * N + row] = acc[s][t4][i] * 16777216.0f;
+          if (tok < ntok && row < N) G.Y[(size_t)(g0 + tok) * N + row] = acc[s][t4][i] * 16777216.0f * upt[t4][i];
         }
     }
   }
@@ -512,8 +473,8 @@ PrefillWs prefill_ws(const LayerDims& L, int64_t T) {
   PrefillWs w{};
   const size_t M = (size_t)T * L.top_k;
   const size_t max_blocks = M / kTB + (size_t)L.n_experts;
-  w.a_pair_words = (size_t)L.d_model / 2 + (size_t)L.d_model / 64;
-  w.h_pair_words = (size_t)L.d_ff / 2 + (size_t)L.d_ff / 64;
+  w.a_pair_words = (size_t)L.d_model / 2 + (size_t)L.d_model / 64 + 4;
+  w.h_pair_words = (size_t)L.d_ff / 2 + (size_t)L.d_ff / 64 + 4;
   size_t off = 0;
   w.poff = off;    off += up256(((size_t)L.n_experts + 1) * 4);
   w.nblk = off;    off += 256;
@@ -523,6 +484,7 @@ PrefillWs prefill_ws(const LayerDims& L, int64_t T) {
   w.gexp = off;    off += up256(M * 4);
   w.xa = off;      off += up256(M * w.a_pair_words * 4);
   w.ha = off;      off += up256(M * w.h_pair_words * 4);
+  w.hf = off;      off += up256(M * (size_t)L.d_ff * 4);
   w.ypair = off;   off += up256(M * (size_t)L.d_model * 4);
   w.total = off;
   w.max_blocks = max_blocks;
@@ -544,15 +506,18 @@ hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void
   float* Ypair = (float*)(ws + w.ypair);
   hipLaunchKernelGGL(k_count_pairs, dim3(1), dim3(1024), 0, st, idx, M, L.n_experts, poff, blocks, nblk);
   hipLaunchKernelGGL(k_scatter_pairs, dim3(L.n_experts), dim3(256), 0, st, idx, M, poff, gpair, ginv, gexp);
-  const size_t stage_lds = (size_t)L.d_model * 2 + (size_t)L.d_model / 16 * 4 + 64;
-  hipLaunchKernelGGL(k_stage_x, dim3(M), dim3(256), stage_lds, st, L, table, x, gpair, gexp, XA, (int64_t)w.a_pair_words);
-  GemmArgs G{L, table, blocks, nblk, poff, XA, (int64_t)w.a_pair_words, HA, (int64_t)w.h_pair_words, Ypair};
+  float* Hf = (float*)(ws + w.hf);
+  auto stage_lds = [](int cols) { return (size_t)cols * 2 + (size_t)cols / 16 * 4 + 64; };
+  hipLaunchKernelGGL(k_stage<false>, dim3(M), dim3(256), stage_lds(L.d_model), st, L, table, x, gpair, gexp, XA,
+                     (int64_t)w.a_pair_words);
+  GemmArgs G{L, table, blocks, nblk, poff, XA, (int64_t)w.a_pair_words, Hf, Ypair};
   const unsigned nb = (unsigned)w.max_blocks;
   if (L.act == MOEQ_ACT_SWIGLU)
     hipLaunchKernelGGL((k_gemm_q<2, 0>), dim3((L.d_ff + kGemmWaves * 32 - 1) / (kGemmWaves * 32), nb), dim3(kGemmThreads), 0, st, G);
   else
     hipLaunchKernelGGL((k_gemm_q<1, 0>), dim3((L.d_ff + kGemmWaves * 64 - 1) / (kGemmWaves * 64), nb), dim3(kGemmThreads), 0, st, G);
-  hipLaunchKernelGGL(k_h_sums, dim3(M), dim3(256), 0, st, L, table, gexp, HA, (int64_t)w.h_pair_words);
+  hipLaunchKernelGGL(k_stage<true>, dim3(M), dim3(256), stage_lds(L.d_ff), st, L, table, (const void*)Hf, gpair, gexp, HA,
+                     (int64_t)w.h_pair_words);
   G.A = HA;
   G.a_pair_words = (int64_t)w.h_pair_words;
   const dim3 grid2((L.d_model + kGemmWaves * 32 - 1) / (kGemmWaves * 32), nb);
