@@ -160,6 +160,20 @@ moeq_status moe_layer_forward(const moeq_layer *layer, const void *x, int32_t n_
                               int32_t *topk_idx_opt, float *topk_gate_opt, void *ws,
                               size_t ws_bytes, void *stream);
 
+/* moe_layer_forward for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same computation, same kernels, same
+ * results; the scratch that `ws` brings in elsewhere is a fixed array inside the library's device code
+ * (moe_static_scratch_bytes() bytes, 8 MiB, held on every GPU the library runs on until the process ends).
+ * The call allocates nothing and frees nothing. Returns MOEQ_EWORKSPACE when
+ * moe_workspace_bytes(layer, n_tokens) exceeds that size (e.g. more than 2 tokens per call on a
+ * Mixtral-sized layer in the columns layout: split the call), MOEQ_EDEVICE when the array's address cannot be
+ * obtained. All calls on one GPU share the one array, which keeps the previous call's contents (nothing in
+ * it needs clearing: every piece is written before it is read): calls that overlap on one GPU - two streams,
+ * two threads - race; order them on one stream. x, y, topk_*_opt, stream as for moe_layer_forward. */
+size_t moe_static_scratch_bytes(void);
+moeq_status moe_layer_forward_static(const moeq_layer *layer, const void *x, int32_t n_tokens, float *y,
+                                     int32_t *topk_idx_opt, float *topk_gate_opt, void *stream);
+
 /* The layer with the routing GIVEN by the caller instead of computed by the router: static-routing
  * layers (Section 3.1, "Applicability": hash layers, expert-choice layers - the experts of a token
  * follow from the input tokens, not from its hidden state):

@@ -74,6 +74,10 @@ def lib():
     L.moe_expert_ffn_q.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp, sz, vp]
     L.moe_layer_forward.restype = C.c_int
     L.moe_layer_forward.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.moe_static_scratch_bytes.restype = sz
+    L.moe_static_scratch_bytes.argtypes = []
+    L.moe_layer_forward_static.restype = C.c_int
+    L.moe_layer_forward_static.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     L.moe_layer_forward_routed.restype = C.c_int
     L.moe_layer_forward_routed.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.moe_quantize_pack.restype = C.c_int
@@ -91,7 +95,7 @@ def lib():
 
 EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
            "moe_layer_destroy", "moe_workspace_bytes", "moe_layer_path", "moe_router_topk", "moe_expert_ffn_q",
-           "moe_layer_forward", "moe_layer_forward_routed", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
+           "moe_layer_forward", "moe_layer_forward_routed", "moe_layer_forward_static", "moe_static_scratch_bytes", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
            "moe_unprepare_out"]
 
 
@@ -290,6 +294,25 @@ def moe_layer_forward(layer, x, y=None, want_routing=False, ws=None, stream=None
         ws = layer.workspace(T)
     _check(lib().moe_layer_forward(layer.handle, _ptr(x), T, _ptr(y), _ptr(idx), _ptr(gate), _ptr(ws), ws.numel(),
                                    _stream(stream)), "moe_layer_forward")
+    return (y, idx, gate) if want_routing else y
+
+
+def moe_static_scratch_bytes():
+    return int(lib().moe_static_scratch_bytes())
+
+
+def moe_layer_forward_static(layer, x, y=None, want_routing=False, stream=None):
+    """moe_layer_forward without a workspace argument (the library's fixed scratch array is used)."""
+    T = x.shape[0]
+    dev = x.device
+    if y is None:
+        y = torch.empty((T, layer.d_model), dtype=torch.float32, device=dev)
+    idx = gate = None
+    if want_routing:
+        idx = torch.empty((T, layer.top_k), dtype=torch.int32, device=dev)
+        gate = torch.empty((T, layer.top_k), dtype=torch.float32, device=dev)
+    _check(lib().moe_layer_forward_static(layer.handle, _ptr(x), T, _ptr(y), _ptr(idx), _ptr(gate), _stream(stream)),
+           "moe_layer_forward_static")
     return (y, idx, gate) if want_routing else y
 
 

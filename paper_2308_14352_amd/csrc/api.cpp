@@ -91,6 +91,30 @@ int inline_router_max() {
 
 inline moeq_status dev(hipError_t e) { return e == hipSuccess ? MOEQ_OK : MOEQ_EDEVICE; }
 
+// Scratch of moe_layer_forward_static: device memory that belongs to the library's code object, so that the
+// entry point needs neither a workspace from its caller nor an allocation. Every GPU the library runs on
+// holds its own copy of the array at its own address; the name below is only a host-side handle, the
+// address on the current device comes from hipGetSymbolAddress (once per device) and is what the kernels
+// and every other use get.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device (nullptr when HIP refuses), looked up on first use per device.
+void* static_scratch() {
+  int devid = -1;
+  if (hipGetDevice(&devid) != hipSuccess || devid < 0 || devid >= kMaxDevices) return nullptr;
+  void* p = __atomic_load_n(&g_scratch_ptr[devid], __ATOMIC_ACQUIRE);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  __atomic_store_n(&g_scratch_ptr[devid], p, __ATOMIC_RELEASE);   // racing threads store the same value
+  return p;
+}
+
 // Measurement aid (moe_profile_kernel): events to record around one kernel of moe_layer_forward.
 struct ProfileHook { int32_t which; hipEvent_t start, stop; };
 ProfileHook g_profile = {0, nullptr, nullptr};
@@ -184,6 +208,7 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
     delete L;
     return MOEQ_EDEVICE;
   }
+  (void)static_scratch();   // set-up time is the place for the symbol lookup; the entry point repeats it if needed
   *out = L;
   return MOEQ_OK;
 }
@@ -330,6 +355,19 @@ moeq_status moe_layer_forward_routed(const moeq_layer* layer, const void* x, int
   if (n_tokens > 0 && (!topk_idx || !topk_gate)) return MOEQ_EINVAL;
   if (((uintptr_t)topk_idx | (uintptr_t)topk_gate) & 3u) return MOEQ_EINVAL;
   return layer_forward_impl(layer, x, n_tokens, y, nullptr, nullptr, topk_idx, topk_gate, ws, ws_bytes, stream);
+}
+
+size_t moe_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+moeq_status moe_layer_forward_static(const moeq_layer* layer, const void* x, int32_t n_tokens, float* y,
+                                     int32_t* topk_idx_opt, float* topk_gate_opt, void* stream) {
+  if (!layer || n_tokens < 0) return MOEQ_EINVAL;
+  if (n_tokens == 0) return MOEQ_OK;
+  if (ws_layout(layer, n_tokens).total > kStaticScratchBytes) return MOEQ_EWORKSPACE;   // beyond the fixed scratch
+  void* ws = static_scratch();
+  if (!ws) return MOEQ_EDEVICE;
+  return layer_forward_impl(layer, x, n_tokens, y, topk_idx_opt, topk_gate_opt, nullptr, nullptr, ws,
+                            kStaticScratchBytes, stream);
 }
 
 int32_t moe_layer_path(const moeq_layer* layer, int32_t n_tokens) {
