@@ -48,6 +48,17 @@
  *   row r, for w < cols*b/32; scales[g][r] = canonical scale[r][g]. rows must be a multiple of 4. With
  *   W_out in this layout a layer's decode calls run as one streaming kernel per call (each workgroup
  *   takes a slice of d_ff through both FFN matrices) plus a small ordered reduction.
+ *
+ * Row-block stream layout of W_in / W_gate (optional, made by moe_prepare_in; cols = 4096, g = 128)
+ *   Codes and scales of a matrix in ONE buffer of rows * (cols*b/8 + cols/g*2) bytes, cut into blocks of
+ *   RB = 16/b rows (8, 4, 2 rows at 2, 4, 8 bits). A block is 8 tiles of 1 KB followed by 64 * RB bytes of
+ *   scales. Tile t holds part t % (b/2) of row t / (b/2) of the block: its 16-byte piece l (l = 0..63) is the
+ *   canonical bytes [16 * ((b/2) * l + part), +16) of that row, so that piece l of every tile of a row lies in
+ *   the columns [64 l, 64 l + 64). The scale bytes of piece l are the RB/2 binary16 values
+ *   scale[row0 + (l & 1) * RB/2 + i][l >> 1], i < RB/2. A pure permutation of the canonical bytes: a wavefront
+ *   of the decode kernel reads a block front to back, its lanes always own the same columns, and the scales
+ *   arrive in the same memory pages as the codes they belong to. With W_in / W_gate in this layout and W_out
+ *   in the dword-column-major one a decode call runs as one streaming kernel on integer dot products.
  */
 #ifndef MOEQ_H
 #define MOEQ_H
@@ -70,6 +81,7 @@ typedef enum {
 typedef enum { MOEQ_ACT_RELU = 0, MOEQ_ACT_SWIGLU = 1 } moeq_act;
 typedef enum { MOEQ_F32 = 0, MOEQ_BF16 = 1 } moeq_dtype;
 typedef enum { MOEQ_OUT_CANONICAL = 0, MOEQ_OUT_COLUMNS = 1 } moeq_out_layout;
+typedef enum { MOEQ_IN_CANONICAL = 0, MOEQ_IN_STREAM = 1 } moeq_in_layout;
 
 /* One expert's packed weights: dev pointers, read-only, in the canonical format.
  * ReLU   (Switch-style): h = relu(W_in x),            y = W_out h;   q_gate/s_gate = NULL
@@ -95,6 +107,9 @@ typedef struct moeq_layer_desc {
   const float *router_bias; /* dev [n_experts] fp32 or NULL                                    */
   const moeq_expert *experts; /* host array [n_experts] of dev pointers                        */
   int32_t out_layout;       /* moeq_out_layout of every expert's q_out / s_out                 */
+  int32_t in_layout;        /* moeq_in_layout of every expert's W_in / W_gate. MOEQ_IN_STREAM: q_in and
+                               q_gate point to stream buffers (moe_prepare_in), s_in / s_gate are not
+                               read (may be NULL); needs out_layout = MOEQ_OUT_COLUMNS                */
 } moeq_layer_desc;
 
 typedef struct moeq_layer moeq_layer; /* opaque, host-side handle */
@@ -110,7 +125,9 @@ size_t moe_layer_table_bytes(int32_t n_experts);
  * `group`; group a multiple of 32 (a multiple of 64 or exactly 32 for 2-bit experts);
  * d_model*bits and d_ff*bits multiples of 128 for every expert; 1 <= top_k <= min(8, n_experts);
  * n_experts <= 1024; d_model, d_ff <= 32768. With out_layout = MOEQ_OUT_COLUMNS also: group and d_ff
- * multiples of 16, d_model <= 8192 (else MOEQ_EUNSUPPORTED).
+ * multiples of 16, d_model <= 8192 (else MOEQ_EUNSUPPORTED). With in_layout = MOEQ_IN_STREAM also: out_layout =
+ * MOEQ_OUT_COLUMNS, d_model = 4096, group = 128, d_ff a multiple of 64 (else MOEQ_EUNSUPPORTED); calls on such a
+ * layer run the streaming kernel at every token count (32 tokens per launch).
  * Errors: MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EDEVICE (copy failed). */
 moeq_status moe_layer_create(const moeq_layer_desc *desc, void *table_dev, size_t table_bytes,
                              moeq_layer **out);
@@ -128,6 +145,7 @@ size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);
 #define MOEQ_PATH_ONE_KERNEL 1     /* columns layout: one streaming kernel per 32 tokens, vector instr.   */
 #define MOEQ_PATH_ONE_KERNEL_MX 2  /* columns layout: the same with matrix-core instructions              */
 #define MOEQ_PATH_GROUPED_GEMM 3   /* 32 tokens or more, either layout: pairs grouped by expert, GEMMs   */
+#define MOEQ_PATH_STREAM 4         /* stream + columns layouts: one streaming kernel on integer dot products */
 int32_t moe_layer_path(const moeq_layer *layer, int32_t n_tokens);
 
 /* Codes bytes of a packed [rows][cols] matrix; *scale_bytes_opt receives the bytes of its scales.
@@ -211,6 +229,17 @@ moeq_status moe_prepare_out(const void *q, const void *s, int64_t rows, int64_t 
                             int32_t group, void *q_cols, void *s_cols, void *stream);
 moeq_status moe_unprepare_out(const void *q_cols, const void *s_cols, int64_t rows, int64_t cols,
                               int32_t bits, int32_t group, void *q, void *s, void *stream);
+
+/* W_in or W_gate of one expert, canonical -> row-block stream layout (see the top of this file) and back:
+ * device to device, out of place. rows = d_ff (a multiple of 8), cols = d_model = 4096, group = 128 (else
+ * MOEQ_EUNSUPPORTED); `stream_buf` holds moe_stream_bytes(rows, cols, bits, group) bytes, 16-byte aligned.
+ * Both are pure permutations: moe_unprepare_in(moe_prepare_in(q, s)) returns q and s bit for bit.
+ * moe_stream_bytes returns 0 for a shape the layout does not cover. */
+size_t moe_stream_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group);
+moeq_status moe_prepare_in(const void *q, const void *s, int64_t rows, int64_t cols, int32_t bits,
+                           int32_t group, void *stream_buf, void *stream);
+moeq_status moe_unprepare_in(const void *stream_buf, int64_t rows, int64_t cols, int32_t bits,
+                             int32_t group, void *q, void *s, void *stream);
 
 /* Measurement aid. While `which` names a kernel, every moe_layer_forward
  * call records start_event just before and stop_event just after that kernel on the call's stream

@@ -16,6 +16,7 @@ MOEQ_OK, MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EWORKSPACE, MOEQ_EDEVICE = range(5
 MOEQ_ACT_RELU, MOEQ_ACT_SWIGLU = 0, 1
 MOEQ_F32, MOEQ_BF16 = 0, 1
 MOEQ_OUT_CANONICAL, MOEQ_OUT_COLUMNS = 0, 1
+MOEQ_IN_CANONICAL, MOEQ_IN_STREAM = 0, 1
 
 
 class MoeqError(RuntimeError):
@@ -36,7 +37,7 @@ class moeq_layer_desc(C.Structure):
                 ("top_k", C.c_int32), ("group", C.c_int32), ("act", C.c_int32),
                 ("renorm", C.c_int32), ("x_dtype", C.c_int32),
                 ("router_w", C.c_void_p), ("router_bias", C.c_void_p),
-                ("experts", C.POINTER(moeq_expert)), ("out_layout", C.c_int32)]
+                ("experts", C.POINTER(moeq_expert)), ("out_layout", C.c_int32), ("in_layout", C.c_int32)]
 
 
 _lib = None
@@ -86,6 +87,12 @@ def lib():
     L.moe_unpack_codes.argtypes = [vp, i64, i64, i32, vp, vp]
     L.moe_dequantize.restype = C.c_int
     L.moe_dequantize.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp]
+    L.moe_stream_bytes.restype = sz
+    L.moe_stream_bytes.argtypes = [i64, i64, i32, i32]
+    L.moe_prepare_in.restype = C.c_int
+    L.moe_prepare_in.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp]
+    L.moe_unprepare_in.restype = C.c_int
+    L.moe_unprepare_in.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
     for fn in (L.moe_prepare_out, L.moe_unprepare_out):
         fn.restype = C.c_int
         fn.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp]
@@ -96,7 +103,7 @@ def lib():
 EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
            "moe_layer_destroy", "moe_workspace_bytes", "moe_layer_path", "moe_router_topk", "moe_expert_ffn_q",
            "moe_layer_forward", "moe_layer_forward_routed", "moe_layer_forward_static", "moe_static_scratch_bytes", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
-           "moe_unprepare_out"]
+           "moe_unprepare_out", "moe_prepare_in", "moe_unprepare_in", "moe_stream_bytes"]
 
 
 def status_str(st):
@@ -119,7 +126,7 @@ def _stream(stream):
 
 
 MOEQ_KERNEL_FFN_IN, MOEQ_KERNEL_FFN_OUT, MOEQ_KERNEL_FUSED = 1, 2, 3
-MOEQ_PATH_TWO_KERNELS, MOEQ_PATH_ONE_KERNEL, MOEQ_PATH_ONE_KERNEL_MX, MOEQ_PATH_GROUPED_GEMM = 0, 1, 2, 3
+MOEQ_PATH_TWO_KERNELS, MOEQ_PATH_ONE_KERNEL, MOEQ_PATH_ONE_KERNEL_MX, MOEQ_PATH_GROUPED_GEMM, MOEQ_PATH_STREAM = 0, 1, 2, 3, 4
 
 
 def moe_profile_kernel(which, start_event=None, stop_event=None):
@@ -188,6 +195,30 @@ def moe_unprepare_out(qc, sc, cols, bits, group, stream=None):
     return q, s
 
 
+def moe_stream_bytes(rows, cols, bits, group):
+    return int(lib().moe_stream_bytes(rows, cols, bits, group))
+
+
+def moe_prepare_in(q, s, cols, bits, group, stream=None):
+    """Canonical W_in / W_gate (codes [rows][cols*bits/8], scales [rows][cols/group]) -> one stream buffer (uint8)."""
+    rows = q.shape[0]
+    n = moe_stream_bytes(rows, cols, bits, group)
+    if n == 0:
+        raise MoeqError(MOEQ_EUNSUPPORTED, "moe_prepare_in")
+    buf = torch.empty(n, dtype=torch.uint8, device=q.device)
+    _check(lib().moe_prepare_in(_ptr(q), _ptr(s), rows, cols, bits, group, _ptr(buf), _stream(stream)), "moe_prepare_in")
+    return buf
+
+
+def moe_unprepare_in(buf, rows, cols, bits, group, stream=None):
+    """Inverse of moe_prepare_in: (codes, scales) in the canonical format."""
+    q = torch.empty((rows, cols * bits // 8), dtype=torch.uint8, device=buf.device)
+    s = torch.empty((rows, cols // group), dtype=torch.float16, device=buf.device)
+    _check(lib().moe_unprepare_in(_ptr(buf), rows, cols, bits, group, _ptr(q), _ptr(s), _stream(stream)),
+           "moe_unprepare_in")
+    return q, s
+
+
 class PackedExpert:
     """Device tensors of one expert in the boundary format (keeps them alive). q_out/s_out are in the
     layout the owning Layer is created with."""
@@ -202,6 +233,14 @@ class PackedExpert:
         qc, sc = moe_prepare_out(self.q_out, self.s_out, d_ff, self.bits, group)
         return PackedExpert(self.bits, self.q_in, self.s_in, qc, sc, self.q_gate, self.s_gate)
 
+    def with_stream_layout(self, d_model, d_ff, group):
+        """A copy of this expert (canonical) for a MOEQ_IN_STREAM layer: W_in / W_gate as stream buffers (their
+        scales inside), W_out in the dword-column-major layout."""
+        qc, sc = moe_prepare_out(self.q_out, self.s_out, d_ff, self.bits, group)
+        b_in = moe_prepare_in(self.q_in, self.s_in, d_model, self.bits, group)
+        b_gate = None if self.q_gate is None else moe_prepare_in(self.q_gate, self.s_gate, d_model, self.bits, group)
+        return PackedExpert(self.bits, b_in, None, qc, sc, b_gate, None)
+
     def nbytes(self):
         ts = [self.q_in, self.s_in, self.q_out, self.s_out, self.q_gate, self.s_gate]
         return sum(t.numel() * t.element_size() for t in ts if t is not None)
@@ -215,8 +254,9 @@ class Layer:
     """Owner of a moeq_layer handle and of the device tensors it borrows."""
 
     def __init__(self, d_model, d_ff, top_k, group, act, renorm, x_dtype, router_w, router_bias, experts,
-                 out_layout=MOEQ_OUT_CANONICAL):
+                 out_layout=MOEQ_OUT_CANONICAL, in_layout=MOEQ_IN_CANONICAL):
         self.out_layout = out_layout
+        self.in_layout = in_layout
         self.d_model, self.d_ff, self.top_k, self.group = d_model, d_ff, top_k, group
         self.n_experts = len(experts)
         self.experts = list(experts)
@@ -226,7 +266,7 @@ class Layer:
         self._table = torch.empty(max(moe_layer_table_bytes(self.n_experts), 16), dtype=torch.uint8, device=dev)
         arr = (moeq_expert * self.n_experts)(*[e.c_struct() for e in self.experts])
         desc = moeq_layer_desc(d_model, d_ff, self.n_experts, top_k, group, act, int(bool(renorm)), x_dtype,
-                               _ptr(router_w), _ptr(router_bias), arr, out_layout)
+                               _ptr(router_w), _ptr(router_bias), arr, out_layout, in_layout)
         h = C.c_void_p()
         _check(lib().moe_layer_create(C.byref(desc), _ptr(self._table), self._table.numel(), C.byref(h)),
                "moe_layer_create")

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoeq.so")
-SOURCES = ["api.cpp", "router.hip", "ffn_decode.hip", "decode_fused.hip", "prefill.hip", "quant.hip"]
+SOURCES = ["api.cpp", "router.hip", "ffn_decode.hip", "decode_fused.hip", "decode_stream.hip", "prefill.hip", "quant.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed-fp32 instructions are kept off on this target: some of their forms have given wrong results

@@ -17,6 +17,7 @@ struct moeq_layer {
   std::vector<int32_t> bits;       // host copy of the bitwidth table
   int32_t bits_mask;               // or of the bitwidths in the table (2 | 4 | 8)
   int32_t out_layout;              // layout of W_out (MOEQ_OUT_CANONICAL or MOEQ_OUT_COLUMNS)
+  int32_t in_layout;               // layout of W_in / W_gate (MOEQ_IN_CANONICAL or MOEQ_IN_STREAM)
   FusedPlan plan;                  // split of the one-kernel path (out_layout == MOEQ_OUT_COLUMNS)
 };
 
@@ -75,7 +76,8 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
 
 bool use_prefill(const moeq_layer* layer, int64_t T) {
   static const bool off = [] { const char* v = std::getenv("MOEQ_NO_PREFILL"); return v && v[0] == '1'; }();
-  return !off && T >= kPrefillMinTokens && prefill_supported(layer->dims);
+  // the grouped GEMMs read W_in / W_gate in the canonical format only
+  return !off && T >= kPrefillMinTokens && layer->in_layout == MOEQ_IN_CANONICAL && prefill_supported(layer->dims);
 }
 
 // Routers with at most this many experts are evaluated inside the one-kernel path by every workgroup;
@@ -163,12 +165,18 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   if (desc->act != MOEQ_ACT_RELU && desc->act != MOEQ_ACT_SWIGLU) return MOEQ_EINVAL;
   if (desc->x_dtype != MOEQ_F32 && desc->x_dtype != MOEQ_BF16) return MOEQ_EINVAL;
   if (desc->out_layout != MOEQ_OUT_CANONICAL && desc->out_layout != MOEQ_OUT_COLUMNS) return MOEQ_EINVAL;
+  if (desc->in_layout != MOEQ_IN_CANONICAL && desc->in_layout != MOEQ_IN_STREAM) return MOEQ_EINVAL;
+  const bool stream = desc->in_layout == MOEQ_IN_STREAM;
+  if (stream && desc->out_layout != MOEQ_OUT_COLUMNS) return MOEQ_EINVAL;
   if (d % g || f % g) return MOEQ_EINVAL;
   if (((uintptr_t)table_dev & 15u) || table_bytes < moe_layer_table_bytes(E)) return MOEQ_EINVAL;
   if (k > 8 || E > 1024 || d > 32768 || f > 32768 || d % 8 || f % 8) return MOEQ_EUNSUPPORTED;
   const LayerDims dims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0};
   FusedPlan plan{0, 0, 0, 0};
-  if (desc->out_layout == MOEQ_OUT_COLUMNS) {
+  if (stream) {
+    if (!stream_supported(dims)) return MOEQ_EUNSUPPORTED;
+    plan = FusedPlan{64, stream_slices(dims), 512, 0};
+  } else if (desc->out_layout == MOEQ_OUT_COLUMNS) {
     plan = plan_fused(dims);
     if (!plan.SW) return MOEQ_EUNSUPPORTED;
   }
@@ -178,8 +186,8 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   for (int32_t e = 0; e < E; ++e) {
     const moeq_expert& x = desc->experts[e];
     if (!bits_ok(x.bits)) return MOEQ_EINVAL;
-    if (!x.q_in || !x.s_in || !x.q_out || !x.s_out) return MOEQ_EINVAL;
-    if (desc->act == MOEQ_ACT_SWIGLU && (!x.q_gate || !x.s_gate)) return MOEQ_EINVAL;
+    if (!x.q_in || (!stream && !x.s_in) || !x.q_out || !x.s_out) return MOEQ_EINVAL;
+    if (desc->act == MOEQ_ACT_SWIGLU && (!x.q_gate || (!stream && !x.s_gate))) return MOEQ_EINVAL;
     if (((int64_t)d * x.bits) % 128 || ((int64_t)f * x.bits) % 128) return MOEQ_EINVAL;
     if (!group_ok(g, x.bits)) return MOEQ_EUNSUPPORTED;
     const uintptr_t align_or = (uintptr_t)x.q_in | (uintptr_t)x.q_out | (uintptr_t)x.q_gate;
@@ -203,6 +211,7 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   for (int32_t b : bits) L->bits_mask |= b;
   L->bits = std::move(bits);
   L->out_layout = desc->out_layout;
+  L->in_layout = desc->in_layout;
   L->plan = plan;
   if (hipMemcpy(table_dev, tab.data(), tab.size() * sizeof(DevExpert), hipMemcpyHostToDevice) != hipSuccess) {
     delete L;
@@ -253,10 +262,14 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
     const size_t x_row = (size_t)layer->dims.d_model * (layer->dims.x_bf16 ? 2 : 4);
     for (int32_t t0 = 0; t0 < n_tokens; t0 += kDecodeChunk) {
       const int32_t n = n_tokens - t0 < kDecodeChunk ? n_tokens - t0 : kDecodeChunk;
-      if (launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert,
-                            gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr, layer->bits[(size_t)expert],
-                            (const char*)x + (size_t)t0 * x_row, n, part, nullptr, nullptr, st) != hipSuccess)
-        return MOEQ_EDEVICE;
+      const hipError_t le = layer->in_layout == MOEQ_IN_STREAM
+          ? launch_moe_stream(layer->dims, layer->table, nullptr, nullptr, nullptr, expert,
+                              gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr,
+                              (const char*)x + (size_t)t0 * x_row, n, part, nullptr, nullptr, st)
+          : launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert,
+                              gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr, layer->bits[(size_t)expert],
+                              (const char*)x + (size_t)t0 * x_row, n, part, nullptr, nullptr, st);
+      if (le != hipSuccess) return MOEQ_EDEVICE;
       if (launch_reduce_partials(part, layer->plan.n_slices, layer->dims.d_model, n, accumulate ? 1 : 0,
                                  y + (size_t)t0 * layer->dims.d_model, st) != hipSuccess)
         return MOEQ_EDEVICE;
@@ -303,8 +316,11 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
   }
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     // one streaming kernel for the whole layer, then the ordered sum of its partial output vectors
+    const bool stream = layer->in_layout == MOEQ_IN_STREAM;
     const float* lg = nullptr;
-    if (!given && L.n_experts > inline_router_max()) {
+    if (!given && L.n_experts > (stream ? (inline_router_max() < stream_inline_router_max() ? inline_router_max()
+                                                                                             : stream_inline_router_max())
+                                        : inline_router_max())) {
       if (launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
         return MOEQ_EDEVICE;
       lg = logits;
@@ -316,12 +332,18 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
       const size_t s0 = (size_t)t0 * (size_t)L.top_k;
       // the profiling events, when asked for, bracket the kernel's own execution (not its dispatch)
       const bool prof = t0 == 0 && g_profile.which == MOEQ_KERNEL_FUSED && g_profile.start && g_profile.stop;
-      if (launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias,
-                            lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
-                            given ? gate + s0 : nullptr, layer->bits_mask, (const char*)x + (size_t)t0 * x_row, n, part,
-                            given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
-                            prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr) != hipSuccess)
-        return MOEQ_EDEVICE;
+      const hipError_t le = stream
+          ? launch_moe_stream(L, layer->table, layer->router_w, layer->router_bias,
+                              lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
+                              given ? gate + s0 : nullptr, (const char*)x + (size_t)t0 * x_row, n, part,
+                              given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
+                              prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr)
+          : launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias,
+                              lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
+                              given ? gate + s0 : nullptr, layer->bits_mask, (const char*)x + (size_t)t0 * x_row, n,
+                              part, given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
+                              prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr);
+      if (le != hipSuccess) return MOEQ_EDEVICE;
       if (launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n, 0, y + (size_t)t0 * L.d_model, st) !=
           hipSuccess)
         return MOEQ_EDEVICE;
@@ -373,6 +395,7 @@ moeq_status moe_layer_forward_static(const moeq_layer* layer, const void* x, int
 int32_t moe_layer_path(const moeq_layer* layer, int32_t n_tokens) {
   if (!layer || n_tokens < 1) return -1;
   if (use_prefill(layer, n_tokens)) return MOEQ_PATH_GROUPED_GEMM;
+  if (layer->in_layout == MOEQ_IN_STREAM) return MOEQ_PATH_STREAM;
   if (layer->out_layout == MOEQ_OUT_COLUMNS) return layer->plan.mx ? MOEQ_PATH_ONE_KERNEL_MX : MOEQ_PATH_ONE_KERNEL;
   return MOEQ_PATH_TWO_KERNELS;
 }
@@ -421,6 +444,31 @@ moeq_status moe_prepare_out(const void* q, const void* s, int64_t rows, int64_t 
 moeq_status moe_unprepare_out(const void* q_cols, const void* s_cols, int64_t rows, int64_t cols, int32_t bits,
                               int32_t group, void* q, void* s, void* stream) {
   return relayout_out(q_cols, s_cols, rows, cols, bits, group, q, s, false, stream);
+}
+
+size_t moe_stream_bytes(int64_t rows, int64_t cols, int32_t bits, int32_t group) {
+  if (rows <= 0 || !bits_ok(bits) || cols != 4096 || group != 128 || rows % 8) return 0;
+  return (size_t)rows * ((size_t)cols * (size_t)bits / 8 + (size_t)(cols / group) * 2);
+}
+
+static moeq_status relayout_in(const void* q, const void* s, int64_t rows, int64_t cols, int32_t bits, int32_t group,
+                               const void* stream_buf, bool to_stream, void* stream) {
+  if (!q || !s || !stream_buf || rows <= 0 || cols <= 0 || !bits_ok(bits) || group <= 0) return MOEQ_EINVAL;
+  if (!moe_stream_bytes(rows, cols, bits, group)) return MOEQ_EUNSUPPORTED;
+  if (((uintptr_t)q | (uintptr_t)stream_buf) & 15u) return MOEQ_EINVAL;
+  if ((uintptr_t)s & 1u) return MOEQ_EINVAL;
+  if (q == stream_buf || s == stream_buf) return MOEQ_EINVAL;
+  return dev(launch_relayout_in(q, s, rows, bits, (void*)stream_buf, to_stream, (hipStream_t)stream));
+}
+
+moeq_status moe_prepare_in(const void* q, const void* s, int64_t rows, int64_t cols, int32_t bits, int32_t group,
+                           void* stream_buf, void* stream) {
+  return relayout_in(q, s, rows, cols, bits, group, stream_buf, true, stream);
+}
+
+moeq_status moe_unprepare_in(const void* stream_buf, int64_t rows, int64_t cols, int32_t bits, int32_t group, void* q,
+                             void* s, void* stream) {
+  return relayout_in(q, s, rows, cols, bits, group, stream_buf, false, stream);
 }
 
 moeq_status moe_unpack_codes(const void* q, int64_t rows, int64_t cols, int32_t bits, int8_t* codes_out,

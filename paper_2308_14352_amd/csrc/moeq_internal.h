@@ -77,6 +77,21 @@ hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_
 hipError_t launch_transpose(const void* in, int64_t rows, int64_t cols, int elem_bytes, void* out,
                             hipStream_t st);
 
+// ---- one-kernel decode path on integer dot products (W_in / W_gate in the row-block stream layout, W_out in
+// the dword-column-major layout; d_model 4096, scale groups of 128 columns). Arguments as launch_moe_decode;
+// the partial outputs are part[T][stream_slices(L)][d].
+bool stream_supported(const LayerDims& L);
+int stream_inline_router_max();
+int stream_slices(const LayerDims& L);
+hipError_t launch_moe_stream(const LayerDims& L, const DevExpert* table, const float* router_w,
+                             const float* router_bias, const float* logits, int32_t fixed_expert,
+                             const float* gate_in, const int32_t* route_idx, const float* route_gate, const void* x,
+                             int32_t T, float* part, int32_t* idx_out, float* gate_out, hipStream_t st,
+                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+// canonical (q, s) <-> stream buffer of a [rows][4096] matrix, groups of 128 columns
+hipError_t launch_relayout_in(const void* q, const void* s, int64_t rows, int bits, void* stream_buf, bool to_stream,
+                              hipStream_t st);
+
 // ---- batched (prefill) path: pairs grouped by expert, two quantized GEMMs on the matrix cores ----------
 // Byte offsets of the pieces of the prefill workspace (all 256-byte aligned) and the per-pair strides.
 struct PrefillWs {

@@ -30,9 +30,10 @@ def pack_expert_oracle(w, bits, group):
     return oracle.Expert(bits, q_in, s_in, q_out, s_out, q_g, s_g)
 
 
-def build_layer_pair(cfg, layer_id, device, bits_table=None, want_oracle=True, columns=False):
+def build_layer_pair(cfg, layer_id, device, bits_table=None, want_oracle=True, columns=False, stream=False):
     """Returns (moeq.Layer on `device`, [oracle.Expert] or None, Wr, bias). columns: the layer holds W_out in
-    the dword-column-major layout (the one-kernel decode path); layer.canonical keeps the canonical experts."""
+    the dword-column-major layout (the one-kernel decode path); stream: W_in / W_gate in the row-block stream
+    layout as well (the integer-dot streaming kernel); layer.canonical keeps the canonical experts."""
     bits_table = bits_table or gen.bitwidth_table(cfg, layer_id)
     gpu_experts, orc_experts = [], []
     for e in range(cfg.n_experts):
@@ -43,12 +44,15 @@ def build_layer_pair(cfg, layer_id, device, bits_table=None, want_oracle=True, c
         del w
     Wr, bias = gen.router_weights(cfg, layer_id, device)
     canonical = gpu_experts
-    if columns:
+    if stream:
+        gpu_experts = [e.with_stream_layout(cfg.d_model, cfg.d_ff, cfg.group) for e in canonical]
+    elif columns:
         gpu_experts = [e.with_out_columns(cfg.d_ff, cfg.group) for e in canonical]
     layer = moeq.Layer(cfg.d_model, cfg.d_ff, cfg.top_k, cfg.group,
                        moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU, cfg.renorm,
                        moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32, Wr, bias, gpu_experts,
-                       moeq.MOEQ_OUT_COLUMNS if columns else moeq.MOEQ_OUT_CANONICAL)
+                       moeq.MOEQ_OUT_COLUMNS if (columns or stream) else moeq.MOEQ_OUT_CANONICAL,
+                       moeq.MOEQ_IN_STREAM if stream else moeq.MOEQ_IN_CANONICAL)
     layer.canonical = canonical
     return layer, (orc_experts if want_oracle else None), Wr, bias
 

@@ -1,0 +1,174 @@
+"""GPU parity of the row-block stream layout and of the streaming decode kernel on integer dot products
+(MOEQ_IN_STREAM layers), through the C ABI, against the CPU oracle."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+import paper_2308_14352_amd as moeq
+from helpers import build_layer_pair, near_tie_tokens, oracle_layer, pack_expert_oracle, rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = 2e-3
+
+
+def stream_layout_reference(q, s, bits):
+    """The stream layout written out with numpy from canonical codes q [rows][4096*bits/8] (uint8) and scales
+    s [rows][32] (uint16): blocks of RB = 16/bits rows = 8 tiles of 1 KB + 64*RB bytes of scales."""
+    rows = q.shape[0]
+    tpr, rb = bits // 2, 16 // bits
+    pieces = q.reshape(rows, 64, tpr, 16)                 # piece tpr*l + part of a row -> [l][part]
+    tiles = pieces.transpose(0, 2, 1, 3)                  # [row][part][l][16 bytes]
+    tiles = tiles.reshape(rows // rb, 8 * 1024)           # tile t of a block = row t // tpr, part t % tpr
+    sb = s.reshape(rows // rb, 2, rb // 2, 32)            # [block][half of the rows][i][group]
+    sc = sb.transpose(0, 3, 1, 2).reshape(rows // rb, 64 * (rb // 2))   # lane l = 2*group + half: its rb/2 values
+    return np.concatenate([tiles, np.ascontiguousarray(sc).view(np.uint8)], axis=1).reshape(-1)
+
+
+@pytest.mark.parametrize("bits", (2, 4, 8))
+@pytest.mark.parametrize("rows", (8, 64, 1792))
+def test_prepare_in_is_the_documented_permutation_and_round_trips(bits, rows):
+    cols, g = 4096, 128
+    w = gen.normal((rows, cols), 0.02, gen.seed_for("stream", bits, rows), DEV)
+    q, s = moeq.moe_quantize_pack(w, bits, g)
+    buf = moeq.moe_prepare_in(q, s, cols, bits, g)
+    q2, s2 = moeq.moe_unprepare_in(buf, rows, cols, bits, g)
+    torch.cuda.synchronize()
+    q_ref, s_ref = oracle.quantize_pack(w.cpu().numpy(), bits, g)
+    assert buf.numel() == rows * (cols * bits // 8 + 64) == moeq.moe_stream_bytes(rows, cols, bits, g)
+    assert np.array_equal(buf.cpu().numpy(), stream_layout_reference(q_ref, s_ref, bits))
+    assert torch.equal(q2, q) and torch.equal(s2.view(torch.int16), s.view(torch.int16))
+    assert moeq.moe_stream_bytes(rows, 2048, bits, g) == 0 and moeq.moe_stream_bytes(rows, cols, bits, 64) == 0
+    assert moeq.moe_stream_bytes(12, cols, bits, g) == 0
+
+
+def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
+    dummy = oracle.Expert(4, np.zeros(1, np.uint8), np.zeros(1, np.uint16), np.zeros(1, np.uint8),
+                          np.zeros(1, np.uint16), np.zeros(1, np.uint8), np.zeros(1, np.uint16))
+    out = [dummy] * cfg.n_experts
+    for e in sorted(needed):
+        out[e] = pack_expert_oracle(gen.expert_weights(cfg, layer_id, e, DEV), bits_table[e], cfg.group)
+    return out
+
+
+@pytest.mark.parametrize("base,x_dtype,f,k,bits_table", [
+    ("c4", "bf16", 1024, 2, [2, 4, 8, 4]),      # SwiGLU, bf16 hidden states, top-2
+    ("c1", "f32", 768, 1, [4, 2, 8]),           # ReLU, fp32 hidden states, top-1
+    ("c4", "f32", 512, 3, [8, 8, 2, 2, 4]),     # three choices
+], ids=("swiglu-bf16", "relu-f32", "swiglu-f32-top3"))
+def test_stream_layer_small_d_ff(base, x_dtype, f, k, bits_table):
+    """Narrow layers (few slices) at d_model 4096: the layer, the single-expert entry, the static-routing entry
+    with every expert, repeated experts and out-of-range indices, purity, zero tokens."""
+    cfg = replace(gen.tiny_config(base, 4096, f, n_experts=len(bits_table), n_layers=1, group=128), top_k=k,
+                  x_dtype=x_dtype)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, stream=True)
+    E = len(bits_table)
+    T = 5
+    assert layer.path(1) == moeq.MOEQ_PATH_STREAM and layer.path(100) == moeq.MOEQ_PATH_STREAM
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 1
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+    y_b = moeq.moe_layer_forward(layer, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_b)
+    moeq.moe_layer_forward(layer, x[:0])
+    xh = x.float().cpu().numpy()
+    for e in range(E):
+        y_e = moeq.moe_expert_ffn_q(layer, e, x)
+        torch.cuda.synchronize()
+        y_e_ref = oracle.expert_ffn(orc_experts[e], cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), xh)
+        assert rel_err(y_e.cpu().numpy(), y_e_ref).max() < TOL, (e, bits_table[e])
+    rng = np.random.default_rng(77 + E)
+    idx_r = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    idx_r[0, 0] = -1
+    idx_r[T - 1, k - 1] = E
+    if k > 1:
+        idx_r[1, 1] = idx_r[1, 0]
+    gate_r = rng.uniform(0.05, 1.2, size=(T, k)).astype(np.float32)
+    y_r = moeq.moe_layer_forward_routed(layer, x, torch.from_numpy(idx_r).to(DEV), torch.from_numpy(gate_r).to(DEV))
+    torch.cuda.synchronize()
+    y_r_ref = oracle.layer_forward_routed(orc_experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), k, xh,
+                                          idx_r, gate_r)
+    live = np.abs(y_r_ref).max(axis=1) > 0
+    assert rel_err(y_r.cpu().numpy()[live], y_r_ref[live]).max() < TOL
+    assert np.array_equal(y_r.cpu().numpy()[~live], y_r_ref[~live])
+    # gate and accumulate through the single-expert entry
+    g1 = torch.linspace(0.25, 0.75, T, device=DEV)
+    y0 = gen.normal((T, cfg.d_model), 1.0, 99, DEV)
+    y2 = moeq.moe_expert_ffn_q(layer, 0, x, gate=g1, y=y0.clone(), accumulate=True)
+    torch.cuda.synchronize()
+    ref2 = y0.cpu().numpy().astype(np.float64) + g1.cpu().numpy()[:, None] * oracle.expert_ffn(
+        orc_experts[0], cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), xh)
+    assert np.abs(y2.cpu().numpy() - ref2).max() < TOL * np.abs(ref2).max()
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -13, 2.0 ** -10, 1.0, 2.0 ** 12, 2.0 ** 20], ids=lambda v: "x2^%d" % int(np.log2(v)))
+def test_stream_layer_scaled_hidden_states_and_outliers(scale):
+    cfg = replace(gen.tiny_config("c4", 4096, 512, n_experts=3, n_layers=1, group=128), x_dtype="f32")
+    bits_table = [2, 4, 8]
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, stream=True)
+    x = gen.hidden(cfg, 0, 0, 4, DEV) * scale
+    x[1, ::97] *= 1000.0                  # a few elements a thousand times the rest
+    x[2, 128:640] *= 2.0 ** -12           # whole scale groups far below the others
+    idx = np.array([[0, 1], [1, 2], [2, 0], [0, 1]], np.int32)
+    gate = np.full((4, 2), 0.5, np.float32)
+    y = moeq.moe_layer_forward_routed(layer, x, torch.from_numpy(idx).to(DEV), torch.from_numpy(gate).to(DEV))
+    torch.cuda.synchronize()
+    y_ref = oracle.layer_forward_routed(orc_experts, cfg.d_model, cfg.d_ff, cfg.group, 1, 2, x.cpu().numpy(), idx, gate)
+    assert np.isfinite(y_ref).all()
+    assert rel_err(y.cpu().numpy(), y_ref).max() < TOL
+
+
+def test_stream_layer_non_finite_and_zero_tokens_are_safe():
+    cfg = gen.tiny_config("c4", 4096, 512, n_experts=8, n_layers=1, group=128)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, stream=True)
+    x = gen.hidden(cfg, 0, 0, 5, DEV)
+    y_clean, idx_clean, _ = moeq.moe_layer_forward(layer, x, want_routing=True)
+    xb = x.clone()
+    xb[1, 5] = float("nan")
+    xb[2, 0] = float("inf")
+    xb[3] = 0.0
+    y, idx, gate = moeq.moe_layer_forward(layer, xb, want_routing=True)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    assert idx_h.min() >= 0 and idx_h.max() < cfg.n_experts
+    assert idx_h[1].tolist() == [0, 1] and idx_h[2].tolist() == [0, 1]
+    assert not torch.isfinite(y[1]).any() and not torch.isfinite(y[2]).any()
+    assert torch.equal(y[3], torch.zeros_like(y[3]))
+    assert torch.equal(y[[0, 4]], y_clean[[0, 4]]) and torch.equal(idx[[0, 4]], idx_clean[[0, 4]])
+
+
+@pytest.mark.parametrize("layer_id", (0, 5))
+def test_stream_layer_mixtral_shape(layer_id):
+    """The benchmark's layer shape (d_ff 14336: 224 slices), 2- and 4-bit experts, the router's own choices for
+    four tokens and every expert once through the static-routing entry."""
+    cfg = gen.CONFIGS["c4"]
+    bits_table = gen.bitwidth_table(cfg, layer_id)
+    layer, _, Wr, bias = build_layer_pair(cfg, layer_id, DEV, bits_table, want_oracle=False, stream=True)
+    T = 4
+    x = gen.hidden(cfg, layer_id, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, _ = oracle.router_topk(x.float().cpu().numpy(), Wr.cpu().numpy(), None, cfg.top_k, cfg.renorm)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 1
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    experts = _lazy_oracle_experts(cfg, layer_id, bits_table, set(idx_ref.flatten().tolist()))
+    y_ref, _, _ = oracle_layer(cfg, experts, Wr, bias, x)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+    # the static entry reproduces the layer bit for bit
+    y_r = moeq.moe_layer_forward_routed(layer, x, idx, gate)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_r)
