@@ -42,9 +42,11 @@ def parse():
     ap.add_argument("--prefill-only", action="store_true",
                     help="run only the c5 prefill layer call (the run its rocprofv3 summaries are made from), "
                          "print its figures as one JSON line and exit")
-    ap.add_argument("--layout", default="auto", choices=["auto", "columns", "canonical"],
-                    help="W_out layout: columns = one streaming kernel per layer call, canonical = the "
-                         "two-kernel path on the boundary format, auto = columns for single-token steps and "
+    ap.add_argument("--layout", default="auto", choices=["auto", "stream", "columns", "canonical"],
+                    help="weight layout: stream = W_in/W_gate in the row-block stream layout + W_out in columns (the "
+                         "integer-dot streaming kernel; d_model 4096, groups of 128), columns = W_out in columns (one "
+                         "streaming kernel per layer call), canonical = the two-kernel path on the boundary format, "
+                         "auto = stream where the shape allows it, else columns for single-token steps and "
                          "for the Mixtral-sized experts, canonical for small layers with several tokens")
     return ap.parse_args()
 
@@ -52,11 +54,11 @@ def parse():
 class Stack:
     """All layers of one workload, packed in HBM, plus the hidden states of every (step, layer)."""
 
-    def __init__(self, cfg, batch, steps, dev, n_layers=None, columns=True):
+    def __init__(self, cfg, batch, steps, dev, n_layers=None, columns=True, stream=False):
         import torch
         import gen
         import paper_2308_14352_amd as moeq
-        self.cfg, self.batch, self.steps, self.columns = cfg, batch, steps, columns
+        self.cfg, self.batch, self.steps, self.columns, self.stream = cfg, batch, steps, columns or stream, stream
         self.L = n_layers or cfg.n_layers
         self.layers, self.bits = [], []
         act = moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU
@@ -72,12 +74,17 @@ class Stack:
                 if cfg.swiglu:
                     q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], bits[e], cfg.group)
                 ex = moeq.PackedExpert(bits[e], q_in, s_in, q_out, s_out, q_g, s_g)
-                experts.append(ex.with_out_columns(cfg.d_ff, cfg.group) if columns else ex)
+                if stream:
+                    experts.append(ex.with_stream_layout(cfg.d_model, cfg.d_ff, cfg.group))
+                    del q_in, s_in, q_g, s_g
+                else:
+                    experts.append(ex.with_out_columns(cfg.d_ff, cfg.group) if columns else ex)
                 del w, ex, q_out, s_out
             Wr, bias = gen.router_weights(cfg, l, dev)
             self.layers.append(moeq.Layer(cfg.d_model, cfg.d_ff, cfg.top_k, cfg.group, act, cfg.renorm, xdt, Wr,
                                           bias, experts,
-                                          moeq.MOEQ_OUT_COLUMNS if columns else moeq.MOEQ_OUT_CANONICAL))
+                                          moeq.MOEQ_OUT_COLUMNS if (columns or stream) else moeq.MOEQ_OUT_CANONICAL,
+                                          moeq.MOEQ_IN_STREAM if stream else moeq.MOEQ_IN_CANONICAL))
             self.bits.append(bits)
         torch.cuda.synchronize()
         # hidden states of every (step, layer): [steps][L][batch][d]
@@ -343,12 +350,12 @@ WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8
 DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
 
 
-def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True, columns=True):
+def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True, layout="columns"):
     import gen
     cfg_id, batch = WORKLOADS[name]
     cfg = gen.CONFIGS[cfg_id]
     n_distinct = min(steps, cfg.steps)
-    stack = Stack(cfg, batch, n_distinct, dev, n_layers, columns)
+    stack = Stack(cfg, batch, n_distinct, dev, n_layers, columns=layout != "canonical", stream=layout == "stream")
     idx = stack.routing()
     bytes_sl = stack.algorithmic_bytes(idx)
     elapsed, _ = time_steps(stack, steps, warmup, use_graph)
@@ -406,14 +413,20 @@ def main():
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]
     use_graph = not args.no_graph
-    def use_columns(workload):
+    def pick_layout(workload):
         c = gen.CONFIGS[WORKLOADS[workload][0]]
         batch = WORKLOADS[workload][1]
-        # auto: the one-kernel path for single-token steps (measured faster on every configuration) and for
-        # the large layers; small layers with several tokens per step run faster on the two-kernel path
-        return args.layout == "columns" or (args.layout == "auto" and (batch == 1 or c.d_model * c.d_ff >= (1 << 24)))
-    columns = use_columns(name)
-    stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers, columns=columns)
+        if args.layout != "auto":
+            return args.layout
+        # auto: the stream layout where the integer-dot kernel takes the shape; else the one-kernel path for
+        # single-token steps (measured faster on every configuration) and for the large layers; small layers
+        # with several tokens per step run faster on the two-kernel path
+        if c.d_model == 4096 and c.group == 128:
+            return "stream"
+        return "columns" if (batch == 1 or c.d_model * c.d_ff >= (1 << 24)) else "canonical"
+    layout = pick_layout(name)
+    columns = layout != "canonical"
+    stack, res = run_workload(name, steps, args.warmup, use_graph, dev, args.layers, layout=layout)
     cfg = stack.cfg
     achieved = res["kernel_bytes"] / (res["kernel_ms"] * 1e-3) / 1e9
     out = {
@@ -427,18 +440,18 @@ def main():
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "act": cfg.act, "group": cfg.group,
                    "batch": stack.batch, "x_dtype": cfg.x_dtype, "bitwidths": cfg.bit_rule,
                    "packed_GB": round(res["packed_GB"], 3), "launch": "hip-graph" if use_graph else "eager",
-                   "w_out_layout": "columns" if columns else "canonical"},
+                   "layout": layout},
         "layer_tokens_per_s": res["layer_tokens_per_s"],
         "algorithmic_GBps": res["algorithmic_GBps"],
         "pct_hbm_peak": 100.0 * res["algorithmic_GBps"] / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm",
-                     "kernel": ("k_moe_decode (router + top-k + dequantize-fused FFN of every d_ff slice)" if columns
+                     "kernel": ("k_moe_stream (router + top-k + dequantize-fused FFN of every d_ff slice, integer dot "
+                                "products)" if layout == "stream" else
+                                "k_moe_decode (router + top-k + dequantize-fused FFN of every d_ff slice)" if columns
                                 else "k_ffn_in (phase 1: top-k + dequantize-fused W_in/W_gate GEMVs)"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "bytes_per_launch": res["kernel_bytes"], "avg_launch_ms": res["kernel_ms"],
-                     "traffic": (PMC_TRAFFIC_C4["fetch_bytes"] + PMC_TRAFFIC_C4["write_bytes"])
-                     if (name == "c4" and columns) else None,
-                     "traffic_detail": PMC_TRAFFIC_C4 if (name == "c4" and columns) else None},
+                     "traffic": None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stack, dev, 4 if name == "c4" else 12)
@@ -450,8 +463,8 @@ def main():
             if other == name:
                 continue
             st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False,
-                                 columns=use_columns(other))
-            extras[other] = {"w_out_layout": "columns" if use_columns(other) else "canonical"}
+                                 layout=pick_layout(other))
+            extras[other] = {"layout": pick_layout(other)}
             extras[other].update({kk: r[kk] for kk in ("tokens_per_s", "layer_tokens_per_s", "ms_per_step",
                                                   "algorithmic_GBps", "layers", "batch", "steps", "packed_GB")
                              if kk in r})

@@ -264,7 +264,7 @@ moeq_status moe_expert_ffn_q(const moeq_layer* layer, int32_t expert, const void
       const int32_t n = n_tokens - t0 < kDecodeChunk ? n_tokens - t0 : kDecodeChunk;
       const hipError_t le = layer->in_layout == MOEQ_IN_STREAM
           ? launch_moe_stream(layer->dims, layer->table, nullptr, nullptr, nullptr, expert,
-                              gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr,
+                              gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr, layer->bits_mask,
                               (const char*)x + (size_t)t0 * x_row, n, part, nullptr, nullptr, st)
           : launch_moe_decode(layer->dims, layer->plan, layer->table, nullptr, nullptr, nullptr, expert,
                               gate_opt ? gate_opt + t0 : nullptr, nullptr, nullptr, layer->bits[(size_t)expert],
@@ -335,8 +335,8 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
       const hipError_t le = stream
           ? launch_moe_stream(L, layer->table, layer->router_w, layer->router_bias,
                               lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
-                              given ? gate + s0 : nullptr, (const char*)x + (size_t)t0 * x_row, n, part,
-                              given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
+                              given ? gate + s0 : nullptr, layer->bits_mask, (const char*)x + (size_t)t0 * x_row, n,
+                              part, given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
                               prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr)
           : launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias,
                               lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,

@@ -716,6 +716,53 @@ __device__ __forceinline__ void topk_small(const float* __restrict__ lg, int E, 
   }
 }
 
+// The same for at most EMAX (8 or 16) experts and at most 2 choices, with no cross-lane step at all: every lane reads the
+// logits (broadcast reads) and selects in its own registers, so the chain is a few dozen dependent vector
+// instructions instead of a dozen DPP / readlane round trips. Same rules: order on the logits, ties to the
+// lowest index, an undefined softmax takes the experts 0 .. k-1 with NaN gates.
+template <int EMAX>
+__device__ __forceinline__ void topk_tiny(const float* __restrict__ lg, int E, int k, int renorm, int lane, int* sel_e,
+                                          float* sel_g) {
+  float v[EMAX];
+  float m = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) {
+    v[e] = e < E ? lg[e] : -INFINITY;
+    m = fmaxf(m, v[e]);
+  }
+  float z = 0.f;
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) z += e < E ? __expf(v[e] - m) : 0.f;
+  const bool defined = z >= 1.0f && z < INFINITY;
+  // first choice: the largest, lowest index on ties (strict comparison while walking up)
+  float b0 = v[0];
+  int i0 = 0;
+#pragma unroll
+  for (int e = 1; e < EMAX; ++e) {
+    const bool better = e < E && v[e] > b0;
+    b0 = better ? v[e] : b0;
+    i0 = better ? e : i0;
+  }
+  float b1 = -INFINITY;
+  int i1 = -1;
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) {
+    const bool ok = e < E && e != i0 && (i1 < 0 || v[e] > b1);
+    b1 = ok ? v[e] : b1;
+    i1 = ok ? e : i1;
+  }
+  const float p0 = __expf(b0 - m), p1 = k > 1 ? __expf(b1 - m) : 0.f;
+  const float inv = 1.0f / (renorm ? p0 + p1 : z);
+  if (lane == 0) {
+    sel_e[0] = defined ? i0 : 0;
+    sel_g[0] = defined ? p0 * inv : __builtin_nanf("");
+    if (k > 1) {
+      sel_e[1] = defined ? i1 : 1;
+      sel_g[1] = defined ? p1 * inv : __builtin_nanf("");
+    }
+  }
+}
+
 __device__ __forceinline__ void topk_from_logits(const float* __restrict__ lg, int E, int k, int renorm, int lane,
                                                  int* sel_e, float* sel_g, float* __restrict__ probs) {
   if (E <= 64) topk_small(lg, E, k, renorm, lane, sel_e, sel_g, probs);

@@ -20,10 +20,13 @@
 // the output rows 4 * (64 * (2w + q) + lane) + {0..3}, q = 0, 1, in phase 2, and keeps its outputs in registers.
 //
 // Memory. A wavefront reads blocks of eight 1 KB tiles (16 bytes per lane, consecutive lanes consecutive
-// addresses) plus the block's scales, two register sets in rotation, so 10 to 20 loads per lane are in flight
-// from the first block of phase 1 to the last of phase 2 (the list of blocks does not stop at the phase
-// boundary). In the stream layout a block is contiguous in memory with its scales right behind its tiles;
-// lane l always holds columns 64 l .. 64 l + 63, so its digit words stay in registers for the whole phase.
+// addresses) plus the block's scales, kNSets register sets in rotation over ONE list of blocks, so ten loads
+// per lane and set are in flight from the first block to the last. The list is ordered so that the memory side
+// never waits for the arithmetic of a phase: phase 1 of expert 0, then phase 1 of expert j interleaved with
+// phase 2 of expert j-1, then phase 2 of the last expert; the barrier pair in front of an expert's first
+// phase-2 block (h of that expert is staged between them) is passed with the other sets' loads in flight.
+// In the stream layout a block is contiguous in memory with its scales right behind its tiles; lane l always
+// holds columns 64 l .. 64 l + 63, so its digit words stay in registers.
 #include <hip/hip_ext.h>
 
 #include "decode_core.h"
@@ -37,6 +40,8 @@ constexpr int kSWaves = 8;
 constexpr int kSThreads = kSWaves * 64;
 constexpr int kSGroup = 128;     // scale group: the columns of two lanes
 constexpr int kSInlineMaxE = 64;
+constexpr int kNSets = 2;        // register sets in rotation
+constexpr int kMaxBlocks = 8 * 12; // blocks of a wavefront's list: 8 experts x (8 of phase 1 + 4 of phase 2) at most
 
 __device__ __forceinline__ int sdot8(uint32_t a, uint32_t b, int c) { return __builtin_amdgcn_sdot8((int)a, (int)b, c, false); }
 __device__ __forceinline__ int sdot4(uint32_t a, uint32_t b, int c) { return __builtin_amdgcn_sdot4((int)a, (int)b, c, false); }
@@ -81,9 +86,10 @@ struct StreamParams {
 struct BlkSet { uint4 t[8]; uint2 s[2]; };
 
 enum BlkKind { B_NONE = 0, B_P1 = 1, B_P2 = 2 };
-struct BlkTag { int kind, j, bits, mat, rb, q; };   // what a requested set holds
+struct BlkTag { int kind, j, bits, mat, rb, q, first; };   // what a requested set holds; first: the expert's first phase-2 block
 
-template <bool SWIGLU>
+// BM: the bitwidths the layer's experts have, or-ed (2 | 4 | 8): code and registers for the others are left out.
+template <bool SWIGLU, int BM>
 __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
   constexpr int NM = SWIGLU ? 2 : 1;
   __shared__ uint4 XD4[8][64];            // digits for 4-bit codes: [word j of the lane][lane] = digit words k = 0..3
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
   __shared__ uint4 XD8[8][64];            // for 8-bit codes: [2 * tile + half][lane] = (lo, hi) byte digits of words 2*half, 2*half+1
   __shared__ float XS[32];                // 2^e of every scale group of x (NaN: the group holds a non-finite value)
   __shared__ int SXL[64];                 // sum of x_int over a lane's 64 columns
-  __shared__ float rpart[kSInlineMaxE * 2];
+  __shared__ float rpart[kSWaves * kSInlineMaxE];   // router: every wavefront's part of every logit
   __shared__ float lgw[kSWaves][kSInlineMaxE];
   __shared__ int sel_ew[kSWaves][8];
   __shared__ float sel_gw[kSWaves][8];
@@ -119,36 +125,8 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
   const bool tab_in_lds = E <= kSInlineMaxE;
   if (tab_in_lds && tid < E * 4) ((uint4*)tab)[tid] = ((const uint4*)P.table)[tid];
   const DevExpert* tabp = tab_in_lds ? tab : P.table;
-  // ---- router partial sums (work unit = expert x half of the columns), loads issued behind the activations'
-  if (inline_router) {
-    for (int u = wave; u < E * 2; u += kSWaves) {
-      const int e = u >> 1, seg = u & 1;
-      const float* wr = P.Wr + (size_t)e * kSD + seg * 2048;
-      float4 w[8], v[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int i = q * 256 + lane * 4;
-        w[q] = *(const float4*)(wr + i);
-        if (bf16) {
-          const uint2 b = *(const uint2*)((const uint16_t*)xt + seg * 2048 + i);
-          v[q] = make_float4(bf16_bits_to_f32(b.x & 0xffffu), bf16_bits_to_f32(b.x >> 16),
-                             bf16_bits_to_f32(b.y & 0xffffu), bf16_bits_to_f32(b.y >> 16));
-        } else {
-          v[q] = *(const float4*)((const float*)xt + seg * 2048 + i);
-        }
-      }
-      float acc = 0.f;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        acc = fmaf(w[q].x, v[q].x, acc); acc = fmaf(w[q].y, v[q].y, acc);
-        acc = fmaf(w[q].z, v[q].z, acc); acc = fmaf(w[q].w, v[q].w, acc);
-      }
-      acc = wave_sum(acc);
-      if (lane == 0) rpart[u] = acc;
-    }
-  }
-  // ---- digits of the activations, for every bitwidth, straight from the registers
-  {
+  // ---- digits of the activations, for every bitwidth the layer has, straight from the registers
+  auto stage_digits = [&]() __attribute__((always_inline)) {
     float m = 0.f;
     bool bad = false;
 #pragma unroll
@@ -177,7 +155,7 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
     sum += __shfl_xor(sum, 4);
     if ((tid & 7) == 0) SXL[tid >> 3] = sum;
     // 8-bit codes: two signed byte digits, x_int = lo + 256 * hi; a word of four codes meets (lo word, hi word)
-    {
+    if constexpr ((BM & 8) != 0) {
       uint32_t lo[2] = {0u, 0u}, hi[2] = {0u, 0u};
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -204,7 +182,7 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
         else he[kk] |= n << (4 * (i >> 1));
       }
     }
-    XD4[tid & 7][tid >> 3] = make_uint4(d4[0], d4[1], d4[2], d4[3]);
+    if constexpr ((BM & 4) != 0) XD4[tid & 7][tid >> 3] = make_uint4(d4[0], d4[1], d4[2], d4[3]);
     // a word of 2-bit codes covers 16 columns = this thread and its neighbour (tid ^ 1)
     uint32_t full[4];
     const bool upper = (tid & 1) != 0;
@@ -216,9 +194,37 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
       const uint32_t got = (uint32_t)dppi<kDppXor1>((int)give);   // neighbour's half of MY word
       full[kk] = upper ? (got | (mine << 16)) : (mine | (got << 16));
     }
-    XD2[2 * ((tid & 7) >> 1) + (tid & 1)][tid >> 3] = make_uint4(full[0], full[1], full[2], full[3]);
+    if constexpr ((BM & 2) != 0) XD2[2 * ((tid & 7) >> 1) + (tid & 1)][tid >> 3] = make_uint4(full[0], full[1], full[2], full[3]);
+  };
+  // ---- router: thread t dots ITS 8 columns (already in registers) with the same columns of every expert's
+  // router row, eight experts at a time: all loads of a pass are requested at once, right behind the
+  // activations', and the digits of the activations are made while they are in flight. Wavefront sums go to
+  // rpart[wave][e]; the logits are the sums of the eight wavefronts' parts, in order.
+  bool staged = false;
+  if (inline_router) {
+    for (int e0 = 0; e0 < E; e0 += 8) {
+      float4 w[8][2];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float* wr = P.Wr + (size_t)min(e0 + i, E - 1) * kSD + 8 * tid;     // rows past E repeat the last one
+        w[i][0] = *(const float4*)wr;
+        w[i][1] = *(const float4*)(wr + 4);
+      }
+      if (!staged) { stage_digits(); staged = true; }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float acc = w[i][0].x * xit.v[0];
+        acc = fmaf(w[i][0].y, xit.v[1], acc); acc = fmaf(w[i][0].z, xit.v[2], acc); acc = fmaf(w[i][0].w, xit.v[3], acc);
+        acc = fmaf(w[i][1].x, xit.v[4], acc); acc = fmaf(w[i][1].y, xit.v[5], acc);
+        acc = fmaf(w[i][1].z, xit.v[6], acc); acc = fmaf(w[i][1].w, xit.v[7], acc);
+        acc = wave_sum(acc);
+        if (lane == 0 && e0 + i < E) rpart[wave * kSInlineMaxE + e0 + i] = acc;
+      }
+    }
   }
+  if (!staged) stage_digits();
   __syncthreads();   // digits, XS, SXL, rpart, tab are complete
+
 
   // ---- routing, by every wavefront for itself (identical arithmetic, identical result): no second barrier
   int* sel_e = sel_ew[wave];
@@ -231,8 +237,15 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
   } else if (routed) {
     if (inline_router) {
       float* lg = lgw[wave];
-      if (lane < E) lg[lane] = rpart[2 * lane] + rpart[2 * lane + 1] + (P.bias ? P.bias[lane] : 0.f);
-      topk_from_logits(lg, E, k, L.renorm, lane, sel_e, sel_g, nullptr);
+      if (lane < E) {
+        float t = rpart[lane];
+#pragma unroll
+        for (int wv = 1; wv < kSWaves; ++wv) t += rpart[wv * kSInlineMaxE + lane];
+        lg[lane] = t + (P.bias ? P.bias[lane] : 0.f);
+      }
+      if (E <= 8 && k <= 2) topk_tiny<8>(lg, E, k, L.renorm, lane, sel_e, sel_g);
+      else if (E <= 16 && k <= 2) topk_tiny<16>(lg, E, k, L.renorm, lane, sel_e, sel_g);
+      else topk_from_logits(lg, E, k, L.renorm, lane, sel_e, sel_g, nullptr);
     } else {
       topk_from_logits(P.logits + (size_t)token * E, E, k, L.renorm, lane, sel_e, sel_g, nullptr);
     }
@@ -246,58 +259,78 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
     if (P.gate_out) P.gate_out[(size_t)token * k + lane] = sel_g[lane];
   }
 
-  // ---- the list of blocks of this wavefront: phase 1 (expert j: row blocks rb, matrices), then phase 2
-  struct Walk {
-    int phase, j, rb, mat, q;     // position
-    int bits, rbsh;               // of expert j: bitwidth, log2 of the rows of a phase-1 block
-    const uint8_t* q_in; const uint8_t* q_gate; const uint8_t* q_out; const uint8_t* s_out;
-  } wi;
-  auto enter = [&](Walk& w, int j) __attribute__((always_inline)) {
-    w.j = j;
-    if (j < k) {
-      const DevExpert* ex = tabp + sel_e[j];
-      w.bits = __builtin_amdgcn_readfirstlane(ex->bits);
-      w.rbsh = w.bits == 2 ? 3 : (w.bits == 4 ? 2 : 1);
-      w.q_in = uniform_ptr(ex->q_in);
-      w.q_gate = SWIGLU ? uniform_ptr(ex->q_gate) : w.q_in;
-      w.q_out = uniform_ptr(ex->q_out);
-      w.s_out = (const uint8_t*)uniform_ptr(ex->s_out);
+  // ---- the list of blocks of a wavefront (the same for every wavefront): lane g computes entries g and g + 64
+  // and keeps them in two registers, read with v_readlane when a block is requested. Entry: kind | first << 2 |
+  // j << 3 | bits << 6 | index << 10, index = rb * NM + mat in phase 1, q in phase 2. Segment j (0 .. k) holds
+  // phase 1 of expert j interleaved with phase 2 of expert j - 1, alternating while both have blocks left.
+  const DevExpert* tabq = tabp;
+  int n_total = 0, bm = 0;
+  int ent_lo = 0, ent_hi = 0;
+  {
+    int start = 0, b2 = 0;                                      // b2: bits of expert j - 1
+    for (int j = 0; j <= k; ++j) {
+      {
+        const int b1 = j < k ? __builtin_amdgcn_readfirstlane(tabq[sel_e[j]].bits) : 0;   // bits of expert j
+        bm |= b1;
+        const int n1 = (b1 >> 1) * NM, n2 = b2 == 0 ? 0 : (b2 == 2 ? 1 : (b2 == 4 ? 2 : 4));
+        const int m = min(n1, n2);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int i = lane + 64 * half - start;
+          if (i >= 0 && i < n1 + n2) {
+            int kind, idx;
+            if (i < 2 * m) { kind = (i & 1) ? B_P2 : B_P1; idx = i >> 1; }
+            else { kind = n1 > n2 ? B_P1 : B_P2; idx = m + (i - 2 * m); }
+            const int ent = kind == B_P1 ? (B_P1 | (j << 3) | (b1 << 6) | (idx << 10))
+                                         : (B_P2 | ((idx == 0 ? 1 : 0) << 2) | ((j - 1) << 3) | (b2 << 6) | (idx << 10));
+            if (half == 0) ent_lo = ent; else ent_hi = ent;
+          }
+        }
+        start += n1 + n2;
+        b2 = b1;
+      }
     }
-  };
-  wi.phase = 1; wi.rb = 0; wi.mat = 0; wi.q = 0;
-  enter(wi, 0);
+    n_total = start;
+  }
   const uint8_t* idle = (const uint8_t*)xt;       // at least 8 KB of readable, cached bytes
-  const uint32_t lane16 = (uint32_t)lane * 16u;
-  auto issue = [&](BlkSet& S, BlkTag& tag) __attribute__((always_inline)) {
-    const bool valid = wi.j < k;
-    tag.kind = valid ? wi.phase : B_NONE;
-    tag.j = wi.j; tag.bits = wi.bits; tag.mat = wi.mat; tag.rb = wi.rb; tag.q = wi.q;
+  // Requests block g of the list into S and notes in tag what it is.
+  auto issue = [&](BlkSet& S, BlkTag& tag, int g) __attribute__((always_inline)) {
+    const int ent = g >= n_total ? 0 : (g < 64 ? __builtin_amdgcn_readlane(ent_lo, g) : __builtin_amdgcn_readlane(ent_hi, g - 64));
+    tag.kind = ent & 3; tag.first = (ent >> 2) & 1; tag.j = (ent >> 3) & 7; tag.bits = (ent >> 6) & 15;
+    const int index = ent >> 10;
+    tag.mat = 0; tag.rb = 0; tag.q = index;
     const uint8_t* base = idle;
     uint32_t tstride = 0u, qstride = 0u, lane_t = (uint32_t)lane * 16u, soff0 = 0u, soff1 = 0u;
     const uint8_t* sbase = idle;
     int qshift = 3;                                  // tiles i >> qshift select the second row quad
-    if (valid && wi.phase == 1) {
-      const uint32_t RB = 1u << wi.rbsh, BB = 8192u + 64u * RB;
-      const uint32_t blk = (((uint32_t)slice * 64u + (uint32_t)wave * 8u) >> wi.rbsh) + (uint32_t)wi.rb;
-      base = (wi.mat ? wi.q_gate : wi.q_in) + (size_t)blk * BB;
-      tstride = 1024u;
-      sbase = base + 8192u;
-      // the aligned 8 bytes that hold the lane's RB bytes of scales (always inside the block's scale area)
-      soff0 = soff1 = ((uint32_t)lane * RB) & ~7u;
-    } else if (valid) {
-      // phase 2: tile i = word column (first + i % wpb) of row quad (q0 + i / wpb)
-      const uint32_t DW = 2u * (uint32_t)wi.bits;                           // word columns of the slice
-      const uint32_t wpb = wi.bits == 2 ? 4u : 8u;                          // word columns per block
-      const uint32_t first = wi.bits == 8 ? (uint32_t)(wi.q & 1) * 8u : 0u; // 8-bit: two blocks per row quad
-      const uint32_t q0 = wi.bits == 2 ? 0u : (wi.bits == 4 ? (uint32_t)wi.q : (uint32_t)(wi.q >> 1));
-      qshift = wi.bits == 2 ? 2 : 3;
-      base = wi.q_out + ((size_t)slice * DW + first) * ((size_t)kSD * 4);
-      tstride = (uint32_t)kSD * 4u;
-      qstride = 1024u - wpb * tstride;                                       // from the last word of quad 0 to quad 1
-      lane_t = (uint32_t)(64 * (2 * wave + (int)q0) + lane) * 16u;
-      sbase = wi.s_out + (size_t)(slice >> 1) * ((size_t)kSD * 2);
-      soff0 = (uint32_t)(64 * (2 * wave + (int)q0) + lane) * 8u;
-      soff1 = wi.bits == 2 ? soff0 + 512u : soff0;
+    if (tag.kind != B_NONE) {
+      const DevExpert* ex = tabq + sel_e[tag.j];
+      if (tag.kind == B_P1) {
+        tag.mat = SWIGLU ? (index & 1) : 0;
+        tag.rb = SWIGLU ? (index >> 1) : index;
+        const int rbsh = tag.bits == 2 ? 3 : (tag.bits == 4 ? 2 : 1);
+        const uint32_t RB = 1u << rbsh, BB = 8192u + 64u * RB;
+        const uint32_t blk = (((uint32_t)slice * 64u + (uint32_t)wave * 8u) >> rbsh) + (uint32_t)tag.rb;
+        base = uniform_ptr(tag.mat ? ex->q_gate : ex->q_in) + (size_t)blk * BB;
+        tstride = 1024u;
+        sbase = base + 8192u;
+        // the aligned 8 bytes that hold the lane's RB bytes of scales (always inside the block's scale area)
+        soff0 = soff1 = ((uint32_t)lane * RB) & ~7u;
+      } else {
+        // phase 2: tile i = word column (first + i % wpb) of row quad (q0 + i / wpb)
+        const uint32_t DW = 2u * (uint32_t)tag.bits;                           // word columns of the slice
+        const uint32_t wpb = tag.bits == 2 ? 4u : 8u;                          // word columns per block
+        const uint32_t first = tag.bits == 8 ? (uint32_t)(tag.q & 1) * 8u : 0u; // 8-bit: two blocks per row quad
+        const uint32_t q0 = tag.bits == 2 ? 0u : (tag.bits == 4 ? (uint32_t)tag.q : (uint32_t)(tag.q >> 1));
+        qshift = tag.bits == 2 ? 2 : 3;
+        base = uniform_ptr(ex->q_out) + ((size_t)slice * DW + first) * ((size_t)kSD * 4);
+        tstride = (uint32_t)kSD * 4u;
+        qstride = 1024u - wpb * tstride;                                       // from the last word of quad 0 to quad 1
+        lane_t = (uint32_t)(64 * (2 * wave + (int)q0) + lane) * 16u;
+        sbase = (const uint8_t*)uniform_ptr(ex->s_out) + (size_t)(slice >> 1) * ((size_t)kSD * 2);
+        soff0 = (uint32_t)(64 * (2 * wave + (int)q0) + lane) * 8u;
+        soff1 = tag.bits == 2 ? soff0 + 512u : soff0;
+      }
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -306,39 +339,25 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
     }
     S.s[0] = gload_u32x2(sbase + soff0);
     S.s[1] = gload_u32x2(sbase + soff1);
-    // advance
-    if (valid) {
-      if (wi.phase == 1) {
-        if (++wi.mat == NM) {
-          wi.mat = 0;
-          if (++wi.rb == wi.bits / 2) {          // 8 rows = bits/2 blocks
-            wi.rb = 0;
-            enter(wi, wi.j + 1);
-            if (wi.j == k) { wi.phase = 2; enter(wi, 0); }
-          }
-        }
-      } else {
-        const int nq = wi.bits == 2 ? 1 : (wi.bits == 4 ? 2 : 4);
-        if (++wi.q == nq) { wi.q = 0; enter(wi, wi.j + 1); }
-      }
-    }
   };
 
-  // ---- per-lane constants of phase 1
-  uint32_t xd4[8][4], xd2[8][4], xd8[8][4];
-  const float xs = XS[lane >> 1];
-  const int sxl = SXL[lane];
+  // ---- per-lane constants of phase 1 (read after the digits are staged)
+  uint32_t xd4[(BM & 4) ? 8 : 1][4], xd2[(BM & 2) ? 8 : 1][4], xd8[(BM & 8) ? 8 : 1][4];
+  float xs = 0.f;
+  int sxl = 0;
   // the digit words of the lane's columns, for the bitwidths the chosen experts have (bm: their bitwidths or-ed)
   auto load_digits = [&](int bm_) __attribute__((always_inline)) {
-    if (bm_ & 4) {
+    xs = XS[lane >> 1];
+    sxl = SXL[lane];
+    if constexpr ((BM & 4) != 0) if (bm_ & 4) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) { const uint4 v = XD4[j][lane]; xd4[j][0] = v.x; xd4[j][1] = v.y; xd4[j][2] = v.z; xd4[j][3] = v.w; }
     }
-    if (bm_ & 2) {
+    if constexpr ((BM & 2) != 0) if (bm_ & 2) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) { const uint4 v = XD2[j][lane]; xd2[j][0] = v.x; xd2[j][1] = v.y; xd2[j][2] = v.z; xd2[j][3] = v.w; }
     }
-    if (bm_ & 8) {
+    if constexpr ((BM & 8) != 0) if (bm_ & 8) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) { const uint4 v = XD8[j][lane]; xd8[j][0] = v.x; xd8[j][1] = v.y; xd8[j][2] = v.z; xd8[j][3] = v.w; }
     }
@@ -358,8 +377,8 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
   // odd lane the others. s: the lane's RB/2 scales (binary16) in s.x / s.y.
   auto consume_p1 = [&](const BlkSet& S, const BlkTag& tag) __attribute__((always_inline)) {
     float f[4] = {0.f, 0.f, 0.f, 0.f};
-    int nrow;                                         // rows this lane finishes
-    if (tag.bits == 4) {
+    int nrow = 0;                                     // rows this lane finishes
+    if ((BM & 4) && tag.bits == 4) {
       int pv[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -382,7 +401,7 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
       const uint32_t s2 = odd ? S.s[0].y : S.s[0].x;      // the lane's 4 bytes of the aligned 8
       f[0] = (float)(odd ? pv[2] : pv[0]) * (f16_bits_to_f32(s2 & 0xffffu) * xs);
       f[1] = (float)(odd ? pv[3] : pv[1]) * (f16_bits_to_f32(s2 >> 16) * xs);
-    } else if (tag.bits == 2) {
+    } else if ((BM & 2) && tag.bits == 2) {
       int pv[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
@@ -406,7 +425,7 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
       f[1] = (float)(odd ? pv[5] : pv[1]) * (f16_bits_to_f32(S.s[0].x >> 16) * xs);
       f[2] = (float)(odd ? pv[6] : pv[2]) * (f16_bits_to_f32(S.s[0].y & 0xffffu) * xs);
       f[3] = (float)(odd ? pv[7] : pv[3]) * (f16_bits_to_f32(S.s[0].y >> 16) * xs);
-    } else {
+    } else if ((BM & 8) && tag.bits == 8) {
       int pv[2];
 #pragma unroll
       for (int r = 0; r < 2; ++r) {
@@ -448,11 +467,11 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
 
   // ---- phase 2 state: the lane's 8 output rows
   float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  int acc8[4][2];                  // 8-bit experts: a row quad's sums run over two blocks
+  int acc8[4][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}};   // 8-bit experts: a row quad's sums run over two blocks
   auto consume_p2 = [&](const BlkSet& S, const BlkTag& tag) __attribute__((always_inline)) {
     const float gu = sel_g[tag.j] * uph[tag.j];
     const uint4* hd = HD[tag.j];
-    if (tag.bits == 4) {
+    if ((BM & 4) && tag.bits == 4) {
       int a[4][4];
 #pragma unroll
       for (int r = 0; r < 4; ++r)
@@ -475,9 +494,11 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
       for (int r = 0; r < 4; ++r) {
         const int v = a[r][0] + (a[r][1] << 4) + (a[r][2] << 8) + (a[r][3] << 12);
         const float c = (float)v * (f16_bits_to_f32(sc[r]) * gu);
-        if (tag.q == 0) y[r] += c; else y[4 + r] += c;
+        // both candidates with static indices (a run-time index would move y out of the registers)
+        y[r] += tag.q == 0 ? c : 0.f;
+        y[4 + r] += tag.q == 0 ? 0.f : c;
       }
-    } else if (tag.bits == 2) {
+    } else if ((BM & 2) && tag.bits == 2) {
       const int sh2 = 2 * SH[tag.j];
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
@@ -510,7 +531,7 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
           y[4 * q + r] += (float)v * (f16_bits_to_f32(sc[r]) * gu);
         }
       }
-    } else {
+    } else if ((BM & 8) && tag.bits == 8) {
       // 8-bit: word columns 8 * (q & 1) .. + 7 of row quad q >> 1; the digits of h: word i -> HD[j][i / 2], (lo, hi) pairs
       const int half = tag.q & 1;
       if (half == 0) {
@@ -535,15 +556,16 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
         for (int r = 0; r < 4; ++r) {
           const int v = acc8[r][0] + (acc8[r][1] << 8);
           const float c = (float)v * (f16_bits_to_f32(sc[r]) * gu);
-          if ((tag.q >> 1) == 0) y[r] += c; else y[4 + r] += c;
+          y[r] += (tag.q >> 1) == 0 ? c : 0.f;
+          y[4 + r] += (tag.q >> 1) == 0 ? 0.f : c;
         }
       }
     }
   };
 
-  // ---- between the phases: digits of every expert's h slice (one wavefront per expert)
-  auto stage_h = [&]() __attribute__((always_inline)) {
-    for (int j = wave; j < k; j += kSWaves) {
+  // ---- between the phases of expert j: digits of its h slice (one wavefront)
+  auto stage_h = [&](int j) __attribute__((always_inline)) {
+    if (wave == (j & (kSWaves - 1))) {
       const int bits = __builtin_amdgcn_readfirstlane(tabp[sel_e[j]].bits);
       const float hv = HF[j][lane];
       float m = !(fabsf(hv) < INFINITY) ? INFINITY : fabsf(hv);
@@ -590,38 +612,30 @@ __global__ __launch_bounds__(kSThreads) void k_moe_stream(StreamParams P) {
     }
   };
 
-  // ---- the stream: two register sets in rotation over the whole list, one barrier pair at the phase boundary
-  int n_p1 = 0, n_all = 0, bm = 0;
-  for (int j = 0; j < k; ++j) {
-    const int b = __builtin_amdgcn_readfirstlane(tabp[sel_e[j]].bits);
-    bm |= b;
-    n_p1 += (b / 2) * NM;
-    n_all += (b / 2) * NM + (b == 2 ? 1 : (b == 4 ? 2 : 4));
-  }
-  BlkSet A, B;
-  BlkTag ta, tb;
-  issue(A, ta);
-  issue(B, tb);
+  // ---- the stream: kNSets register sets in rotation over the list
+  BlkSet S[kNSets];
+  BlkTag tg[kNSets];
+#pragma unroll
+  for (int i = 0; i < kNSets; ++i) issue(S[i], tg[i], i);
   load_digits(bm);     // behind the first requests
-  bool h_staged = false;
-  auto consume = [&](const BlkSet& S, const BlkTag& tag) __attribute__((always_inline)) {
+  auto consume = [&](const BlkSet& St, const BlkTag& tag) __attribute__((always_inline)) {
     if (tag.kind == B_P1) {
-      consume_p1(S, tag);
+      consume_p1(St, tag);
     } else if (tag.kind == B_P2) {
-      if (!h_staged) {          // uniform over the workgroup: every wavefront has the same list
-        __syncthreads();        // the h slices are complete (fp32)
-        stage_h();
+      if (tag.first) {          // uniform over the workgroup: every wavefront walks the same list
+        __syncthreads();        // the h slice of expert tag.j is complete (fp32)
+        stage_h(tag.j);
         __syncthreads();
-        h_staged = true;
       }
-      consume_p2(S, tag);
+      consume_p2(St, tag);
     }
   };
-  for (int b = 0; b < n_all; b += 2) {
-    consume(A, ta);
-    issue(A, ta);
-    consume(B, tb);
-    issue(B, tb);
+  for (int g = 0; g < n_total; g += kNSets) {
+#pragma unroll
+    for (int i = 0; i < kNSets; ++i) {
+      consume(S[i], tg[i]);
+      issue(S[i], tg[i], g + kNSets + i);
+    }
   }
   // ---- the partial output vector, straight from the registers
   float* out = P.part + ((size_t)token * gridDim.x + slice) * kSD;
@@ -671,14 +685,24 @@ int stream_slices(const LayerDims& L) { return L.d_ff / kSSlice; }
 
 hipError_t launch_moe_stream(const LayerDims& L, const DevExpert* table, const float* router_w, const float* router_bias,
                              const float* logits, int32_t fixed_expert, const float* gate_in, const int32_t* route_idx,
-                             const float* route_gate, const void* x, int32_t T, float* part, int32_t* idx_out,
-                             float* gate_out, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  if (!stream_supported(L) || T < 1 || T > 65535) return hipErrorInvalidValue;
+                             const float* route_gate, int32_t bits_mask, const void* x, int32_t T, float* part,
+                             int32_t* idx_out, float* gate_out, hipStream_t st, hipEvent_t ev_start,
+                             hipEvent_t ev_stop) {
+  if (!stream_supported(L) || T < 1 || T > 65535 || !(bits_mask & 14)) return hipErrorInvalidValue;
   if (!logits && !route_idx && fixed_expert < 0 && L.n_experts > kSInlineMaxE) return hipErrorInvalidValue;
   if ((route_idx != nullptr) != (route_gate != nullptr)) return hipErrorInvalidValue;
   StreamParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, route_idx, route_gate, x, part,
                  idx_out, gate_out};
-  auto kernel = L.act == MOEQ_ACT_SWIGLU ? k_moe_stream<true> : k_moe_stream<false>;
+  // the variant for the bitwidths the layer holds (2 | 4 | 8 or-ed); the mixes without their own variant take the full one
+  const bool sw = L.act == MOEQ_ACT_SWIGLU;
+  void (*kernel)(StreamParams) = nullptr;
+  switch (bits_mask & 14) {
+    case 2: kernel = sw ? k_moe_stream<true, 2> : k_moe_stream<false, 2>; break;
+    case 4: kernel = sw ? k_moe_stream<true, 4> : k_moe_stream<false, 4>; break;
+    case 6: kernel = sw ? k_moe_stream<true, 6> : k_moe_stream<false, 6>; break;
+    case 8: kernel = sw ? k_moe_stream<true, 8> : k_moe_stream<false, 8>; break;
+    default: kernel = sw ? k_moe_stream<true, 14> : k_moe_stream<false, 14>; break;
+  }
   const dim3 grid(stream_slices(L), T), block(kSThreads);
   if (ev_start && ev_stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev_start, ev_stop, 0, P);
   else hipLaunchKernelGGL(kernel, grid, block, 0, st, P);

@@ -85,9 +85,10 @@ int stream_inline_router_max();
 int stream_slices(const LayerDims& L);
 hipError_t launch_moe_stream(const LayerDims& L, const DevExpert* table, const float* router_w,
                              const float* router_bias, const float* logits, int32_t fixed_expert,
-                             const float* gate_in, const int32_t* route_idx, const float* route_gate, const void* x,
-                             int32_t T, float* part, int32_t* idx_out, float* gate_out, hipStream_t st,
-                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+                             const float* gate_in, const int32_t* route_idx, const float* route_gate,
+                             int32_t bits_mask, const void* x, int32_t T, float* part, int32_t* idx_out,
+                             float* gate_out, hipStream_t st, hipEvent_t ev_start = nullptr,
+                             hipEvent_t ev_stop = nullptr);
 // canonical (q, s) <-> stream buffer of a [rows][4096] matrix, groups of 128 columns
 hipError_t launch_relayout_in(const void* q, const void* s, int64_t rows, int bits, void* stream_buf, bool to_stream,
                               hipStream_t st);
