@@ -110,19 +110,28 @@ typedef struct moeq_layer_desc {
   int32_t in_layout;        /* moeq_in_layout of every expert's W_in / W_gate. MOEQ_IN_STREAM: q_in and
                                q_gate point to stream buffers (moe_prepare_in), s_in / s_gate are not
                                read (may be NULL); needs out_layout = MOEQ_OUT_COLUMNS                */
+  int32_t group_in;         /* scale group of W_in / W_gate along d_model; 0: `group`                  */
+  int32_t group_out;        /* scale group of W_out along d_ff; 0: `group`. group_in = d_model with
+                               group_out = d_ff is Section 3.2's scheme: one float16 scale per channel
+                               of each matrix                                                          */
 } moeq_layer_desc;
 
 typedef struct moeq_layer moeq_layer; /* opaque, host-side handle */
 
 /* ---- set-up (not on the hot path) -------------------------------------------------------- */
 
-/* Bytes of device memory the expert table of a layer with n_experts experts needs. */
+/* Bytes of device memory the expert table of a layer with n_experts experts needs (one record per expert:
+ * its bitwidth - the per-expert bitwidth table of Section 3.2 - and the addresses of its packed matrices). */
 size_t moe_layer_table_bytes(int32_t n_experts);
 
 /* Validates `desc`, copies the expert table into `table_dev` (synchronous copy) and returns a
  * handle. `table_dev` (dev, >= moe_layer_table_bytes(n_experts), 16-byte aligned) and every
- * pointer in `desc` must stay valid until moe_layer_destroy. Limits: d_model, d_ff multiples of
- * `group`; group a multiple of 32 (a multiple of 64 or exactly 32 for 2-bit experts);
+ * pointer in `desc` must stay valid until moe_layer_destroy. All per-device set-up happens here (the kernels'
+ * shared-memory ceilings, the scratch lookup of moe_layer_forward_static), with the device current on which
+ * the layer will run: every compute call on the layer, the first one included, only enqueues kernels and may
+ * be recorded into a HIP graph. Limits: d_model a multiple of the scale group of W_in / W_gate, d_ff of the
+ * scale group of W_out (`group` for both unless group_in / group_out say otherwise); each group a multiple of
+ * 32 (a multiple of 64 or exactly 32 for 2-bit experts);
  * d_model*bits and d_ff*bits multiples of 128 for every expert; 1 <= top_k <= min(8, n_experts);
  * n_experts <= 1024; d_model, d_ff <= 32768. With out_layout = MOEQ_OUT_COLUMNS also: group and d_ff
  * multiples of 16, d_model <= 8192 (else MOEQ_EUNSUPPORTED). With in_layout = MOEQ_IN_STREAM also: out_layout =
@@ -133,7 +142,9 @@ moeq_status moe_layer_create(const moeq_layer_desc *desc, void *table_dev, size_
                              moeq_layer **out);
 void moe_layer_destroy(moeq_layer *layer);
 
-/* Workspace bytes needed by any compute call on `layer` with up to max_tokens tokens. */
+/* Workspace bytes needed by any compute call on `layer` with up to max_tokens tokens (the routing, the router
+ * logits, and what the path of Section 2.1 needs between its kernels: h, or the partial output vectors, or
+ * the grouped path's staging). Host-only arithmetic. */
 size_t moe_workspace_bytes(const moeq_layer *layer, int32_t max_tokens);
 
 /* Which kernels moe_layer_forward / moe_layer_forward_routed run for a call with n_tokens tokens on
@@ -171,7 +182,8 @@ moeq_status moe_expert_ffn_q(const moeq_layer *layer, int32_t expert, const void
                              int32_t n_tokens, const float *gate_opt, int32_t accumulate,
                              float *y, void *ws, size_t ws_bytes, void *stream);
 
-/* The whole layer: router, top-k, the chosen experts' FFNs, gate-weighted combine:
+/* The whole layer (Section 1; Section 2.1, the sparse MoE layer; Section 3.2 for the experts' weights): router,
+ * top-k, the chosen experts' FFNs on their decompressed weights, gate-weighted combine:
  * y[t] = sum_j gate[t][j] * FFN_{idx[t][j]}(x[t]). topk_idx_opt / topk_gate_opt (dev, may be NULL)
  * receive the routing decision. */
 moeq_status moe_layer_forward(const moeq_layer *layer, const void *x, int32_t n_tokens, float *y,

@@ -37,7 +37,8 @@ class moeq_layer_desc(C.Structure):
                 ("top_k", C.c_int32), ("group", C.c_int32), ("act", C.c_int32),
                 ("renorm", C.c_int32), ("x_dtype", C.c_int32),
                 ("router_w", C.c_void_p), ("router_bias", C.c_void_p),
-                ("experts", C.POINTER(moeq_expert)), ("out_layout", C.c_int32), ("in_layout", C.c_int32)]
+                ("experts", C.POINTER(moeq_expert)), ("out_layout", C.c_int32), ("in_layout", C.c_int32),
+                ("group_in", C.c_int32), ("group_out", C.c_int32)]
 
 
 _lib = None
@@ -254,9 +255,10 @@ class Layer:
     """Owner of a moeq_layer handle and of the device tensors it borrows."""
 
     def __init__(self, d_model, d_ff, top_k, group, act, renorm, x_dtype, router_w, router_bias, experts,
-                 out_layout=MOEQ_OUT_CANONICAL, in_layout=MOEQ_IN_CANONICAL):
+                 out_layout=MOEQ_OUT_CANONICAL, in_layout=MOEQ_IN_CANONICAL, group_in=0, group_out=0):
         self.out_layout = out_layout
         self.in_layout = in_layout
+        self.group_in, self.group_out = group_in or group, group_out or group
         self.d_model, self.d_ff, self.top_k, self.group = d_model, d_ff, top_k, group
         self.n_experts = len(experts)
         self.experts = list(experts)
@@ -266,7 +268,7 @@ class Layer:
         self._table = torch.empty(max(moe_layer_table_bytes(self.n_experts), 16), dtype=torch.uint8, device=dev)
         arr = (moeq_expert * self.n_experts)(*[e.c_struct() for e in self.experts])
         desc = moeq_layer_desc(d_model, d_ff, self.n_experts, top_k, group, act, int(bool(renorm)), x_dtype,
-                               _ptr(router_w), _ptr(router_bias), arr, out_layout, in_layout)
+                               _ptr(router_w), _ptr(router_bias), arr, out_layout, in_layout, group_in, group_out)
         h = C.c_void_p()
         _check(lib().moe_layer_create(C.byref(desc), _ptr(self._table), self._table.numel(), C.byref(h)),
                "moe_layer_create")

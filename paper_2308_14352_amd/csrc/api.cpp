@@ -159,8 +159,12 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
                              moeq_layer** out) {
   if (out) *out = nullptr;
   if (!desc || !out || !table_dev || !desc->experts || !desc->router_w) return MOEQ_EINVAL;
-  const int32_t d = desc->d_model, f = desc->d_ff, E = desc->n_experts, k = desc->top_k, g = desc->group;
-  if (d <= 0 || f <= 0 || E <= 0 || k <= 0 || g <= 0) return MOEQ_EINVAL;
+  const int32_t d = desc->d_model, f = desc->d_ff, E = desc->n_experts, k = desc->top_k;
+  // group_in / group_out, each falling back to the shorthand `group`
+  const int32_t g = desc->group_in > 0 ? desc->group_in : desc->group;
+  const int32_t go = desc->group_out > 0 ? desc->group_out : desc->group;
+  if (desc->group_in < 0 || desc->group_out < 0) return MOEQ_EINVAL;
+  if (d <= 0 || f <= 0 || E <= 0 || k <= 0 || g <= 0 || go <= 0) return MOEQ_EINVAL;
   if (k > E) return MOEQ_EINVAL;
   if (desc->act != MOEQ_ACT_RELU && desc->act != MOEQ_ACT_SWIGLU) return MOEQ_EINVAL;
   if (desc->x_dtype != MOEQ_F32 && desc->x_dtype != MOEQ_BF16) return MOEQ_EINVAL;
@@ -168,10 +172,10 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   if (desc->in_layout != MOEQ_IN_CANONICAL && desc->in_layout != MOEQ_IN_STREAM) return MOEQ_EINVAL;
   const bool stream = desc->in_layout == MOEQ_IN_STREAM;
   if (stream && desc->out_layout != MOEQ_OUT_COLUMNS) return MOEQ_EINVAL;
-  if (d % g || f % g) return MOEQ_EINVAL;
+  if (d % g || f % go) return MOEQ_EINVAL;
   if (((uintptr_t)table_dev & 15u) || table_bytes < moe_layer_table_bytes(E)) return MOEQ_EINVAL;
   if (k > 8 || E > 1024 || d > 32768 || f > 32768 || d % 8 || f % 8) return MOEQ_EUNSUPPORTED;
-  const LayerDims dims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0};
+  const LayerDims dims{d, f, E, k, g, desc->act, desc->renorm ? 1 : 0, desc->x_dtype == MOEQ_BF16 ? 1 : 0, go};
   FusedPlan plan{0, 0, 0, 0};
   if (stream) {
     if (!stream_supported(dims)) return MOEQ_EUNSUPPORTED;
@@ -189,7 +193,7 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
     if (!x.q_in || (!stream && !x.s_in) || !x.q_out || !x.s_out) return MOEQ_EINVAL;
     if (desc->act == MOEQ_ACT_SWIGLU && (!x.q_gate || (!stream && !x.s_gate))) return MOEQ_EINVAL;
     if (((int64_t)d * x.bits) % 128 || ((int64_t)f * x.bits) % 128) return MOEQ_EINVAL;
-    if (!group_ok(g, x.bits)) return MOEQ_EUNSUPPORTED;
+    if (!group_ok(g, x.bits) || !group_ok(go, x.bits)) return MOEQ_EUNSUPPORTED;
     const uintptr_t align_or = (uintptr_t)x.q_in | (uintptr_t)x.q_out | (uintptr_t)x.q_gate;
     if (align_or & 15u) return MOEQ_EINVAL;  // 16-byte loads on the code rows
     if (((uintptr_t)x.s_in | (uintptr_t)x.s_out | (uintptr_t)x.s_gate) & 1u) return MOEQ_EINVAL;
@@ -213,7 +217,10 @@ moeq_status moe_layer_create(const moeq_layer_desc* desc, void* table_dev, size_
   L->out_layout = desc->out_layout;
   L->in_layout = desc->in_layout;
   L->plan = plan;
-  if (hipMemcpy(table_dev, tab.data(), tab.size() * sizeof(DevExpert), hipMemcpyHostToDevice) != hipSuccess) {
+  if (hipMemcpy(table_dev, tab.data(), tab.size() * sizeof(DevExpert), hipMemcpyHostToDevice) != hipSuccess ||
+      init_attrs_decode_fused() != hipSuccess || init_attrs_ffn_decode() != hipSuccess ||
+      init_attrs_prefill() != hipSuccess) {
+    (void)hipGetLastError();
     delete L;
     return MOEQ_EDEVICE;
   }

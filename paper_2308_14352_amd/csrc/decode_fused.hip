@@ -1091,10 +1091,10 @@ __global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
     auto run = [&](auto bits_tag) __attribute__((always_inline)) {
       constexpr int BITS = decltype(bits_tag)::value;
       const int DW = SW * BITS / 32;
-      if (DW >= 8) fused_expert_out<BITS, 8>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
-      else if (DW == 4) fused_expert_out<BITS, 4>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
-      else if (DW == 2) fused_expert_out<BITS, 2>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
-      else fused_expert_out<BITS, 1>(ex, tid, nthreads, d, L.group, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      if (DW >= 8) fused_expert_out<BITS, 8>(ex, tid, nthreads, d, L.group_out, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      else if (DW == 4) fused_expert_out<BITS, 4>(ex, tid, nthreads, d, L.group_out, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      else if (DW == 2) fused_expert_out<BITS, 2>(ex, tid, nthreads, d, L.group_out, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
+      else fused_expert_out<BITS, 1>(ex, tid, nthreads, d, L.group_out, slice, SW, gate, uph + j, j == 0, HL, HP, Y, between);
     };
     switch (bits) {
       case 2: run(std::integral_constant<int, 2>{}); break;
@@ -1206,12 +1206,12 @@ size_t fused_lds_bytes(const LayerDims& L, int k, int SW, int n_layouts) {
 // compute unit, else the narrowest.
 FusedPlan plan_fused(const LayerDims& L) {
   FusedPlan p{0, 0, 0, 0};
-  if (L.d_model % 8 || L.d_ff % 16 || L.group % 16) return p;
+  if (L.d_model % 8 || L.d_ff % 16 || L.group_out % 16) return p;
   static const int forced = [] { const char* v = std::getenv("MOEQ_SLICE"); return v ? std::atoi(v) : 0; }();
   const int want = cu_count() * 3 / 4;
   int best = 0;
   for (int sw = 16; sw <= 256; sw *= 2) {
-    if (L.group % sw || L.d_ff % sw) break;
+    if (L.group_out % sw || L.d_ff % sw) break;
     if (best == 0 || L.d_ff / sw >= want) best = sw;
     if (forced == sw) { best = sw; break; }
   }
@@ -1226,7 +1226,7 @@ FusedPlan plan_fused(const LayerDims& L) {
   // rows that are whole bursts (two tiles) at every bitwidth (4096 columns), and wavefronts that share the
   // rows of a slice and the 64-row groups of the output evenly.
   static const bool no_mx = [] { const char* v = std::getenv("MOEQ_NO_MFMA"); return v && v[0] == '1'; }();
-  const int mx = (!no_mx && best == kMxSlice && L.group % 128 == 0 && (L.group & (L.group - 1)) == 0 && L.group <= 1024 &&
+  const int mx = (!no_mx && best == kMxSlice && L.group == L.group_out && L.group % 128 == 0 && (L.group & (L.group - 1)) == 0 && L.group <= 1024 &&
                   L.d_model % 4096 == 0 && kMxSlice % (nt / 64) == 0 && L.d_model % (4 * nt) == 0) ? 1 : 0;
   if (fused_lds_bytes(L, L.top_k, best, 3) > kFusedLdsBudget) return p;
   if (L.d_model > 2048 * kMaxSegs) return p;
@@ -1238,6 +1238,16 @@ FusedPlan plan_fused(const LayerDims& L) {
 }
 
 int fused_inline_router_max() { return kInlineMaxE; }
+
+hipError_t init_attrs_decode_fused() {
+  (void)cu_count();
+  const void* ks[4] = {(const void*)k_moe_decode<false, false>, (const void*)k_moe_decode<true, false>,
+                       (const void*)k_moe_decode<false, true>, (const void*)k_moe_decode<true, true>};
+  for (const void* kf : ks)
+    if (hipError_t e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBudget); e != hipSuccess)
+      return e;
+  return hipSuccess;
+}
 
 hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const DevExpert* table, const float* router_w,
                              const float* router_bias, const float* logits, int32_t fixed_expert,
@@ -1252,16 +1262,10 @@ hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const De
   const size_t lds = fused_lds_bytes(L, k, plan.SW, n_layouts);
   FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, route_idx, route_gate, x, part,
                 idx_out, gate_out, plan.SW, bits_mask};
-  static size_t granted[4] = {0, 0, 0, 0};
   const bool sw = L.act == MOEQ_ACT_SWIGLU, mx = plan.mx != 0;
-  const int v = (sw ? 1 : 0) + (mx ? 2 : 0);
   auto kernel = mx ? (sw ? k_moe_decode<true, true> : k_moe_decode<false, true>)
                    : (sw ? k_moe_decode<true, false> : k_moe_decode<false, false>);
-  if (lds > 48 * 1024 && lds > granted[v]) {
-    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    granted[v] = lds;
-  }
+  if (lds > kFusedLdsBudget) return hipErrorInvalidValue;   // the ceiling init_attrs_decode_fused() asked for
   if (ev_start && ev_stop)
     hipExtLaunchKernelGGL(kernel, dim3(plan.n_slices, T), dim3(plan.threads), lds, st, ev_start, ev_stop, 0, P);
   else

@@ -678,7 +678,7 @@ __global__ __launch_bounds__(256) void k_relayout_in(const uint8_t* __restrict__
 }  // namespace
 
 bool stream_supported(const LayerDims& L) {
-  return L.d_model == kSD && L.group == kSGroup && L.d_ff % kSSlice == 0 && L.top_k <= 8;
+  return L.d_model == kSD && L.group == kSGroup && L.group_out == kSGroup && L.d_ff % kSSlice == 0 && L.top_k <= 8;
 }
 int stream_inline_router_max() { return kSInlineMaxE; }
 int stream_slices(const LayerDims& L) { return L.d_ff / kSSlice; }

@@ -294,15 +294,15 @@ __device__ __forceinline__ void phase2_body(const LayerDims& L, const DevExpert*
           uint32_t* XPs = LAY + (jj - j0) * lay_words;
           float* XKs = (float*)(XPs + f / 2);
           const int bits = sel_x[jj].bits;
-          if (bits == 2) permute_x<2>(RAW, f, L.group, tid, blockDim.x, XPs, XKs);
-          else if (bits == 4) permute_x<4>(RAW, f, L.group, tid, blockDim.x, XPs, XKs);
-          else permute_x<8>(RAW, f, L.group, tid, blockDim.x, XPs, XKs);
+          if (bits == 2) permute_x<2>(RAW, f, L.group_out, tid, blockDim.x, XPs, XKs);
+          else if (bits == 4) permute_x<4>(RAW, f, L.group_out, tid, blockDim.x, XPs, XKs);
+          else permute_x<8>(RAW, f, L.group_out, tid, blockDim.x, XPs, XKs);
           __syncthreads();   // the layout and s_up are complete; RAW may be overwritten
         }
       };
       auto run = [&](auto bits_tag) {
         constexpr int BITS = decltype(bits_tag)::value;
-        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group, g, s_up + j, row_begin, row_end, rows_per_wg,
+        ffn_out_tasks<BITS>(ex, tid, nwaves, d, f, L.group_out, g, s_up + j, row_begin, row_end, rows_per_wg,
                             ybuf + j * kMaxKs * rows_per_wg, XP, XK, stage);
       };
       switch (ex.bits) {
@@ -437,17 +437,16 @@ PhaseLds phase2_lds(const LayerDims& L, int k, int rows_per_wg) {
   return {ybuf + raw + (size_t)spp * per_slot, spp};
 }
 
-template <typename K>
-hipError_t allow_lds(K kernel, size_t lds, size_t& granted) {
-  if (lds > 48 * 1024 && lds > granted) {
-    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    granted = lds;
-  }
-  return hipSuccess;
-}
 
 }  // namespace
+
+hipError_t init_attrs_ffn_decode() {
+  (void)num_cus();
+  if (hipError_t e = hipFuncSetAttribute((const void*)k_ffn_in, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+      e != hipSuccess)
+    return e;
+  return hipFuncSetAttribute((const void*)k_ffn_out, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+}
 
 hipError_t launch_topk(const LayerDims& L, const float* logits, int32_t T, int32_t* idx, float* gate, float* probs,
                        hipStream_t st) {
@@ -467,8 +466,7 @@ hipError_t launch_ffn_in(const LayerDims& L, const DevExpert* table, const float
   const Split sp = plan_rows(L.d_ff, min_lanes_per_row(L.d_model), wgs_per_token(T),
                              L.act == MOEQ_ACT_SWIGLU ? kBlock / 2 : kBlock);
   const PhaseLds pl = phase1_lds(L, fixed_expert >= 0 ? 1 : L.top_k);
-  static size_t granted = 0;
-  if (hipError_t e = allow_lds(k_ffn_in, pl.bytes, granted); e != hipSuccess) return e;
+  if (pl.bytes > kLdsBudget) return hipErrorInvalidValue;   // the ceiling init_attrs_ffn_decode() asked for
   hipLaunchKernelGGL(k_ffn_in, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, logits, idx_out, gate_out,
                      sel_tab, fixed_expert, x, h, sp.rows_per_wg, pl.spp);
   return hipGetLastError();
@@ -480,8 +478,7 @@ hipError_t launch_ffn_out(const LayerDims& L, const DevExpert* table, const DevE
   Split sp = plan_rows(L.d_model, min_lanes_per_row(L.d_ff), wgs_per_token(T), kBlock);
   sp.threads = phase2_threads(sp.threads);
   const PhaseLds pl = phase2_lds(L, fixed_expert >= 0 ? 1 : L.top_k, sp.rows_per_wg);
-  static size_t granted = 0;
-  if (hipError_t e = allow_lds(k_ffn_out, pl.bytes, granted); e != hipSuccess) return e;
+  if (pl.bytes > kLdsBudget) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_ffn_out, dim3(sp.gx, T), dim3(sp.threads), pl.bytes, st, L, table, sel_tab, gate, fixed_expert,
                      accumulate, h, y, sp.rows_per_wg, pl.spp);
   return hipGetLastError();

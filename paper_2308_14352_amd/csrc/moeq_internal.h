@@ -20,8 +20,9 @@ struct alignas(64) DevExpert {
 };
 static_assert(sizeof(DevExpert) == 64, "expert table entry is 64 bytes");
 
+// group: scale group of W_in / W_gate (along d_model); group_out: of W_out (along d_ff).
 struct LayerDims {
-  int32_t d_model, d_ff, n_experts, top_k, group, act, renorm, x_bf16;
+  int32_t d_model, d_ff, n_experts, top_k, group, act, renorm, x_bf16, group_out;
 };
 
 // Launchers (defined in the .hip files). All enqueue on `st` and return the launch status.
@@ -76,6 +77,12 @@ hipError_t launch_reduce_partials(const float* part, int n_slices, int d, int32_
 // out[c][r] = in[r][c], elements of 2 or 4 bytes.
 hipError_t launch_transpose(const void* in, int64_t rows, int64_t cols, int elem_bytes, void* out,
                             hipStream_t st);
+
+// Per-kernel attributes (the dynamic LDS ceiling) for the current device, set at layer creation so that no
+// compute call has to: a fresh layer's first call can then be recorded into a graph like any other.
+hipError_t init_attrs_decode_fused();
+hipError_t init_attrs_ffn_decode();
+hipError_t init_attrs_prefill();
 
 // ---- one-kernel decode path on integer dot products (W_in / W_gate in the row-block stream layout, W_out in
 // the dword-column-major layout; d_model 4096, scale groups of 128 columns). Arguments as launch_moe_decode;

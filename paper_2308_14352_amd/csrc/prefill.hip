@@ -109,9 +109,10 @@ __global__ __launch_bounds__(256) void k_stage(LayerDims L, const DevExpert* __r
   uint32_t* XP = OUT + (size_t)g * pair_words;
   float* KS = (float*)(XP + cols / 2);
   float* scratch = (float*)(smem + cols / 2);     // the per-chunk offset terms permute_x also makes; not kept
-  if (bits == 2) { permute_x<2>(RAW, cols, L.group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<2>(RAW, cols, threadIdx.x, blockDim.x, KS); }
-  else if (bits == 4) { permute_x<4>(RAW, cols, L.group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<4>(RAW, cols, threadIdx.x, blockDim.x, KS); }
-  else { permute_x<8>(RAW, cols, L.group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<8>(RAW, cols, threadIdx.x, blockDim.x, KS); }
+  const int group = FROM_H ? L.group_out : L.group;
+  if (bits == 2) { permute_x<2>(RAW, cols, group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<2>(RAW, cols, threadIdx.x, blockDim.x, KS); }
+  else if (bits == 4) { permute_x<4>(RAW, cols, group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<4>(RAW, cols, threadIdx.x, blockDim.x, KS); }
+  else { permute_x<8>(RAW, cols, group, threadIdx.x, blockDim.x, XP, scratch); range_offset_terms<8>(RAW, cols, threadIdx.x, blockDim.x, KS); }
   if (threadIdx.x == 0) KS[cols / 64] = up;
 }
 
@@ -153,7 +154,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   using TileT = std::conditional_t<BITS == 2, uint2, uint4>;
   const int K = PHASE == 0 ? G.L.d_model : G.L.d_ff;
   const int N = PHASE == 0 ? G.L.d_ff : G.L.d_model;
-  const int group = G.L.group;
+  const int group = PHASE == 0 ? G.L.group : G.L.group_out;
   const int C = K / WPC, n_steps = K / SC;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, kb = lane >> 4;
@@ -465,8 +466,18 @@ inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 }  // namespace
 
 bool prefill_supported(const LayerDims& L) {
-  return L.group % 128 == 0 && L.d_model % 256 == 0 && L.d_ff % 256 == 0 &&
-         (L.d_model / L.group) % 4 == 0 && (L.d_ff / L.group) % 4 == 0 && L.d_model <= 16384 && L.n_experts <= 1024;
+  return L.group % 128 == 0 && L.group_out % 128 == 0 && L.d_model % 256 == 0 && L.d_ff % 256 == 0 &&
+         (L.d_model / L.group) % 4 == 0 && (L.d_ff / L.group_out) % 4 == 0 && L.d_model <= 16384 &&
+         L.d_ff <= 32768 && L.n_experts <= 1024;
+}
+
+hipError_t init_attrs_prefill() {
+  // the staging kernels keep one activation vector (up to 32768 values) in LDS
+  const int lds = 32768 * 2 + 32768 / 16 * 4 + 64;
+  if (hipError_t e = hipFuncSetAttribute((const void*)k_stage<false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      e != hipSuccess)
+    return e;
+  return hipFuncSetAttribute((const void*)k_stage<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
 PrefillWs prefill_ws(const LayerDims& L, int64_t T) {

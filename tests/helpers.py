@@ -9,21 +9,21 @@ import oracle
 import paper_2308_14352_amd as moeq
 
 
-def pack_expert_gpu(w, bits, group):
+def pack_expert_gpu(w, bits, group, group_out=None):
     """fp32 device weights dict -> moeq.PackedExpert via the library's device quantizer."""
     q_in, s_in = moeq.moe_quantize_pack(w["w_in"], bits, group)
-    q_out, s_out = moeq.moe_quantize_pack(w["w_out"], bits, group)
+    q_out, s_out = moeq.moe_quantize_pack(w["w_out"], bits, group_out or group)
     q_g = s_g = None
     if "w_gate" in w:
         q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], bits, group)
     return moeq.PackedExpert(bits, q_in, s_in, q_out, s_out, q_g, s_g)
 
 
-def pack_expert_oracle(w, bits, group):
+def pack_expert_oracle(w, bits, group, group_out=None):
     """fp32 weights dict (any device) -> oracle.Expert via the oracle's quantizer, on the host."""
     host = {k: v.detach().cpu().numpy() for k, v in w.items()}
     q_in, s_in = oracle.quantize_pack(host["w_in"], bits, group)
-    q_out, s_out = oracle.quantize_pack(host["w_out"], bits, group)
+    q_out, s_out = oracle.quantize_pack(host["w_out"], bits, group_out or group)
     q_g = s_g = None
     if "w_gate" in host:
         q_g, s_g = oracle.quantize_pack(host["w_gate"], bits, group)

@@ -390,6 +390,78 @@ def test_one_kernel_path_takes_many_tokens_in_chunks():
     assert torch.equal(y, y_r)
 
 
+# ------------------------------------------------------------------ one scale per channel of each matrix
+@pytest.mark.parametrize("bits", (2, 4, 8))
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+def test_per_channel_scales_on_both_matrices(bits, columns):
+    """Section 3.2 ("Choosing the algorithm"): one float16 scale per channel. For a Switch-base expert that is
+    group_in = d_model = 768 for W_in and group_out = d_ff = 3072 for W_out; the oracle dequantizes W_out with
+    its own group size, the library is told both."""
+    d, f, g_in, g_out = 768, 3072, 768, 3072
+    cfg = gen.tiny_config("c1", d, f, n_experts=3, group=g_in)
+    experts_gpu, experts_orc = [], []
+    for e in range(3):
+        w = gen.expert_weights(cfg, 0, e, DEV)
+        ex = pack_expert_gpu(w, bits, g_in, g_out)
+        assert tuple(ex.s_in.shape) == (f, 1) and tuple(ex.s_out.shape) == (d, 1)
+        experts_gpu.append(ex.with_out_columns(f, g_out) if columns else ex)
+        experts_orc.append(pack_expert_oracle(w, bits, g_in, g_out))
+    Wr, _ = gen.router_weights(cfg, 0, DEV)
+    layer = moeq.Layer(d, f, 1, g_in, moeq.MOEQ_ACT_RELU, False, moeq.MOEQ_F32, Wr, None, experts_gpu,
+                       moeq.MOEQ_OUT_COLUMNS if columns else moeq.MOEQ_OUT_CANONICAL, group_in=g_in, group_out=g_out)
+    T = 3
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    xh = x.cpu().numpy()
+
+    def ffn_ref(e):        # the oracle's dequantization per matrix (each with its own group), then the plain FFN
+        w_in = oracle.dequant(experts_orc[e].q_in, experts_orc[e].s_in, d, bits, g_in).astype(np.float64)
+        w_out = oracle.dequant(experts_orc[e].q_out, experts_orc[e].s_out, f, bits, g_out).astype(np.float64)
+        return np.maximum(xh.astype(np.float64) @ w_in.T, 0.0) @ w_out.T
+
+    for e in range(3):
+        y = moeq.moe_expert_ffn_q(layer, e, x)
+        torch.cuda.synchronize()
+        assert rel_err(y.cpu().numpy(), ffn_ref(e)).max() < TOL
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    idx_ref, gate_ref, _ = oracle.router_topk(xh, Wr.cpu().numpy(), None, 1, False)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    y_ref = np.stack([gate_ref[t, 0] * ffn_ref(int(idx_ref[t, 0]))[t] for t in range(T)])
+    assert rel_err(y.cpu().numpy(), y_ref).max() < TOL
+
+
+# ------------------------------------------------------------------ the first call of a fresh layer under graph capture
+@pytest.mark.parametrize("layout", ("canonical", "columns", "stream"))
+def test_first_call_of_a_fresh_layer_can_be_captured(layout):
+    """Every per-device set-up step happens in moe_layer_create, so the very first compute call on a layer may
+    be recorded into a HIP graph. The graph is replayed several times with eager work and synchronisations in
+    between and every replay is compared with the eager result."""
+    if layout == "stream":
+        cfg = gen.tiny_config("c4", 4096, 256, n_experts=4, n_layers=1, group=128)
+    else:
+        cfg = gen.tiny_config("c4", 640, 5120, n_experts=4, n_layers=1, group=128)   # needs more than 48 KB of LDS
+    layer, _, Wr, bias = build_layer_pair(cfg, 0, DEV, want_oracle=False, columns=layout != "canonical",
+                                          stream=layout == "stream")
+    T = 2
+    xs = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device=DEV)
+    y = torch.empty((T, cfg.d_model), dtype=torch.float32, device=DEV)
+    ws = torch.empty(layer.workspace_bytes(T), dtype=torch.uint8, device=DEV)
+    xs.copy_(gen.hidden(cfg, 0, 0, T, DEV))
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        moeq.moe_layer_forward(layer, xs, y=y, ws=ws)          # the layer's first call
+    for step in range(3):
+        x_step = gen.hidden(cfg, 0, step, T, DEV)
+        xs.copy_(x_step)
+        g.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        want = moeq.moe_layer_forward(layer, x_step)           # eager, on its own buffers
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), step
+
+
 # ------------------------------------------------------------------ hidden states far from unit scale
 # Section 4.1 ("Baselines"): the decompressed weights are used in FP32 arithmetic, so the range of the hidden
 # states is fp32's. The kernels feed binary16 multipliers; they must normalise what they feed them.
