@@ -54,12 +54,14 @@ def parse():
 class Stack:
     """All layers of one workload, packed in HBM, plus the hidden states of every (step, layer)."""
 
-    def __init__(self, cfg, batch, steps, dev, n_layers=None, columns=True, stream=False):
+    def __init__(self, cfg, batch, steps, dev, n_layers=None, columns=True, stream=False, group_in=None,
+                 group_out=None):
         import torch
         import gen
         import paper_2308_14352_amd as moeq
         self.cfg, self.batch, self.steps, self.columns, self.stream = cfg, batch, steps, columns or stream, stream
         self.L = n_layers or cfg.n_layers
+        g_in, g_out = group_in or cfg.group, group_out or cfg.group
         self.layers, self.bits = [], []
         act = moeq.MOEQ_ACT_SWIGLU if cfg.swiglu else moeq.MOEQ_ACT_RELU
         xdt = moeq.MOEQ_BF16 if cfg.x_dtype == "bf16" else moeq.MOEQ_F32
@@ -68,23 +70,24 @@ class Stack:
             experts = []
             for e in range(cfg.n_experts):
                 w = gen.expert_weights(cfg, l, e, dev)
-                q_in, s_in = moeq.moe_quantize_pack(w["w_in"], bits[e], cfg.group)
-                q_out, s_out = moeq.moe_quantize_pack(w["w_out"], bits[e], cfg.group)
+                q_in, s_in = moeq.moe_quantize_pack(w["w_in"], bits[e], g_in)
+                q_out, s_out = moeq.moe_quantize_pack(w["w_out"], bits[e], g_out)
                 q_g = s_g = None
                 if cfg.swiglu:
-                    q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], bits[e], cfg.group)
+                    q_g, s_g = moeq.moe_quantize_pack(w["w_gate"], bits[e], g_in)
                 ex = moeq.PackedExpert(bits[e], q_in, s_in, q_out, s_out, q_g, s_g)
                 if stream:
                     experts.append(ex.with_stream_layout(cfg.d_model, cfg.d_ff, cfg.group))
                     del q_in, s_in, q_g, s_g
                 else:
-                    experts.append(ex.with_out_columns(cfg.d_ff, cfg.group) if columns else ex)
+                    experts.append(ex.with_out_columns(cfg.d_ff, g_out) if columns else ex)
                 del w, ex, q_out, s_out
             Wr, bias = gen.router_weights(cfg, l, dev)
             self.layers.append(moeq.Layer(cfg.d_model, cfg.d_ff, cfg.top_k, cfg.group, act, cfg.renorm, xdt, Wr,
                                           bias, experts,
                                           moeq.MOEQ_OUT_COLUMNS if (columns or stream) else moeq.MOEQ_OUT_CANONICAL,
-                                          moeq.MOEQ_IN_STREAM if stream else moeq.MOEQ_IN_CANONICAL))
+                                          moeq.MOEQ_IN_STREAM if stream else moeq.MOEQ_IN_CANONICAL,
+                                          group_in=g_in, group_out=g_out))
             self.bits.append(bits)
         torch.cuda.synchronize()
         # hidden states of every (step, layer): [steps][L][batch][d]
@@ -141,22 +144,25 @@ class Stack:
         g.replay()
 
 
-def time_steps(stack, steps, warmup, use_graph):
+def time_steps(stack, steps, warmup, use_graph, passes=5):
+    """W warm-up steps, then the K steps timed `passes` times over (each pass: exactly K steps between two
+    synchronisations). Returns (seconds of the median pass, seconds of every pass, graph)."""
     import torch
     g = None
-    stack.run_step_eager(0)                       # first call sets kernel attributes; never inside a capture
-    torch.cuda.synchronize()
     if use_graph:
-        g = stack.capture()
+        g = stack.capture()                       # a fresh layer's first call may be captured
     run = (lambda s: stack.run_step_graph(g, s)) if use_graph else stack.run_step_eager
     for s in range(warmup):
         run(s % stack.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(steps):
-        run(s % stack.steps)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0), g
+    times = []
+    for _ in range(passes):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            run(s % stack.steps)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+    return sorted(times)[len(times) // 2], times, g
 
 
 class HipEvents:
@@ -242,7 +248,8 @@ def cpu_baseline(stack, dev, budget_layers):
     import gen
     import oracle
     cfg = stack.cfg
-    total, n = 0.0, 0
+    total, n, one_core = 0.0, 0, 0.0
+    all_cores = oracle.num_threads()
     for l in range(min(budget_layers, stack.L)):
         Wr, bias = gen.router_weights(cfg, l, dev)
         x = stack.x_all[0, l].float().cpu().numpy()
@@ -265,9 +272,19 @@ def cpu_baseline(stack, dev, budget_layers):
                              Wr_h, b_h, x)
         total += time.perf_counter() - t0
         n += 1
+        if l == 0:                                  # the same token-layer once more on a single core
+            oracle.set_num_threads(1)
+            t0 = time.perf_counter()
+            oracle.layer_forward(experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), cfg.top_k, cfg.renorm,
+                                 Wr_h, b_h, x)
+            one_core = time.perf_counter() - t0
+            oracle.set_num_threads(all_cores)
     per_layer = total / n
-    return {"value": stack.batch / (per_layer * stack.L), "unit": "tokens/s", "cores": oracle.num_threads(),
+    return {"value": stack.batch / (per_layer * stack.L), "unit": "tokens/s", "cores": all_cores,
             "kind": "oracle",
+            "one_core": {"value": stack.batch / (one_core * stack.L), "unit": "tokens/s",
+                         "sample": f"step 0 of layer 0 (1 token-layer), {one_core * 1e3:.1f} ms"},
+            "build": oracle.BUILD_FLAGS,
             "sample": f"step 0 of layers 0..{n - 1} ({n} token-layers, batch {stack.batch}); "
                       f"{per_layer * 1e3:.1f} ms per token-layer, scaled to the {stack.L}-layer stack"}
 
@@ -350,15 +367,18 @@ WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8
 DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
 
 
-def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True, layout="columns"):
+def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True, layout="columns",
+                 per_channel=False):
     import gen
     cfg_id, batch = WORKLOADS[name]
     cfg = gen.CONFIGS[cfg_id]
     n_distinct = min(steps, cfg.steps)
-    stack = Stack(cfg, batch, n_distinct, dev, n_layers, columns=layout != "canonical", stream=layout == "stream")
+    # per_channel: one float16 scale per channel of each matrix (Section 3.2) instead of the configuration's groups
+    stack = Stack(cfg, batch, n_distinct, dev, n_layers, columns=layout != "canonical", stream=layout == "stream",
+                  group_in=cfg.d_model if per_channel else None, group_out=cfg.d_ff if per_channel else None)
     idx = stack.routing()
     bytes_sl = stack.algorithmic_bytes(idx)
-    elapsed, _ = time_steps(stack, steps, warmup, use_graph)
+    elapsed, pass_times, _ = time_steps(stack, steps, warmup, use_graph)
     # bytes over the timed steps (steps may wrap around the distinct inputs)
     order = [s % n_distinct for s in range(steps)]
     total_bytes = float(bytes_sl[order].sum())
@@ -370,6 +390,7 @@ def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events
         "bytes_per_layer_call": total_bytes / (steps * stack.L),
         "layers": stack.L, "batch": batch, "steps": steps,
         "packed_GB": stack.packed_bytes / 1e9,
+        "ms_per_step_passes": [t / steps * 1e3 for t in pass_times],
     }
     if want_events:
         ms, kb = dominant_kernel_events(stack, min(steps, 32), idx)
@@ -432,7 +453,8 @@ def main():
     out = {
         "metric": "decode MoE-layer tokens/s + achieved HBM GB/s on packed experts (% peak)",
         "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": res["ms_per_step"], "passes": len(res["ms_per_step_passes"]),
+        "ms_per_step_passes": res["ms_per_step_passes"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "dtype_note": "codes and activations enter the multipliers as binary16 (codes exactly; bf16 hidden states "
                       "exactly), every product and sum is fp32; scales and offsets are applied in fp32",
@@ -472,6 +494,12 @@ def main():
                 extras[other]["hot_expert_share"] = r["hot_expert_share"]
             del st
             torch.cuda.empty_cache()
+        st, r = run_workload("c1", 64, args.warmup, use_graph, dev, want_events=False, layout="columns", per_channel=True)
+        extras["c1_per_channel_scales"] = {"layout": "columns", "group_in": 768, "group_out": 3072}
+        extras["c1_per_channel_scales"].update({kk: r[kk] for kk in ("tokens_per_s", "ms_per_step", "algorithmic_GBps",
+                                                                      "layers", "batch", "steps", "packed_GB")})
+        del st
+        torch.cuda.empty_cache()
         extras["c5_prefill"] = run_prefill(dev)
         extras["c4_expert_fused_vs_unfused"] = run_unfused_comparison(dev)
         out["other_workloads"] = extras

@@ -70,6 +70,14 @@ def num_threads():
     return int(lib().orc_num_threads())
 
 
+def set_num_threads(n):
+    """OpenMP threads of the following calls (a timing knob of the benchmark's baseline leg)."""
+    lib().orc_set_num_threads(C.c_int(int(n)))
+
+
+BUILD_FLAGS = "g++ -std=c++17 -O2 -fopenmp -ffp-contract=off -fno-fast-math"
+
+
 def quantize(w, bits, group):
     """w [rows][cols] fp32 -> (q int8 [rows][cols], scales uint16(fp16 bits) [rows][cols/group])."""
     w = np.ascontiguousarray(w, dtype=np.float32)

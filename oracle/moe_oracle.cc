@@ -35,6 +35,9 @@
 #include <cstdlib>
 #include <cstring>
 #include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 extern "C" {
 
@@ -305,6 +308,15 @@ int orc_layer_forward(const orc_expert* experts, int32_t E, int32_t d, int32_t f
                       const float* x, int32_t T, float* y, int32_t* idx, float* gate) {
   if (orc_router_topk(x, T, d, Wr, bias, E, k, renorm, idx, gate, nullptr, nullptr)) return 1;
   return orc_layer_forward_routed(experts, E, d, f, g, act, k, x, T, idx, gate, y);
+}
+
+// Harness knob for the timed baseline (1 thread against all): no effect on any result.
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
 }
 
 int orc_num_threads() {
