@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c3b8", "c4"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c2b8", "c3", "c3b8", "c4"])
     ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other decode workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every layer from Python instead of a HIP graph")
@@ -363,8 +363,8 @@ def run_unfused_comparison(dev, reps=10):
             "max_rel_diff": diff, "fp32_copy_GB": 3 * cfg.d_model * cfg.d_ff * 4 / 1e9}
 
 
-WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c3": ("c3", 1), "c3b8": ("c3", 8), "c4": ("c4", 1)}
-DEFAULT_STEPS = {"c1": 64, "c2": 512, "c3": 256, "c3b8": 256, "c4": 128}
+WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c2b8": ("c2", 8), "c3": ("c3", 1), "c3b8": ("c3", 8), "c4": ("c4", 1)}
+DEFAULT_STEPS = {"c1": 64, "c2": 512, "c2b8": 256, "c3": 256, "c3b8": 256, "c4": 128}
 
 
 def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events=True, layout="columns",
@@ -396,6 +396,11 @@ def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events
         ms, kb = dominant_kernel_events(stack, min(steps, 32), idx)
         res["kernel_ms"] = ms
         res["kernel_bytes"] = kb
+    if batch > 1:
+        import numpy as np
+        distinct = np.mean([len(np.unique(idx[s % n_distinct, l])) for s in range(steps) for l in range(stack.L)])
+        res["distinct_experts_per_layer_call"] = float(distinct)
+        res["pairs_per_layer_call"] = batch * cfg.top_k
     if cfg.bias_rule == "hotset":
         import numpy as np
         hot_share = []
@@ -481,14 +486,15 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_extras:
         extras = {}
-        for other, k in (("c1", 64), ("c2", 256), ("c3", 128), ("c3b8", 128)):
+        for other, k in (("c1", 64), ("c2", 256), ("c2b8", 128), ("c3", 128), ("c3b8", 128)):
             if other == name:
                 continue
             st, r = run_workload(other, k, args.warmup, use_graph, dev, want_events=False,
                                  layout=pick_layout(other))
             extras[other] = {"layout": pick_layout(other)}
             extras[other].update({kk: r[kk] for kk in ("tokens_per_s", "layer_tokens_per_s", "ms_per_step",
-                                                  "algorithmic_GBps", "layers", "batch", "steps", "packed_GB")
+                                                  "algorithmic_GBps", "bytes_per_layer_call", "layers", "batch", "steps",
+                                                  "packed_GB", "distinct_experts_per_layer_call", "pairs_per_layer_call")
                              if kk in r})
             if "hot_expert_share" in r:
                 extras[other]["hot_expert_share"] = r["hot_expert_share"]

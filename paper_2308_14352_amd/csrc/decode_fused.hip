@@ -719,8 +719,10 @@ __device__ __forceinline__ void mx2_compute(const MxSet2& S, const MxWalk2& w, i
   }
 }
 
-template <bool SWIGLU, bool MX>
-__global__ __launch_bounds__(1024) void k_moe_decode(FusedParams P) {
+// MAXT: the largest workgroup the variant is launched with (small layers run 256 threads and then have four
+// times the registers per thread).
+template <bool SWIGLU, bool MX, int MAXT = 1024>
+__global__ __launch_bounds__(MAXT) void k_moe_decode(FusedParams P) {
   extern __shared__ uint32_t smem[];
   __shared__ int sel_e[8];
   __shared__ float sel_g[8];
@@ -1241,8 +1243,9 @@ int fused_inline_router_max() { return kInlineMaxE; }
 
 hipError_t init_attrs_decode_fused() {
   (void)cu_count();
-  const void* ks[4] = {(const void*)k_moe_decode<false, false>, (const void*)k_moe_decode<true, false>,
-                       (const void*)k_moe_decode<false, true>, (const void*)k_moe_decode<true, true>};
+  const void* ks[6] = {(const void*)k_moe_decode<false, false>, (const void*)k_moe_decode<true, false>,
+                       (const void*)k_moe_decode<false, true>, (const void*)k_moe_decode<true, true>,
+                       (const void*)k_moe_decode<false, false, 256>, (const void*)k_moe_decode<true, false, 256>};
   for (const void* kf : ks)
     if (hipError_t e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLdsBudget); e != hipSuccess)
       return e;
@@ -1263,8 +1266,10 @@ hipError_t launch_moe_decode(const LayerDims& L, const FusedPlan& plan, const De
   FusedParams P{L, table, router_w, router_bias, logits, fixed_expert, gate_in, route_idx, route_gate, x, part,
                 idx_out, gate_out, plan.SW, bits_mask};
   const bool sw = L.act == MOEQ_ACT_SWIGLU, mx = plan.mx != 0;
+  const bool small = !mx && plan.threads <= 256;
   auto kernel = mx ? (sw ? k_moe_decode<true, true> : k_moe_decode<false, true>)
-                   : (sw ? k_moe_decode<true, false> : k_moe_decode<false, false>);
+                   : small ? (sw ? k_moe_decode<true, false, 256> : k_moe_decode<false, false, 256>)
+                           : (sw ? k_moe_decode<true, false> : k_moe_decode<false, false>);
   if (lds > kFusedLdsBudget) return hipErrorInvalidValue;   // the ceiling init_attrs_decode_fused() asked for
   if (ev_start && ev_stop)
     hipExtLaunchKernelGGL(kernel, dim3(plan.n_slices, T), dim3(plan.threads), lds, st, ev_start, ev_stop, 0, P);

@@ -7,26 +7,17 @@
 namespace moeq {
 namespace {
 
-// fp32 -> binary16 bits, round to nearest even, done with integer arithmetic so that the result does
-// not depend on the floating-point mode of the wavefront. Input is finite and >= 0 here.
+// fp32 -> binary16 bits, round to nearest even, for a finite input >= 0.
+// Normal results: the exponent is re-biased and the 13 dropped mantissa bits are rounded by adding 0xfff plus
+// the lowest kept bit, one integer addition whose carry runs into the exponent where it must (so values that
+// round up to 65536 come out as the infinity pattern 0x7c00). Results below 2^-14 are multiples of 2^-24:
+// adding 0.5f puts the float's last mantissa bit exactly there, the addition itself rounds to nearest even
+// (the wavefront's default mode), and the low bits of the sum are the binary16 pattern.
 __device__ __forceinline__ uint32_t f32_to_f16_bits_rne(float f) {
   const uint32_t x = __float_as_uint(f);
-  const int32_t e = (int32_t)((x >> 23) & 0xffu) - 127;
-  uint32_t m = x & 0x7fffffu;
-  if (e > 15) return 0x7c00u;
-  if (e >= -14) {
-    uint32_t h = ((uint32_t)(e + 15) << 10) | (m >> 13);
-    const uint32_t rem = m & 0x1fffu;
-    h += (rem > 0x1000u) || (rem == 0x1000u && (h & 1u));
-    return h;
-  }
-  if (e < -25) return 0u;
-  m |= 0x800000u;
-  const int sh = -e - 1;  // 14 .. 24
-  uint32_t h = m >> sh;
-  const uint32_t rem = m & ((1u << sh) - 1u), half = 1u << (sh - 1);
-  h += (rem > half) || (rem == half && (h & 1u));
-  return h;
+  if (x >= 0x47800000u) return 0x7c00u;                            // 65536 and above
+  if (x < 0x38800000u) return __float_as_uint(f + 0.5f) - 0x3f000000u;
+  return (x + 0xc8000fffu + ((x >> 13) & 1u)) >> 13;               // 0xc8000000 = -(112 << 23): exponent bias 127 -> 15
 }
 
 // binary16 bits (finite, non-negative) -> fp32, exact.
