@@ -6,7 +6,7 @@ top-k -> dequantize-fused expert FFNs -> gate-weighted combine on that step's hi
 layers strictly in order on one stream. Inputs (packed experts, router weights, all hidden states)
 are resident in HBM before the timed region. Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c3|c3b8] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c2b8|c3|c3b8] [--no-extras]
 """
 import argparse
 import json
@@ -19,11 +19,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by
-# what the counter reads for a plain pass over 1 GiB: factors 2.000 and 1.000), mean over the dispatches of
-# `bench.py --no-extras --no-cpu-baseline --no-graph --layers 4 --steps 6 --warmup 2`, whose algorithmic bytes
-# per launch are 130.4 MB. The summary with the commands is profiles/c4_decode_pmc.md.
-PMC_TRAFFIC_C4 = {"fetch_bytes": 132.7e6, "write_bytes": 3.67e6, "algorithmic_bytes_same_slice": 130.4e6}
+# HBM bytes per launch of k_moe_stream on the c4 stack from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per
+# dispatch, each scaled by what the counter reads for a plain pass over 1 GiB: factors 2.000 and 1.000), mean
+# over the dispatches of `bench.py --no-extras --no-cpu-baseline --no-graph --layers 4 --steps 6 --warmup 2`,
+# whose algorithmic bytes per launch are 130.4 MB. A stored figure, not measured in this run: counters need the
+# profiler. The summary with the commands is profiles/k_moe_stream_c4_pmc.md.
+PMC_TRAFFIC_C4_STREAM = {"fetch_bytes": 132.0e6, "write_bytes": 3.67e6, "algorithmic_bytes_same_slice": 130.4e6,
+                         "source": "profiles/k_moe_stream_c4_pmc.md (rocprofv3 --pmc, stored; not re-measured here)"}
 
 
 def parse():
@@ -214,16 +216,17 @@ def dominant_kernel_events(stack, steps, idx):
         stack.xs.copy_(stack.x_all[sd])
         for l in range(stack.L):
             a, b = evs.new(), evs.new()
-            binding.moe_profile_kernel(binding.MOEQ_KERNEL_FUSED if stack.columns else binding.MOEQ_KERNEL_FFN_IN,
-                                       a.value, b.value)
+            binding.moe_layer_profile_kernel(stack.layers[l], binding.MOEQ_KERNEL_FUSED if stack.columns
+                                             else binding.MOEQ_KERNEL_FFN_IN, a.value, b.value)
             moeq.moe_layer_forward(stack.layers[l], stack.xs[l], y=stack.y[l], ws=stack.ws)
+            binding.moe_layer_profile_kernel(stack.layers[l], 0)
             pairs.append((a, b))
             layer = stack.layers[l]
             if stack.columns:       # router weights (+bias), x, every (token, choice) slot's whole expert
                 tot = stack.batch * cfg.d_model * xb + layer.router_w.numel() * 4 \
                     + (0 if layer.router_bias is None else cfg.n_experts * 4)
             else:                   # x, logits, the h vectors out
-                tot = stack.batch * cfg.d_model * xb + stack.batch * cfg.top_k * cfg.d_ff * 2 \
+                tot = stack.batch * cfg.d_model * xb + stack.batch * cfg.top_k * cfg.d_ff * 4 \
                     + stack.batch * cfg.n_experts * 4
             for t in range(stack.batch):                 # the kernel streams every (token, choice) slot
                 for e in idx[sd, l, t]:
@@ -233,7 +236,6 @@ def dominant_kernel_events(stack, steps, idx):
                         if tns is not None:
                             tot += tns.numel() * tns.element_size()
             nbytes.append(tot)
-    binding.moe_profile_kernel(0)
     torch.cuda.synchronize()
     ms = [evs.ms(a, b) for a, b in pairs]
     evs.close()
@@ -460,9 +462,14 @@ def main():
         "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_step"], "passes": len(res["ms_per_step_passes"]),
         "ms_per_step_passes": res["ms_per_step_passes"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "dtype_note": "codes and activations enter the multipliers as binary16 (codes exactly; bf16 hidden states "
-                      "exactly), every product and sum is fp32; scales and offsets are applied in fp32",
+        "dtype": "i32" if layout == "stream" else "f32", "data": "synthetic",
+        "dtype_note": ("hidden states enter as block-floating-point integers (one power of two per 128 columns, "
+                       "15 bits), codes as stored; every group's dot product is an exact int32 sum of 4- or 8-bit "
+                       "digit products; group scales, offsets, the activation and the gate-weighted sum are fp32"
+                       if layout == "stream" else
+                       "codes and activations enter the multipliers as binary16 (codes exactly; hidden states after "
+                       "a per-token power-of-two scaling), every product and sum is fp32; scales and offsets are "
+                       "applied in fp32"),
         "config": {"workload": f"{name}: {cfg.name}", "layers": stack.L, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
                    "experts": cfg.n_experts, "top_k": cfg.top_k, "act": cfg.act, "group": cfg.group,
                    "batch": stack.batch, "x_dtype": cfg.x_dtype, "bitwidths": cfg.bit_rule,
@@ -480,6 +487,14 @@ def main():
                      "bytes_per_launch": res["kernel_bytes"], "avg_launch_ms": res["kernel_ms"],
                      "traffic": None},
     }
+    if name == "c4" and layout == "stream":
+        t = PMC_TRAFFIC_C4_STREAM
+        out["roofline"]["traffic"] = t["fetch_bytes"] + t["write_bytes"]
+        out["roofline"]["traffic_detail"] = t
+    if stack.batch > 1:
+        # FETCH_SIZE of the layer call's kernels is compared against these: bytes of the DISTINCT activated experts
+        out["distinct_experts_per_layer_call"] = res["distinct_experts_per_layer_call"]
+        out["distinct_expert_bytes_per_layer_call"] = res["bytes_per_layer_call"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stack, dev, 4 if name == "c4" else 12)
     del stack

@@ -42,6 +42,8 @@
  *             u = q + 2^(b-1) (q in [-(2^(b-1)-1), 2^(b-1)-1]) at bits [i*b mod 8, +b) of byte
  *             floor(i*b/8). cols*b must be a multiple of 128 (16-byte rows).
  *     scales: rows * cols/g IEEE binary16 values, row-major. W^[o][i] = scale[o][i/g] * q[o][i].
+ *             Every entry point uses a scale as the binary16 value it is, sign bit included
+ *             (moe_quantize_pack writes none below zero).
  *
  * Dword-column-major layout of W_out (optional, made from the canonical one by moe_prepare_out)
  *   The same bits, transposed in units of 32-bit words: codes[w][r] = word w (little-endian) of canonical
@@ -253,17 +255,18 @@ moeq_status moe_prepare_in(const void *q, const void *s, int64_t rows, int64_t c
 moeq_status moe_unprepare_in(const void *stream_buf, int64_t rows, int64_t cols, int32_t bits,
                              int32_t group, void *q, void *s, void *stream);
 
-/* Measurement aid. While `which` names a kernel, every moe_layer_forward
- * call records start_event just before and stop_event just after that kernel on the call's stream
- * (hipEvent_t handles created by the caller with timing enabled), so a benchmark can time the
- * dominant kernel alone. For MOEQ_KERNEL_FUSED the two events are attached to the kernel launch
- * itself and receive the begin and end of the kernel's execution (what a kernel trace reports),
- * without the dispatch before it. which = 0 turns it off. Process-wide, not thread-safe; do not
- * use under stream capture. */
+/* Measurement aid, per layer. While `which` names a kernel, every moe_layer_forward call on THIS
+ * layer records start_event just before and stop_event just after that kernel on the call's stream
+ * (hipEvent_t handles created by the caller with timing enabled, which must outlive the setting),
+ * so a benchmark can time the dominant kernel alone. For MOEQ_KERNEL_FUSED the two events are
+ * attached to the kernel launch itself and receive the begin and end of the kernel's execution
+ * (what a kernel trace reports), without the dispatch before it. which = 0 turns it off (the
+ * default). The setting is part of the layer handle: change it only while no other thread is
+ * inside a call on the same layer, and turn it off before a call is captured into a graph. */
 #define MOEQ_KERNEL_FFN_IN 1  /* phase 1: top-k + W_in / W_gate GEMVs (Section 3.2, dequantize-fused) */
 #define MOEQ_KERNEL_FFN_OUT 2 /* phase 2: W_out GEMVs + gate-weighted combine                          */
-#define MOEQ_KERNEL_FUSED 3   /* the one-kernel path: router, top-k and both phases of every d_ff slice */
-moeq_status moe_profile_kernel(int32_t which, void *start_event, void *stop_event);
+#define MOEQ_KERNEL_FUSED 3   /* the one-kernel paths: router, top-k and both phases of every d_ff slice */
+moeq_status moe_layer_profile_kernel(moeq_layer *layer, int32_t which, void *start_event, void *stop_event);
 
 const char *moe_status_str(moeq_status st);
 

@@ -64,8 +64,8 @@ def lib():
     L.moe_layer_create.argtypes = [C.POINTER(moeq_layer_desc), vp, sz, C.POINTER(vp)]
     L.moe_layer_destroy.restype = None
     L.moe_layer_destroy.argtypes = [vp]
-    L.moe_profile_kernel.restype = C.c_int
-    L.moe_profile_kernel.argtypes = [i32, vp, vp]
+    L.moe_layer_profile_kernel.restype = C.c_int
+    L.moe_layer_profile_kernel.argtypes = [vp, i32, vp, vp]
     L.moe_workspace_bytes.restype = sz
     L.moe_workspace_bytes.argtypes = [vp, i32]
     L.moe_layer_path.restype = i32
@@ -101,7 +101,7 @@ def lib():
     return L
 
 
-EXPORTS = ["moe_status_str", "moe_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
+EXPORTS = ["moe_status_str", "moe_layer_profile_kernel", "moe_layer_table_bytes", "moe_packed_bytes", "moe_layer_create",
            "moe_layer_destroy", "moe_workspace_bytes", "moe_layer_path", "moe_router_topk", "moe_expert_ffn_q",
            "moe_layer_forward", "moe_layer_forward_routed", "moe_layer_forward_static", "moe_static_scratch_bytes", "moe_quantize_pack", "moe_unpack_codes", "moe_dequantize", "moe_prepare_out",
            "moe_unprepare_out", "moe_prepare_in", "moe_unprepare_in", "moe_stream_bytes"]
@@ -130,9 +130,10 @@ MOEQ_KERNEL_FFN_IN, MOEQ_KERNEL_FFN_OUT, MOEQ_KERNEL_FUSED = 1, 2, 3
 MOEQ_PATH_TWO_KERNELS, MOEQ_PATH_ONE_KERNEL, MOEQ_PATH_ONE_KERNEL_MX, MOEQ_PATH_GROUPED_GEMM, MOEQ_PATH_STREAM = 0, 1, 2, 3, 4
 
 
-def moe_profile_kernel(which, start_event=None, stop_event=None):
+def moe_layer_profile_kernel(layer, which, start_event=None, stop_event=None):
     """which: 0 (off) or one of the MOEQ_KERNEL_* ids; events are raw hipEvent_t handles (ints)."""
-    _check(lib().moe_profile_kernel(int(which), C.c_void_p(start_event), C.c_void_p(stop_event)), "moe_profile_kernel")
+    _check(lib().moe_layer_profile_kernel(layer.handle, int(which), C.c_void_p(start_event), C.c_void_p(stop_event)),
+           "moe_layer_profile_kernel")
 
 
 def moe_packed_bytes(rows, cols, bits, group):

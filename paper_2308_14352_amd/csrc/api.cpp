@@ -19,6 +19,9 @@ struct moeq_layer {
   int32_t out_layout;              // layout of W_out (MOEQ_OUT_CANONICAL or MOEQ_OUT_COLUMNS)
   int32_t in_layout;               // layout of W_in / W_gate (MOEQ_IN_CANONICAL or MOEQ_IN_STREAM)
   FusedPlan plan;                  // split of the one-kernel path (out_layout == MOEQ_OUT_COLUMNS)
+  // measurement aid (moe_layer_profile_kernel): events to record around one kernel of this layer's calls
+  int32_t prof_which = 0;
+  hipEvent_t prof_start = nullptr, prof_stop = nullptr;
 };
 
 namespace {
@@ -117,16 +120,14 @@ void* static_scratch() {
   return p;
 }
 
-// Measurement aid (moe_profile_kernel): events to record around one kernel of moe_layer_forward.
-struct ProfileHook { int32_t which; hipEvent_t start, stop; };
-ProfileHook g_profile = {0, nullptr, nullptr};
-
+// Measurement aid (moe_layer_profile_kernel): records the layer's two events around one kernel launch.
 struct ScopedEvents {
-  bool on; hipStream_t st;
-  ScopedEvents(int32_t which, hipStream_t s) : on(g_profile.which == which && g_profile.start && g_profile.stop), st(s) {
-    if (on) (void)hipEventRecord(g_profile.start, st);
+  const moeq_layer* l; bool on; hipStream_t st;
+  ScopedEvents(const moeq_layer* layer, int32_t which, hipStream_t s)
+      : l(layer), on(layer->prof_which == which && layer->prof_start && layer->prof_stop), st(s) {
+    if (on) (void)hipEventRecord(l->prof_start, st);
   }
-  ~ScopedEvents() { if (on) (void)hipEventRecord(g_profile.stop, st); }
+  ~ScopedEvents() { if (on) (void)hipEventRecord(l->prof_stop, st); }
 };
 
 }  // namespace
@@ -338,18 +339,18 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
       const int32_t n = n_tokens - t0 < kDecodeChunk ? n_tokens - t0 : kDecodeChunk;
       const size_t s0 = (size_t)t0 * (size_t)L.top_k;
       // the profiling events, when asked for, bracket the kernel's own execution (not its dispatch)
-      const bool prof = t0 == 0 && g_profile.which == MOEQ_KERNEL_FUSED && g_profile.start && g_profile.stop;
+      const bool prof = t0 == 0 && layer->prof_which == MOEQ_KERNEL_FUSED && layer->prof_start && layer->prof_stop;
       const hipError_t le = stream
           ? launch_moe_stream(L, layer->table, layer->router_w, layer->router_bias,
                               lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
                               given ? gate + s0 : nullptr, layer->bits_mask, (const char*)x + (size_t)t0 * x_row, n,
                               part, given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
-                              prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr)
+                              prof ? layer->prof_start : nullptr, prof ? layer->prof_stop : nullptr)
           : launch_moe_decode(L, layer->plan, layer->table, layer->router_w, layer->router_bias,
                               lg ? lg + (size_t)t0 * L.n_experts : nullptr, -1, nullptr, given ? idx + s0 : nullptr,
                               given ? gate + s0 : nullptr, layer->bits_mask, (const char*)x + (size_t)t0 * x_row, n,
                               part, given ? nullptr : idx + s0, given ? nullptr : gate + s0, st,
-                              prof ? g_profile.start : nullptr, prof ? g_profile.stop : nullptr);
+                              prof ? layer->prof_start : nullptr, prof ? layer->prof_stop : nullptr);
       if (le != hipSuccess) return MOEQ_EDEVICE;
       if (launch_reduce_partials(part, layer->plan.n_slices, L.d_model, n, 0, y + (size_t)t0 * L.d_model, st) !=
           hipSuccess)
@@ -362,12 +363,12 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
   if (!given && launch_router_logits(L, layer->router_w, layer->router_bias, x, n_tokens, logits, st) != hipSuccess)
     return MOEQ_EDEVICE;
   {
-    ScopedEvents ev(MOEQ_KERNEL_FFN_IN, st);
+    ScopedEvents ev(layer, MOEQ_KERNEL_FFN_IN, st);
     if (launch_ffn_in(L, layer->table, given ? nullptr : logits, idx, gate, sel_tab, -1, x, n_tokens, h, st) !=
         hipSuccess)
       return MOEQ_EDEVICE;
   }
-  ScopedEvents ev(MOEQ_KERNEL_FFN_OUT, st);
+  ScopedEvents ev(layer, MOEQ_KERNEL_FFN_OUT, st);
   return dev(launch_ffn_out(L, layer->table, sel_tab, gate, -1, 0, h, n_tokens, y, st));
 }
 
@@ -407,10 +408,12 @@ int32_t moe_layer_path(const moeq_layer* layer, int32_t n_tokens) {
   return MOEQ_PATH_TWO_KERNELS;
 }
 
-moeq_status moe_profile_kernel(int32_t which, void* start_event, void* stop_event) {
-  if (which < 0 || which > MOEQ_KERNEL_FUSED) return MOEQ_EINVAL;
+moeq_status moe_layer_profile_kernel(moeq_layer* layer, int32_t which, void* start_event, void* stop_event) {
+  if (!layer || which < 0 || which > MOEQ_KERNEL_FUSED) return MOEQ_EINVAL;
   if (which != 0 && (!start_event || !stop_event)) return MOEQ_EINVAL;
-  g_profile = ProfileHook{which, (hipEvent_t)start_event, (hipEvent_t)stop_event};
+  layer->prof_which = which;
+  layer->prof_start = which ? (hipEvent_t)start_event : nullptr;
+  layer->prof_stop = which ? (hipEvent_t)stop_event : nullptr;
   return MOEQ_OK;
 }
 

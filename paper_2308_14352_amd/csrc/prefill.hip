@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void k_stage(LayerDims L, const DevExpert* __r
 }
 
 // ---------------------------------------------------------------------------------------------
-// The quantized GEMM. Workgroup = 4 wavefronts = 64 tokens x (4 wavefronts x 4 streams x 16 rows); a
+// The quantized GEMM. Workgroup = 8 wavefronts = 64 tokens x (8 wavefronts x NS streams x 16 rows); a
 // stream is (matrix, block of 16 rows): with two matrices (SwiGLU phase 1) a wavefront owns 32 rows of both,
 // else 64 rows. Lane (n, kb) of a wavefront holds, per K step, the 16-byte piece 4*step + kb of row n of
 // each stream (8 bytes at 2 bits): four k blocks along one scale group.

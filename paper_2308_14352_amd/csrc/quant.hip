@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void k_dequantize_any(const uint8_t* __restric
   const int64_t bit = i * bits;
   const uint32_t u = (q[bit >> 3] >> (bit & 7)) & ((1u << bits) - 1u);
   const int64_t row = i / cols, col = i % cols;
-  const float sc = f16_bits_to_f32(s[row * (cols / group) + col / group] & 0x7fffu);
+  const float sc = f16_bits_to_f32(s[row * (cols / group) + col / group]);
   w[i] = sc * (float)((int)u - (1 << (bits - 1)));
 }
 
@@ -122,13 +122,13 @@ __global__ __launch_bounds__(256) void k_dequantize(const uint32_t* __restrict__
   const uint32_t u = q[i];
   float v[WPW];
   if (group % WPW == 0) {
-    const float sc = f16_bits_to_f32(srow[col0 / group] & 0x7fffu);
+    const float sc = f16_bits_to_f32(srow[col0 / group]);
 #pragma unroll
     for (int e = 0; e < WPW; ++e) v[e] = sc * (float)((int)((u >> (e * BITS)) & MASK) - OFF);
   } else {
 #pragma unroll
     for (int e = 0; e < WPW; ++e)
-      v[e] = f16_bits_to_f32(srow[(col0 + e) / group] & 0x7fffu) * (float)((int)((u >> (e * BITS)) & MASK) - OFF);
+      v[e] = f16_bits_to_f32(srow[(col0 + e) / group]) * (float)((int)((u >> (e * BITS)) & MASK) - OFF);
   }
   float4* o = (float4*)(w + row * cols + col0);
 #pragma unroll

@@ -227,6 +227,44 @@ def test_layer_forward_routed_small(base, d, f, E, T, columns):
     moeq.moe_layer_forward_routed(layer, x[:0], idx_l[:0], gate_l[:0])
 
 
+@pytest.mark.parametrize("T", (2, 8, 31))
+@pytest.mark.parametrize("base,d,f,E,layout", [
+    ("c2", 384, 768, 16, "canonical"), ("c2", 384, 768, 16, "columns"), ("c3", 512, 1024, 32, "canonical"),
+    ("c4", 4096, 256, 8, "stream"), ("c4", 512, 1792, 8, "columns"),
+])
+def test_small_batches_whose_tokens_share_experts(base, d, f, E, layout, T):
+    """Calls of 2..31 tokens in which several tokens choose the same expert (a hot set: every token draws its
+    experts from three of the layer's), through moe_layer_forward_routed with seeded gates, and with the
+    router's own decision through moe_layer_forward; every token's output against the oracle."""
+    cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=layout == "columns", stream=layout == "stream")
+    want = {"canonical": (moeq.MOEQ_PATH_TWO_KERNELS,), "stream": (moeq.MOEQ_PATH_STREAM,),
+            "columns": (moeq.MOEQ_PATH_ONE_KERNEL, moeq.MOEQ_PATH_ONE_KERNEL_MX)}[layout]
+    assert layer.path(T) in want
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    k = cfg.top_k
+    rng = np.random.default_rng(77 + T)
+    hot = rng.choice(E, size=3, replace=False)
+    idx = np.stack([rng.permutation(hot)[:k] for _ in range(T)]).astype(np.int32)
+    counts = np.bincount(idx.reshape(-1), minlength=E)
+    assert counts.max() >= 2                         # some expert serves several tokens of the call
+    gate = rng.uniform(0.05, 1.2, size=(T, k)).astype(np.float32)
+    y = moeq.moe_layer_forward_routed(layer, x, torch.from_numpy(idx).to(DEV), torch.from_numpy(gate).to(DEV))
+    torch.cuda.synchronize()
+    y_ref = oracle.layer_forward_routed(orc_experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), k,
+                                        x.float().cpu().numpy(), idx, gate)
+    assert rel_err(y.cpu().numpy(), y_ref).max() < TOL
+    # the router's own decision on the same call (T > E/k forces repeats; otherwise they are likely)
+    y2, idx2, _ = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y2_ref, idx2_ref, _ = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 1
+    assert np.array_equal(idx2.cpu().numpy()[keep], idx2_ref[keep])
+    assert rel_err(y2.cpu().numpy()[keep], y2_ref[keep]).max() < TOL
+
+
 def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
     """Oracle-side experts for the activated ones only; the rest are never dereferenced."""
     dummy = oracle.Expert(4, np.zeros(1, np.uint8), np.zeros(1, np.uint16), np.zeros(1, np.uint8),

@@ -117,8 +117,8 @@ def _stratified_tokens(idx, n_experts, per_expert):
             continue
         ranks = {0, n - 1, n // 2, min(63, n - 1), min(64, n - 1), min(65, n - 1), (n // 64) * 64 - 1 if n >= 64 else 0,
                  min((n // 64) * 64, n - 1)}
-        ranks |= set(np.linspace(0, n - 1, max(per_expert - len(ranks), 2)).astype(int).tolist())
-        chosen |= {int(toks[r]) for r in sorted(ranks)[:max(per_expert, 8)]}
+        ranks |= set(np.linspace(0, n - 1, max(per_expert - len(ranks), 2) + 2).astype(int).tolist())
+        chosen |= {int(toks[r]) for r in ranks}
     return sorted(chosen)
 
 
@@ -129,7 +129,7 @@ def test_c5_prefill_stratified_tokens(layout):
     xs = gen.hidden(cfg, 0, 0, T, DEV)
     Wr, bias = gen.router_weights(cfg, 0, DEV)
     idx_all, _, _ = oracle.router_topk(xs.float().cpu().numpy(), Wr.cpu().numpy(), bias.cpu().numpy(), cfg.top_k, cfg.renorm)
-    rows = _stratified_tokens(idx_all, cfg.n_experts, 40 if FULL else 11)
+    rows = _stratified_tokens(idx_all, cfg.n_experts, 40 if FULL else 12)
     assert len(rows) >= (256 if FULL else 64)
     err, n, tied = check_layer(cfg, 0, layout, xs, [(0, T)], 2e-2, gpu_rows=rows)
     _record(f"c5_{layout}", tokens_compared=n, near_ties=tied, max_rel_err=err)
