@@ -41,6 +41,11 @@ def parse():
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="run only a plain elementwise pass over 1 GiB (reads 1 GiB, writes 1 GiB) and exit: the "
                          "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--shared-expert-probe", action="store_true",
+                    help="run only calls of 8 tokens on a c3-shaped layer whose routing is given: all tokens on one "
+                         "expert, 4 experts with 2 tokens each (neighbouring tokens / tokens 4 apart), 8 different "
+                         "experts; 4 calls of each pattern in this order, every call on experts no earlier call touched "
+                         "(the run rocprofv3's FETCH_SIZE per dispatch is read from)")
     ap.add_argument("--prefill-only", action="store_true",
                     help="run only the c5 prefill layer call (the run its rocprofv3 summaries are made from), "
                          "print its figures as one JSON line and exit")
@@ -202,14 +207,15 @@ def dominant_kernel_events(stack, steps, idx):
     """Eager pass over `steps` steps with a HIP event pair the library attaches to the dominant kernel
     of every layer call (begin and end of the kernel's execution on its stream): k_moe_decode (the whole layer
     but the final sum of partial vectors) with W_out in columns, else k_ffn_in (phase 1, about two thirds
-    of the bytes). Returns (mean duration in ms, mean algorithmic bytes of that kernel)."""
+    of the bytes). Returns (mean duration in ms, mean algorithmic bytes of that kernel, and for single-token
+    calls the same two figures grouped by the bitwidths of the chosen experts)."""
     import numpy as np
     import torch
     import paper_2308_14352_amd as moeq
     from paper_2308_14352_amd import binding
     cfg = stack.cfg
     evs = HipEvents()
-    pairs, nbytes = [], []
+    pairs, nbytes, mixes = [], [], []
     xb = 2 if cfg.x_dtype == "bf16" else 4
     for s in range(steps):
         sd = s % stack.steps
@@ -236,10 +242,17 @@ def dominant_kernel_events(stack, steps, idx):
                         if tns is not None:
                             tot += tns.numel() * tns.element_size()
             nbytes.append(tot)
+            mixes.append("+".join(str(b) for b in sorted(layer.experts[int(e)].bits for e in idx[sd, l, 0])))
     torch.cuda.synchronize()
     ms = [evs.ms(a, b) for a, b in pairs]
     evs.close()
-    return float(np.mean(ms)), float(np.mean(nbytes))
+    by_mix = {}
+    if stack.batch == 1:
+        for m in sorted(set(mixes)):
+            sel = [i for i, mm in enumerate(mixes) if mm == m]
+            t, nb = float(np.mean([ms[i] for i in sel])), float(np.mean([nbytes[i] for i in sel]))
+            by_mix[m] = {"launches": len(sel), "avg_launch_ms": t, "bytes_per_launch": nb, "GBps": nb / t / 1e6}
+    return float(np.mean(ms)), float(np.mean(nbytes)), by_mix
 
 
 def cpu_baseline(stack, dev, budget_layers):
@@ -365,6 +378,43 @@ def run_unfused_comparison(dev, reps=10):
             "max_rel_diff": diff, "fp32_copy_GB": 3 * cfg.d_model * cfg.d_ff * 4 / 1e9}
 
 
+def run_shared_expert_probe(dev, layout):
+    """Calls of 8 tokens with caller-given routing (moe_layer_forward_routed) on one c3-shaped layer whose 128
+    experts are all 4-bit: how many bytes a call fetches when its tokens share experts is read from rocprofv3's
+    FETCH_SIZE of the dispatches, in the order stated in `order`."""
+    import torch
+    import gen
+    import paper_2308_14352_amd as moeq
+    cfg = gen.CONFIGS["c3"]
+    columns = layout == "columns"
+    experts = []
+    for e in range(cfg.n_experts):
+        w = gen.expert_weights(cfg, 0, e, dev)
+        q = [moeq.moe_quantize_pack(m, 4, cfg.group) for m in (w["w_in"], w["w_out"])]
+        ex = moeq.PackedExpert(4, q[0][0], q[0][1], q[1][0], q[1][1], None, None)
+        experts.append(ex.with_out_columns(cfg.d_ff, cfg.group) if columns else ex)
+    Wr, bias = gen.router_weights(cfg, 0, dev)
+    layer = moeq.Layer(cfg.d_model, cfg.d_ff, 1, cfg.group, moeq.MOEQ_ACT_RELU, 0, moeq.MOEQ_F32, Wr, bias, experts,
+                       moeq.MOEQ_OUT_COLUMNS if columns else moeq.MOEQ_OUT_CANONICAL)
+    T = 8
+    x = gen.hidden(cfg, 0, 0, T, dev)
+    gate = torch.ones((T, 1), dtype=torch.float32, device=dev)
+    patterns = {"one_expert": [0] * 8, "four_experts_neighbours": [0, 0, 1, 1, 2, 2, 3, 3],
+                "four_experts_apart": [0, 1, 2, 3, 0, 1, 2, 3], "eight_experts": list(range(8))}
+    base, order = 0, []
+    for name, pat in patterns.items():
+        for _ in range(4):
+            idx = torch.tensor([[base + v] for v in pat], dtype=torch.int32, device=dev)
+            moeq.moe_layer_forward_routed(layer, x, idx, gate)
+            torch.cuda.synchronize()
+            base += max(pat) + 1
+            order.append(name)
+    assert base <= cfg.n_experts
+    return {"layout": layout if layout != "auto" else "canonical", "tokens_per_call": T, "order": order,
+            "expert_bytes": experts[0].nbytes(),
+            "distinct_experts": {k: len(set(v)) for k, v in patterns.items()}}
+
+
 WORKLOADS = {"c1": ("c1", 1), "c2": ("c2", 1), "c2b8": ("c2", 8), "c3": ("c3", 1), "c3b8": ("c3", 8), "c4": ("c4", 1)}
 DEFAULT_STEPS = {"c1": 64, "c2": 512, "c2b8": 256, "c3": 256, "c3b8": 256, "c4": 128}
 
@@ -395,9 +445,10 @@ def run_workload(name, steps, warmup, use_graph, dev, n_layers=None, want_events
         "ms_per_step_passes": [t / steps * 1e3 for t in pass_times],
     }
     if want_events:
-        ms, kb = dominant_kernel_events(stack, min(steps, 32), idx)
+        ms, kb, by_mix = dominant_kernel_events(stack, min(steps, 32), idx)
         res["kernel_ms"] = ms
         res["kernel_bytes"] = kb
+        res["kernel_by_mix"] = by_mix
     if batch > 1:
         import numpy as np
         distinct = np.mean([len(np.unique(idx[s % n_distinct, l])) for s in range(steps) for l in range(stack.L)])
@@ -434,6 +485,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "torch.add over 2^28 fp32", "read_bytes": a.numel() * 4,
                           "write_bytes": b.numel() * 4}))
+        return
+    if args.shared_expert_probe:
+        print(json.dumps({"shared_expert_probe": run_shared_expert_probe(dev, args.layout)}))
         return
     if args.prefill_only:
         print(json.dumps({"c5_prefill": run_prefill(dev, reps=args.steps or 5, columns=args.layout == "columns")}))
@@ -487,6 +541,9 @@ def main():
                      "bytes_per_launch": res["kernel_bytes"], "avg_launch_ms": res["kernel_ms"],
                      "traffic": None},
     }
+    if res["kernel_by_mix"]:
+        # the same kernel figures grouped by the bitwidths of the experts the token chose
+        out["roofline"]["by_expert_bitwidths"] = res["kernel_by_mix"]
     if name == "c4" and layout == "stream":
         t = PMC_TRAFFIC_C4_STREAM
         out["roofline"]["traffic"] = t["fetch_bytes"] + t["write_bytes"]
