@@ -265,6 +265,30 @@ def test_small_batches_whose_tokens_share_experts(base, d, f, E, layout, T):
     assert rel_err(y2.cpu().numpy()[keep], y2_ref[keep]).max() < TOL
 
 
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+@pytest.mark.parametrize("name,base,d,f,E,k,g,T", [
+    # a SwiGLU top-2 layer of 8 experts with dimensions that are no powers of two, and a ReLU top-2 layer of 16
+    # experts with a long d_ff: the size classes of the paper's two other evaluated model families (Section 4.1
+    # model table; their real dimensions are not printed in the paper and are not claimed here)
+    ("swiglu_8x_top2", "c4", 2304, 5760, 8, 2, 128, 3), ("swiglu_8x_top2", "c4", 2304, 5760, 8, 2, 128, 40),
+    ("relu_16x_top2", "c3", 1024, 8192, 16, 2, 64, 5),
+])
+def test_layer_forward_other_layer_shapes(name, base, d, f, E, k, g, T, columns):
+    from dataclasses import replace
+    cfg = replace(gen.tiny_config(base, d, f, n_experts=E, n_layers=1, group=g), top_k=k, bit_rule="uniform248")
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 2
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL
+
+
 def _lazy_oracle_experts(cfg, layer_id, bits_table, needed):
     """Oracle-side experts for the activated ones only; the rest are never dereferenced."""
     dummy = oracle.Expert(4, np.zeros(1, np.uint8), np.zeros(1, np.uint16), np.zeros(1, np.uint8),
