@@ -290,7 +290,13 @@ __device__ __forceinline__ void offset_terms(const uint16_t* lin, int cols, int 
 // The negated offset terms of whole lane-column ranges (128 columns, 64 at 8 bits) of a linear binary16
 // vector in LDS: KS[r] = -2^(b-1) * 2^-24 * (sum of the activations of range r). Four threads share a range.
 template <int BITS>
-__device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS);
+__device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS,
+                                                   int stride = 1);
+
+// Where permute_x puts 16-byte item i of the pair order: by default item i itself.
+struct PairOrderLinear {
+  __device__ __forceinline__ int operator()(int i) const { return i; }
+};
 
 // Two binary16 halves of two registers as one pair register: (lo of a, lo of b) or (hi of a, hi of b).
 __device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
@@ -305,9 +311,9 @@ __device__ __forceinline__ uint32_t pair_scale(uint32_t p, float s) {
 // The staged layout, written with 16-byte accesses: the four pair registers of a quad (pair_pos) are made of
 // eight (2-bit codes: sixteen) consecutive activations, so one work item turns one or two 16-byte reads of
 // RAW into one or two 16-byte writes: quad q of chunk c goes to XP4[q * C + c].
-template <int BITS, bool RANGES = false>
+template <int BITS, bool RANGES = false, typename Map = PairOrderLinear>
 __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int group, int tid, int nthreads,
-                                          uint32_t* XP, float* XK) {
+                                          uint32_t* XP, float* XK, Map at = Map()) {
   constexpr int WPC = Fmt<BITS>::WPC;
   const int C = cols / WPC;
   const uint4* R4 = (const uint4*)RAW;
@@ -317,15 +323,15 @@ __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int gro
     for (int i = tid; i < 4 * C; i += nthreads) {
       const int q = i / C, c = i - q * C;
       const uint4 v = R4[c * 4 + q];
-      X4[i] = make_uint4(pair_lo(v.x, v.z), pair_scale(pair_hi(v.x, v.z), 0.0625f), pair_lo(v.y, v.w),
-                         pair_scale(pair_hi(v.y, v.w), 0.0625f));
+      X4[at(i)] = make_uint4(pair_lo(v.x, v.z), pair_scale(pair_hi(v.x, v.z), 0.0625f), pair_lo(v.y, v.w),
+                             pair_scale(pair_hi(v.y, v.w), 0.0625f));
     }
   } else if constexpr (BITS == 8) {
     // chunk = 16 activations = 2 reads; quad q = dwords 2q, 2q+1 of the codes: pairs (k, k+2)
     for (int i = tid; i < 2 * C; i += nthreads) {
       const int q = i / C, c = i - q * C;
       const uint4 v = R4[c * 2 + q];
-      X4[i] = make_uint4(pair_lo(v.x, v.y), pair_hi(v.x, v.y), pair_lo(v.z, v.w), pair_hi(v.z, v.w));
+      X4[at(i)] = make_uint4(pair_lo(v.x, v.y), pair_hi(v.x, v.y), pair_lo(v.z, v.w), pair_hi(v.z, v.w));
     }
   } else {
     // chunk = 64 activations = 8 reads; dword d of the codes: pairs (j, j+8), j = 0..7, in the quads 2d
@@ -333,10 +339,10 @@ __device__ __forceinline__ void permute_x(const uint16_t* RAW, int cols, int gro
     for (int i = tid; i < 4 * C; i += nthreads) {
       const int dd = i / C, c = i - dd * C;
       const uint4 a = R4[c * 8 + 2 * dd], b = R4[c * 8 + 2 * dd + 1];
-      X4[(2 * dd) * C + c] = make_uint4(pair_lo(a.x, b.x), pair_scale(pair_hi(a.x, b.x), 0.25f),
-                                        pair_scale(pair_lo(a.y, b.y), 0.0625f), pair_scale(pair_hi(a.y, b.y), 0.015625f));
-      X4[(2 * dd + 1) * C + c] = make_uint4(pair_scale(pair_lo(a.z, b.z), 0.00390625f), pair_hi(a.z, b.z),
-                                            pair_scale(pair_lo(a.w, b.w), 0.25f), pair_scale(pair_hi(a.w, b.w), 0.0625f));
+      X4[at((2 * dd) * C + c)] = make_uint4(pair_lo(a.x, b.x), pair_scale(pair_hi(a.x, b.x), 0.25f),
+                                            pair_scale(pair_lo(a.y, b.y), 0.0625f), pair_scale(pair_hi(a.y, b.y), 0.015625f));
+      X4[at((2 * dd + 1) * C + c)] = make_uint4(pair_scale(pair_lo(a.z, b.z), 0.00390625f), pair_hi(a.z, b.z),
+                                                pair_scale(pair_lo(a.w, b.w), 0.25f), pair_scale(pair_hi(a.w, b.w), 0.0625f));
     }
   }
   if constexpr (RANGES) range_offset_terms<BITS>(RAW, cols, tid, nthreads, XK);
@@ -355,7 +361,8 @@ constexpr int kDppRor4 = 0x124;  // row_ror:4  (rotation inside a 16-lane row)
 constexpr int kDppRor8 = 0x128;  // row_ror:8
 
 template <int BITS>
-__device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS) {
+__device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols, int tid, int nthreads, float* KS,
+                                                   int stride) {
   constexpr int R = BITS == 8 ? 64 : 128;    // columns of a range
   constexpr int V = R / 32;                  // 128-bit loads per thread
   const uint4* lin4 = (const uint4*)lin;
@@ -370,7 +377,7 @@ __device__ __forceinline__ void range_offset_terms(const uint16_t* lin, int cols
     }
     acc += dpp<kDppXor1>(acc);
     acc += dpp<kDppXor2>(acc);
-    if ((i & 3) == 0) KS[i >> 2] = acc * (-Fmt<BITS>::OFF * 5.9604644775390625e-08f);
+    if ((i & 3) == 0) KS[(i >> 2) * stride] = acc * (-Fmt<BITS>::OFF * 5.9604644775390625e-08f);
   }
 }
 

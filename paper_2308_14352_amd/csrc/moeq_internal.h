@@ -101,10 +101,10 @@ hipError_t launch_relayout_in(const void* q, const void* s, int64_t rows, int bi
                               hipStream_t st);
 
 // ---- batched (prefill) path: pairs grouped by expert, two quantized GEMMs on the matrix cores ----------
-// Byte offsets of the pieces of the prefill workspace (all 256-byte aligned) and the per-pair strides.
+// Byte offsets of the pieces of the prefill workspace (all 256-byte aligned).
 struct PrefillWs {
-  size_t poff, nblk, blocks, gpair, ginv, gexp, xa, ha, hf, ypair, total;
-  size_t a_pair_words, h_pair_words, max_blocks;
+  size_t poff, boff, nblk, blocks, gpair, ginv, gexp, xa, ha, hf, ypair, total;
+  size_t max_blocks;
 };
 bool prefill_supported(const LayerDims& L);
 PrefillWs prefill_ws(const LayerDims& L, int64_t T);
