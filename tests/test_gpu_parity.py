@@ -730,6 +730,34 @@ def test_prefill_layer_matches_oracle(base, d, f, E, g, T, columns):
 
 
 @pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
+@pytest.mark.parametrize("bits", (2, 4, 8))
+def test_prefill_with_given_expert_loads(bits, columns):
+    """The grouped path on a routing chosen so that the experts' token counts sit on the edges of its tiling (token
+    tiles of 64, work items of 128): 0, 1, 63, 64, 65, 127, 128, 129 pairs per expert, and an index outside
+    [0, E); every token against the oracle. PREFILL_TOL is the grouped path's bar."""
+    cfg = gen.tiny_config("c5", 512, 1024, n_experts=8, n_layers=1, group=128)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, [bits] * 8, columns=columns)
+    counts = [0, 1, 63, 64, 65, 127, 128, 129]
+    pairs = np.concatenate([np.full(c, e, dtype=np.int32) for e, c in enumerate(counts)])
+    rng = np.random.default_rng(5 + bits)
+    rng.shuffle(pairs)
+    k = cfg.top_k
+    if len(pairs) % k:
+        pairs = np.concatenate([pairs, np.array([8], dtype=np.int32)])       # an index outside [0, E): dropped
+    idx = pairs.reshape(-1, k)
+    T = idx.shape[0]
+    assert layer.path(T) == moeq.MOEQ_PATH_GROUPED_GEMM
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    gate = rng.uniform(0.1, 1.0, size=(T, k)).astype(np.float32)
+    y = moeq.moe_layer_forward_routed(layer, x, torch.from_numpy(idx).to(DEV), torch.from_numpy(gate).to(DEV))
+    torch.cuda.synchronize()
+    y_ref = oracle.layer_forward_routed(orc_experts, cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), k,
+                                        x.float().cpu().numpy(), idx, gate)
+    assert rel_err(y.cpu().numpy(), y_ref).max() < PREFILL_TOL
+    assert rel_err(y.cpu().numpy(), y_ref).max() < 2e-3      # (in fact it meets the decode bar as well)
+
+
+@pytest.mark.parametrize("columns", (False, True), ids=("canonical", "columns"))
 def test_prefill_full_size_mixtral_layer_on_sampled_tokens(columns):
     """The prefill configuration at its real shape (2048 tokens, top-2 of 8 SwiGLU experts at 4/8 bits):
     routing of every token against the oracle, outputs of a sample of tokens against the oracle."""
