@@ -4,9 +4,9 @@ Default (-m gpu): a reduced sweep - c4: 4 layers x 16 tokens on the stream and t
 are chosen so that 2+2, 2+4 and 4+4 bit expert pairs all occur), c5: 64 tokens of the 2048-token prefill call,
 stratified over every expert, the first and last positions of its 64-token blocks and the ragged last block.
 With MOEQ_FULL_SCOPE=1: every (token, layer) pair of the benchmark's c1, c2 and c3 runs (c3 also with 8 tokens
-per call), c4 all 32 layers x 16 tokens, c5 at least 256 stratified tokens; the figures go to
-gpurun_out/parity_scope.json. The oracle side groups the tokens by expert, so that an expert is decompressed
-once per layer."""
+per call), c4 all 32 layers x 16 tokens, c5 at least 256 stratified tokens; the figures are printed and, when
+MOEQ_SCOPE_OUT names a file, written there as JSON. The oracle side groups the tokens by expert, so that an expert
+is decompressed once per layer."""
 import json
 import os
 
@@ -22,15 +22,14 @@ from helpers import build_layer_pair, pack_expert_oracle, rel_err
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 FULL = os.environ.get("MOEQ_FULL_SCOPE") == "1"
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 RESULTS = {}
 
 
 def _record(name, **kw):
     RESULTS[name] = kw
-    if FULL:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "parity_scope.json"), "w") as f:
+    out = os.environ.get("MOEQ_SCOPE_OUT")
+    if out:
+        with open(out, "w") as f:
             json.dump(RESULTS, f, indent=1)
     print(name, kw, flush=True)
 
