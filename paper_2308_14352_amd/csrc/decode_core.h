@@ -166,7 +166,9 @@ __device__ __forceinline__ half8_t codes8(uint32_t w0, uint32_t w1) {
     const uint32_t w8 = w0 >> 8;
     r = {w0 & 0x000f000fu, w0 & 0x00f000f0u, w8 & 0x000f000fu, w8 & 0x00f000f0u};
   } else if (BITS == 8) {
-    r = {w0 & 0x00ff00ffu, (w0 >> 8) & 0x00ff00ffu, w1 & 0x00ff00ffu, (w1 >> 8) & 0x00ff00ffu};
+    // bytes 1 and 3 of a word into the low bytes of the two halves: one byte permute (selector 0x0c = zero byte)
+    r = {w0 & 0x00ff00ffu, __builtin_amdgcn_perm(0u, w0, 0x0c030c01u), w1 & 0x00ff00ffu,
+         __builtin_amdgcn_perm(0u, w1, 0x0c030c01u)};
   } else if (HH == 0) {
     r = {w0 & 0x00030003u, w0 & 0x000c000cu, w0 & 0x00300030u, w0 & 0x00c000c0u};
   } else {
