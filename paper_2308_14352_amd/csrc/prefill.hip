@@ -30,8 +30,10 @@ namespace {
 
 constexpr int kTB = 64;        // tokens per staged tile
 constexpr int kItemTiles = 2;  // token tiles per GEMM work item (128 tokens)
-// Wavefronts of a GEMM workgroup (template parameter WV): 8 (two per SIMD), or 16 where the registers allow four per
-// SIMD (GEMM 2 on the canonical W_out). Wavefront = (token tile, row group); WV / kItemTiles row groups.
+// Wavefronts of a GEMM workgroup (template parameter WV): 16 (four per SIMD, two streams per wavefront: 123 registers),
+// or 8 with two per SIMD (GEMM 2 on a W_out in columns, whose gathers need more registers). Wavefront = (token tile,
+// row group); WV / kItemTiles row groups.
+__host__ __device__ constexpr int gemm_streams(int phase, int wv) { return (phase == 1 || wv == 16) ? 2 : 4; }
 
 #define MOEQ_LDS __attribute__((address_space(3)))
 
@@ -183,8 +185,8 @@ __global__ __launch_bounds__(256) void k_stage(LayerDims L, const DevExpert* __r
 // ---------------------------------------------------------------------------------------------
 // The quantized GEMM. Workgroup = 8 wavefronts = 128 tokens (two token tiles) x 4 row groups; wavefront
 // (tile th, row group rg) multiplies the 64 tokens of its tile with the NS streams of its row group; a stream is
-// (matrix, block of 16 rows): GEMM 1 has NS = 4 (with two matrices a row group is 32 rows of both, else 64 rows),
-// GEMM 2 NS = 2. The two wavefronts of a row group share its packed pieces (each requests half of the streams), so
+// (matrix, block of 16 rows): NS = 2 per row group with 16 wavefronts (with two matrices a row group is 16 rows of
+// both), NS = 4 with 8. The two wavefronts of a row group share its packed pieces (each requests half of the streams), so
 // a weight byte comes from memory once per 128 tokens. Lane (n, kb) takes, per K step, the 16-byte piece
 // 4*step + kb of row n of each stream (8 bytes at 2 bits): four k blocks along one scale group.
 struct GemmArgs {
@@ -228,9 +230,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   // so two stages of it take the LDS that three stages take otherwise.
   constexpr int STAGES = BITS == 8 ? 2 : 3;
   constexpr int AHEAD = STAGES - 1;
-  // streams (row blocks of 16 rows) per row group; GEMM 2 has few rows (d_model): with two streams per
-  // row group its grid has twice the workgroups and fills the compute units more evenly
-  constexpr int NS = PHASE == 1 ? 2 : 4;
+  // streams (row blocks of 16 rows) per row group: two with 16 wavefronts per workgroup, four with 8
+  constexpr int NS = gemm_streams(PHASE, WV);
   constexpr int HS = NS / kItemTiles;             // streams whose pieces one wavefront of the pair requests
   constexpr int RBW = NS / NM;                    // row blocks per row group and matrix
   constexpr int kRowGroups = WV / kItemTiles;
@@ -533,7 +534,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
 // LDS of a GEMM workgroup: the largest carve over the bitwidths
 template <int PHASE, bool COLS, int WV>
 constexpr int gemm_lds_bytes() {
-  constexpr int NS = PHASE == 1 ? 2 : 4;
+  constexpr int NS = gemm_streams(PHASE, WV);
   constexpr int RG = WV / kItemTiles;
   constexpr int scales = RG * 2 * NS * (COLS ? 4 : 2) * 64;
   constexpr int b24 = 3 * kItemTiles * (16 * 1024 + 256) + RG * 3 * NS * 1024 + scales;    // 2 and 4 bits
@@ -542,7 +543,7 @@ constexpr int gemm_lds_bytes() {
 }
 // rows of the GEMM's output a workgroup covers
 template <int NM, int PHASE, int WV>
-constexpr int gemm_rows() { return (WV / kItemTiles) * ((PHASE == 1 ? 2 : 4) / NM) * 16; }
+constexpr int gemm_rows() { return (WV / kItemTiles) * (gemm_streams(PHASE, WV) / NM) * 16; }
 
 // Grid: one dimension, n_rb * (upper bound of the work items) workgroups, n_rb = row blocks of the GEMM; the row
 // blocks of a work item are consecutive workgroups (they share the item's activation tiles in the L2s).
@@ -587,6 +588,7 @@ bool prefill_supported(const LayerDims& L) {
          L.d_ff <= 32768 && L.n_experts <= 1024;
 }
 
+constexpr int kWaves1 = 16;    // wavefronts of a GEMM 1 workgroup
 constexpr int kWaves2 = 16;    // wavefronts of a GEMM 2 workgroup on the canonical W_out
 
 hipError_t init_attrs_prefill() {
@@ -599,12 +601,12 @@ hipError_t init_attrs_prefill() {
       e != hipSuccess)
     return e;
   // the GEMMs' rings
-  if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<2, 0, false, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         gemm_lds_bytes<0, false, 8>());
+  if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<2, 0, false, kWaves1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         gemm_lds_bytes<0, false, kWaves1>());
       e != hipSuccess)
     return e;
-  if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<1, 0, false, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         gemm_lds_bytes<0, false, 8>());
+  if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<1, 0, false, kWaves1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         gemm_lds_bytes<0, false, kWaves1>());
       e != hipSuccess)
     return e;
   if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<1, 1, false, kWaves2>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -661,16 +663,16 @@ hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void
                      poff, boff, XA, M);
   GemmArgs G{L, table, blocks, nblk, poff, boff, XA, Hf, Ypair};
   const unsigned nb = (unsigned)w.max_blocks;
-  constexpr int lds1 = gemm_lds_bytes<0, false, 8>(), lds2 = gemm_lds_bytes<1, false, kWaves2>(),
+  constexpr int lds1 = gemm_lds_bytes<0, false, kWaves1>(), lds2 = gemm_lds_bytes<1, false, kWaves2>(),
                 lds2c = gemm_lds_bytes<1, true, 8>();
   if (L.act == MOEQ_ACT_SWIGLU) {
-    constexpr int BN = gemm_rows<2, 0, 8>();
+    constexpr int BN = gemm_rows<2, 0, kWaves1>();
     const int n_rb = (L.d_ff + BN - 1) / BN;
-    hipLaunchKernelGGL((k_gemm_q<2, 0, false, 8>), dim3((unsigned)n_rb * nb), dim3(512), lds1, st, G, n_rb);
+    hipLaunchKernelGGL((k_gemm_q<2, 0, false, kWaves1>), dim3((unsigned)n_rb * nb), dim3(kWaves1 * 64), lds1, st, G, n_rb);
   } else {
-    constexpr int BN = gemm_rows<1, 0, 8>();
+    constexpr int BN = gemm_rows<1, 0, kWaves1>();
     const int n_rb = (L.d_ff + BN - 1) / BN;
-    hipLaunchKernelGGL((k_gemm_q<1, 0, false, 8>), dim3((unsigned)n_rb * nb), dim3(512), lds1, st, G, n_rb);
+    hipLaunchKernelGGL((k_gemm_q<1, 0, false, kWaves1>), dim3((unsigned)n_rb * nb), dim3(kWaves1 * 64), lds1, st, G, n_rb);
   }
   hipLaunchKernelGGL(k_stage<true>, dim3(stage_grid), dim3(256), stage_lds(L.d_ff), st, L, table, (const void*)Hf, gpair,
                      gexp, poff, boff, HA, M);
