@@ -19,10 +19,11 @@ DEV = "cuda:0"
     ("c3", 512, 1024, 32, False, 8, 3),     # two-kernel path
     ("c5", 512, 1024, 8, False, 70, 40),    # grouped GEMMs, then fewer tokens through the same scratch
     ("c5", 512, 1024, 8, True, 40, 1),      # grouped GEMMs, then one token through the one-kernel path
+    ("c4", 4096, 256, 8, "stream", 2, 1),   # the streaming kernel on integer dot products (stream layout)
 ])
 def test_static_entry_matches_the_workspace_entry_on_two_calls_in_a_row(base, d, f, E, columns, T1, T2):
     cfg = gen.tiny_config(base, d, f, n_experts=E, n_layers=1)
-    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, columns=columns is True, stream=columns == "stream")
     assert layer.workspace_bytes(T1) <= binding.moe_static_scratch_bytes()
     x1 = gen.hidden(cfg, 0, 0, T1, DEV)
     x2 = gen.hidden(cfg, 0, 1, T2, DEV)
