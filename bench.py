@@ -304,15 +304,16 @@ def cpu_baseline(stack, dev, budget_layers):
                       f"{per_layer * 1e3:.1f} ms per token-layer, scaled to the {stack.L}-layer stack"}
 
 
-def run_prefill(dev, reps=5, columns=False):
+def run_prefill(dev, reps=5, columns=False, stream=False):
     """c5: one Mixtral-8x7B-shaped layer, 2048 tokens in one call (grouped GEMMs on the matrix cores).
-    columns: W_out in the dword-column-major layout the decode kernel wants (GEMM 2 then gathers its words)."""
+    columns: W_out in the dword-column-major layout the decode kernels want (GEMM 2 then gathers its words);
+    stream: W_in / W_gate in the stream layout of the decode kernel as well (the layer a decode stack holds)."""
     import torch
     import gen
     import paper_2308_14352_amd as moeq
     cfg = gen.CONFIGS["c5"]
     T = cfg.prefill_tokens
-    st = Stack(cfg, T, 1, dev, 1, columns=columns)
+    st = Stack(cfg, T, 1, dev, 1, columns=columns, stream=stream)
     layer, x = st.layers[0], st.x_all[0, 0]
     y = torch.empty((T, cfg.d_model), dtype=torch.float32, device=dev)
     ws = torch.empty(layer.workspace_bytes(T), dtype=torch.uint8, device=dev)
@@ -328,7 +329,7 @@ def run_prefill(dev, reps=5, columns=False):
     return {"tokens_per_s": T / dt, "ms_per_call": dt * 1e3, "tokens": T, "achieved_TFLOPs": flops / dt / 1e12,
             "mfma_f16_peak_TFLOPs": 2500.0, "frac_of_mfma_peak": flops / dt / 2.5e15,
             "packed_GB": st.packed_bytes / 1e9, "bitwidths": st.bits[0],
-            "w_out_layout": "columns" if columns else "canonical"}
+            "layout": "stream" if stream else ("columns" if columns else "canonical")}
 
 
 def run_unfused_comparison(dev, reps=10):
@@ -490,7 +491,8 @@ def main():
         print(json.dumps({"shared_expert_probe": run_shared_expert_probe(dev, args.layout)}))
         return
     if args.prefill_only:
-        print(json.dumps({"c5_prefill": run_prefill(dev, reps=args.steps or 5, columns=args.layout == "columns")}))
+        print(json.dumps({"c5_prefill": run_prefill(dev, reps=args.steps or 5, columns=args.layout == "columns",
+                                                    stream=args.layout == "stream")}))
         return
     name = args.workload
     steps = args.steps or DEFAULT_STEPS[name]
@@ -579,6 +581,7 @@ def main():
         del st
         torch.cuda.empty_cache()
         extras["c5_prefill"] = run_prefill(dev)
+        extras["c5_prefill_stream_layout"] = run_prefill(dev, stream=True)
         extras["c4_expert_fused_vs_unfused"] = run_unfused_comparison(dev)
         out["other_workloads"] = extras
     print(json.dumps(out))

@@ -138,7 +138,9 @@ size_t moe_layer_table_bytes(int32_t n_experts);
  * n_experts <= 1024; d_model, d_ff <= 32768. With out_layout = MOEQ_OUT_COLUMNS also: group and d_ff
  * multiples of 16, d_model <= 8192 (else MOEQ_EUNSUPPORTED). With in_layout = MOEQ_IN_STREAM also: out_layout =
  * MOEQ_OUT_COLUMNS, d_model = 4096, group = 128, d_ff a multiple of 64 (else MOEQ_EUNSUPPORTED); calls on such a
- * layer run the streaming kernel at every token count (32 tokens per launch).
+ * layer run the streaming kernel below 32 tokens and the grouped GEMMs from 32 tokens on where their shape rules
+ * hold (d_ff a multiple of 256 with d_ff / 128 a multiple of 4; else the streaming kernel, 32 tokens per launch):
+ * one copy of the weights serves decode and prefill.
  * Errors: MOEQ_EINVAL, MOEQ_EUNSUPPORTED, MOEQ_EDEVICE (copy failed). */
 moeq_status moe_layer_create(const moeq_layer_desc *desc, void *table_dev, size_t table_bytes,
                              moeq_layer **out);

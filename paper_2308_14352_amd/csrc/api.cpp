@@ -79,8 +79,8 @@ WsLayout ws_layout(const moeq_layer* layer, int64_t T) {
 
 bool use_prefill(const moeq_layer* layer, int64_t T) {
   static const bool off = [] { const char* v = std::getenv("MOEQ_NO_PREFILL"); return v && v[0] == '1'; }();
-  // the grouped GEMMs read W_in / W_gate in the canonical format only
-  return !off && T >= kPrefillMinTokens && layer->in_layout == MOEQ_IN_CANONICAL && prefill_supported(layer->dims);
+  // (the grouped GEMMs read W_in / W_gate in the canonical and in the stream layout, W_out in both of its layouts)
+  return !off && T >= kPrefillMinTokens && prefill_supported(layer->dims);
 }
 
 // Routers with at most this many experts are evaluated inside the one-kernel path by every workgroup;
@@ -320,7 +320,7 @@ static moeq_status layer_forward_impl(const moeq_layer* layer, const void* x, in
     }
     const PrefillWs pw = prefill_ws(L, n_tokens);
     return dev(launch_prefill(L, layer->table, x, n_tokens, idx, gate, (char*)ws + w.prefill_off, pw, y,
-                              layer->out_layout == MOEQ_OUT_COLUMNS, st));
+                              layer->out_layout == MOEQ_OUT_COLUMNS, layer->in_layout == MOEQ_IN_STREAM, st));
   }
   if (layer->out_layout == MOEQ_OUT_COLUMNS) {
     // one streaming kernel for the whole layer, then the ordered sum of its partial output vectors

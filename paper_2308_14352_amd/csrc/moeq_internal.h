@@ -108,10 +108,11 @@ struct PrefillWs {
 };
 bool prefill_supported(const LayerDims& L);
 PrefillWs prefill_ws(const LayerDims& L, int64_t T);
-// idx / gate: the routing of the T tokens ([T][k], already computed). W_out in the canonical layout.
+// idx / gate: the routing of the T tokens ([T][k], already computed). out_columns / in_stream: the layouts of W_out and
+// of W_in / W_gate.
 hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void* x, int32_t T,
                           const int32_t* idx, const float* gate, char* ws, const PrefillWs& w, float* y,
-                          bool out_columns, hipStream_t st);
+                          bool out_columns, bool in_stream, hipStream_t st);
 
 hipError_t launch_quantize_pack(const float* w, int64_t rows, int64_t cols, int bits, int group,
                                 uint8_t* q, uint16_t* s, hipStream_t st);

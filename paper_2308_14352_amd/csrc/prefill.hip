@@ -219,7 +219,10 @@ __device__ __forceinline__ void stage_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int BITS, int NM, int PHASE, bool COLS, int WV>
+// COLS: GEMM 2 on a W_out in the dword-column-major layout. SIN: GEMM 1 on W_in / W_gate in the row-block stream
+// layout (blocks of RB = 16 / bits rows: 8 tiles of 1 KB, then 64 * RB bytes of scales; 16-byte piece c of row r is
+// piece c / TPR of tile (r % RB) * TPR + c % TPR of block r / RB, TPR = bits / 2).
+template <int BITS, int NM, int PHASE, bool COLS, int WV, bool SIN>
 __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex, int e, int tb, int rb, char* smem) {
   constexpr int SC = 128;                         // columns per K step: one scale group (or a part of one)
   constexpr int NQ = 4;                           // instructions per step, stream and token block
@@ -242,7 +245,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   constexpr int A_STAGE = kItemTiles * A_TILE;
   constexpr int B_STREAM = NH * 1024;             // a stream's pieces of a step (2-bit codes use half of it)
   constexpr int B_STAGE = NS * B_STREAM;          // per row group
-  constexpr int NSCW = COLS ? 4 : 2;              // dwords of a row's scale block (four groups)
+  constexpr int NSCW = (COLS || SIN) ? 4 : 2;     // dwords of a row's scale block (four groups)
   constexpr int SC_SLOT = NS * NSCW * 64;         // per row group: NSCW areas of 16 dwords per stream
   // loads a wavefront issues per stage, counted by stage_wait: its half of the row group's pieces + its lines
   // of the two A tiles
@@ -276,25 +279,46 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
   const uint8_t* qs[NM];
   const uint8_t* ss[NM];
   if (PHASE == 0) {
-    qs[0] = ex.q_in; ss[0] = (const uint8_t*)ex.s_in;
-    if (NM == 2) { qs[NM - 1] = ex.q_gate; ss[NM - 1] = (const uint8_t*)ex.s_gate; }
+    qs[0] = ex.q_in; ss[0] = SIN ? ex.q_in : (const uint8_t*)ex.s_in;
+    if (NM == 2) { qs[NM - 1] = ex.q_gate; ss[NM - 1] = SIN ? ex.q_gate : (const uint8_t*)ex.s_gate; }
   } else {
     qs[0] = ex.q_out; ss[0] = (const uint8_t*)ex.s_out;
   }
   // the streams this wavefront requests: s = th * HS + i
+  constexpr uint32_t RB = 16 / BITS, TPR = BITS / 2, BB = 8192u + 64u * RB;   // stream layout: rows, tiles per row, bytes of a block
+  // scale of group g of row r: COLS the binary16 value g * N + r (fetched as the dword of rows r & ~1, r | 1); SIN
+  // value (r % RB) % (RB / 2) of lane 2 g + ((r % RB) >= RB / 2) of its block's scale area (RB bytes per lane),
+  // fetched as the dword around it; sgrp = bytes from a group's dword to the next group's
+  const uint32_t sgrp = COLS ? (uint32_t)N * 2u : (SIN ? 2u * RB : 0u);
+  auto scale_half = [&](uint32_t row) __attribute__((always_inline)) {       // which half of the fetched dword
+    if (COLS) return (row & 1u) * 16u;
+    if (SIN) { const uint32_t rr = row % RB; return (BITS == 8 ? rr : (rr % (RB / 2)) & 1u) * 16u; }
+    return 0u;
+  };
   uint32_t qrow[HS], srow[HS];
 #pragma unroll
   for (int i = 0; i < HS; ++i) {
     const int s = th * HS + i;
     const uint32_t row = (uint32_t)min(R0 + (s % RBW) * 16 + n, N - 1);
-    // COLS (GEMM 2 on a W_out in the dword-column-major layout): word w of row r is the 32-bit word
-    // w * N + r, the scale of group g of row r the binary16 value g * N + r (fetched as the dword of rows r & ~1, r | 1)
-    qrow[i] = COLS ? row * 4u : row * row_bytes;
-    srow[i] = COLS ? (row & ~1u) * 2u : row * ng2;
+    if (SIN) {
+      const uint32_t blk = row / RB, rr = row % RB, hi2 = rr >= RB / 2 ? 1u : 0u, ii = rr % (RB / 2 ? RB / 2 : 1);
+      // the lane's piece of (half) step 0: 4 bits: tile part kb & 1, piece kb >> 1; 8 bits: tile part kb, piece 0;
+      // 2 bits: the 8 bytes kb of the row's first 32
+      const uint32_t koff = BITS == 4 ? (uint32_t)(kb & 1) * 1024u + (uint32_t)(kb >> 1) * 16u
+                          : (BITS == 8 ? (uint32_t)kb * 1024u : (uint32_t)kb * 8u);
+      qrow[i] = blk * BB + rr * TPR * 1024u + koff;
+      srow[i] = blk * BB + 8192u + (BITS == 8 ? 0u : hi2 * RB + (ii >> 1) * 4u);
+    } else {
+      // COLS: word w of row r is the 32-bit word w * N + r
+      qrow[i] = COLS ? row * 4u : row * row_bytes + (uint32_t)kb * (BITS == 2 ? 8u : 16u);
+      srow[i] = COLS ? (row & ~1u) * 2u : row * ng2;
+    }
   }
-  uint32_t rodd[NS];        // COLS: which half of a scale dword is row n of stream s
+  // bytes from the lane's piece of one (half) step to that of the next
+  constexpr uint32_t hstep = SIN ? (BITS == 8 ? 16u : 32u) : (BITS == 2 ? 32u : 64u);
+  uint32_t rodd[NS];        // which half of a fetched scale dword is row n of stream s
 #pragma unroll
-  for (int s = 0; s < NS; ++s) rodd[s] = COLS ? ((uint32_t)min(R0 + (s % RBW) * 16 + n, N - 1) & 1u) * 16u : 0u;
+  for (int s = 0; s < NS; ++s) rodd[s] = scale_half((uint32_t)min(R0 + (s % RBW) * 16 + n, N - 1));
   // The scales of a stream's row for four consecutive groups (8 contiguous bytes in the canonical layout; the
   // plan makes rows of scales multiples of 8 bytes), fetched once per block of blk_steps = 4 * group / SC steps
   // by the sixteen lanes with kb = 0 into slot (block & 1).
@@ -309,8 +333,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
         const uint8_t* sb = ss[s / RBW];
 #pragma unroll
         for (int j = 0; j < NSCW; ++j) {
-          const uint8_t* sp = COLS ? sb + ((gi + (uint32_t)j) * ((uint32_t)N * 2u) + srow[i])
-                                   : sb + (srow[i] + gi * 2u + (uint32_t)j * 4u);
+          const uint8_t* sp = (COLS || SIN) ? sb + ((gi + (uint32_t)j) * sgrp + srow[i])
+                                            : sb + (srow[i] + gi * 2u + (uint32_t)j * 4u);
           dma4(sp, slot + (uint32_t)((s * NSCW + j) * 64));
         }
       }
@@ -342,13 +366,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
             dma4(q + ((w0 + (uint32_t)j) * col_bytes + qrow[i]), bst + (uint32_t)(s * B_STREAM + h * 1024 + j * 256));
         }
       } else if constexpr (BITS == 2) {
-        const uint8_t* p = q + (qrow[i] + (uint32_t)step * 32u + (uint32_t)kb * 8u);
+        const uint8_t* p = q + (qrow[i] + (uint32_t)step * hstep);
         dma4(p, bst + (uint32_t)(s * B_STREAM));
         dma4(p + 4, bst + (uint32_t)(s * B_STREAM + 256));
       } else {
 #pragma unroll
         for (int h = 0; h < NH; ++h)
-          dma16(q + (qrow[i] + ((uint32_t)step * NH + h) * 64u + (uint32_t)kb * 16u), bst + (uint32_t)(s * B_STREAM + h * 1024));
+          dma16(q + (qrow[i] + ((uint32_t)step * NH + h) * hstep), bst + (uint32_t)(s * B_STREAM + h * 1024));
       }
     }
 #pragma unroll
@@ -401,7 +425,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
       }
       // the step's scale among the four of the block
       uint32_t w;
-      if constexpr (COLS) w = *(const uint32_t*)(slot + (s * NSCW + (int)(gi & 3u)) * 64 + n * 4) >> rodd[s];
+      if constexpr (COLS || SIN) w = *(const uint32_t*)(slot + (s * NSCW + (int)(gi & 3u)) * 64 + n * 4) >> rodd[s];
       else w = *(const uint32_t*)(slot + (s * NSCW + (int)((gi >> 1) & 1u)) * 64 + n * 4) >> ((gi & 1u) * 16u);
       sc[s] = f16_bits_to_f32(w);   // (the conversion takes the low 16 bits)
     }
@@ -532,11 +556,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& G, const DevExpert& ex
 }
 
 // LDS of a GEMM workgroup: the largest carve over the bitwidths
-template <int PHASE, bool COLS, int WV>
+template <int PHASE, bool WIDE, int WV>      // WIDE: four dwords per row and scale block (columns and stream layouts)
 constexpr int gemm_lds_bytes() {
   constexpr int NS = gemm_streams(PHASE, WV);
   constexpr int RG = WV / kItemTiles;
-  constexpr int scales = RG * 2 * NS * (COLS ? 4 : 2) * 64;
+  constexpr int scales = RG * 2 * NS * (WIDE ? 4 : 2) * 64;
   constexpr int b24 = 3 * kItemTiles * (16 * 1024 + 256) + RG * 3 * NS * 1024 + scales;    // 2 and 4 bits
   constexpr int b8 = 2 * kItemTiles * (16 * 1024 + 512) + RG * 2 * NS * 2048 + scales;     // 8 bits
   return b24 > b8 ? b24 : b8;
@@ -547,7 +571,7 @@ constexpr int gemm_rows() { return (WV / kItemTiles) * (gemm_streams(PHASE, WV) 
 
 // Grid: one dimension, n_rb * (upper bound of the work items) workgroups, n_rb = row blocks of the GEMM; the row
 // blocks of a work item are consecutive workgroups (they share the item's activation tiles in the L2s).
-template <int NM, int PHASE, bool COLS, int WV>
+template <int NM, int PHASE, bool COLS, int WV, bool SIN = false>
 __global__ __launch_bounds__(WV * 64) void k_gemm_q(GemmArgs G, int n_rb) {
   extern __shared__ __attribute__((aligned(16))) char gsmem[];
   const int it0 = (int)blockIdx.x / n_rb;
@@ -557,9 +581,9 @@ __global__ __launch_bounds__(WV * 64) void k_gemm_q(GemmArgs G, int n_rb) {
   const int rb = (int)blockIdx.x - it0 * n_rb;
   const DevExpert ex = G.table[e];
   switch (ex.bits) {
-    case 2: gemm_body<2, NM, PHASE, COLS, WV>(G, ex, e, tb, rb, gsmem); break;
-    case 4: gemm_body<4, NM, PHASE, COLS, WV>(G, ex, e, tb, rb, gsmem); break;
-    default: gemm_body<8, NM, PHASE, COLS, WV>(G, ex, e, tb, rb, gsmem); break;
+    case 2: gemm_body<2, NM, PHASE, COLS, WV, SIN>(G, ex, e, tb, rb, gsmem); break;
+    case 4: gemm_body<4, NM, PHASE, COLS, WV, SIN>(G, ex, e, tb, rb, gsmem); break;
+    default: gemm_body<8, NM, PHASE, COLS, WV, SIN>(G, ex, e, tb, rb, gsmem); break;
   }
 }
 
@@ -609,6 +633,14 @@ hipError_t init_attrs_prefill() {
                                          gemm_lds_bytes<0, false, kWaves1>());
       e != hipSuccess)
     return e;
+  if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<2, 0, false, kWaves1, true>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, gemm_lds_bytes<0, true, kWaves1>());
+      e != hipSuccess)
+    return e;
+  if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<1, 0, false, kWaves1, true>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, gemm_lds_bytes<0, true, kWaves1>());
+      e != hipSuccess)
+    return e;
   if (hipError_t e = hipFuncSetAttribute((const void*)k_gemm_q<1, 1, false, kWaves2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                          gemm_lds_bytes<1, false, kWaves2>());
       e != hipSuccess)
@@ -641,7 +673,7 @@ PrefillWs prefill_ws(const LayerDims& L, int64_t T) {
 }
 
 hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void* x, int32_t T, const int32_t* idx,
-                          const float* gate, char* ws, const PrefillWs& w, float* y, bool out_columns,
+                          const float* gate, char* ws, const PrefillWs& w, float* y, bool out_columns, bool in_stream,
                           hipStream_t st) {
   const int M = T * L.top_k;
   int32_t* poff = (int32_t*)(ws + w.poff);
@@ -665,14 +697,19 @@ hipError_t launch_prefill(const LayerDims& L, const DevExpert* table, const void
   const unsigned nb = (unsigned)w.max_blocks;
   constexpr int lds1 = gemm_lds_bytes<0, false, kWaves1>(), lds2 = gemm_lds_bytes<1, false, kWaves2>(),
                 lds2c = gemm_lds_bytes<1, true, 8>();
+  constexpr int lds1s = gemm_lds_bytes<0, true, kWaves1>();
   if (L.act == MOEQ_ACT_SWIGLU) {
     constexpr int BN = gemm_rows<2, 0, kWaves1>();
     const int n_rb = (L.d_ff + BN - 1) / BN;
-    hipLaunchKernelGGL((k_gemm_q<2, 0, false, kWaves1>), dim3((unsigned)n_rb * nb), dim3(kWaves1 * 64), lds1, st, G, n_rb);
+    const dim3 grid((unsigned)n_rb * nb), block(kWaves1 * 64);
+    if (in_stream) hipLaunchKernelGGL((k_gemm_q<2, 0, false, kWaves1, true>), grid, block, lds1s, st, G, n_rb);
+    else hipLaunchKernelGGL((k_gemm_q<2, 0, false, kWaves1>), grid, block, lds1, st, G, n_rb);
   } else {
     constexpr int BN = gemm_rows<1, 0, kWaves1>();
     const int n_rb = (L.d_ff + BN - 1) / BN;
-    hipLaunchKernelGGL((k_gemm_q<1, 0, false, kWaves1>), dim3((unsigned)n_rb * nb), dim3(kWaves1 * 64), lds1, st, G, n_rb);
+    const dim3 grid((unsigned)n_rb * nb), block(kWaves1 * 64);
+    if (in_stream) hipLaunchKernelGGL((k_gemm_q<1, 0, false, kWaves1, true>), grid, block, lds1s, st, G, n_rb);
+    else hipLaunchKernelGGL((k_gemm_q<1, 0, false, kWaves1>), grid, block, lds1, st, G, n_rb);
   }
   hipLaunchKernelGGL(k_stage<true>, dim3(stage_grid), dim3(256), stage_lds(L.d_ff), st, L, table, (const void*)Hf, gpair,
                      gexp, poff, boff, HA, M);

@@ -68,7 +68,9 @@ def test_stream_layer_small_d_ff(base, x_dtype, f, k, bits_table):
     layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, stream=True)
     E = len(bits_table)
     T = 5
-    assert layer.path(1) == moeq.MOEQ_PATH_STREAM and layer.path(100) == moeq.MOEQ_PATH_STREAM
+    grouped_ok = f % 256 == 0 and (f // 128) % 4 == 0          # the shape rule of the grouped GEMMs
+    assert layer.path(1) == moeq.MOEQ_PATH_STREAM and layer.path(31) == moeq.MOEQ_PATH_STREAM
+    assert layer.path(100) == (moeq.MOEQ_PATH_GROUPED_GEMM if grouped_ok else moeq.MOEQ_PATH_STREAM)
     x = gen.hidden(cfg, 0, 0, T, DEV)
     y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
     torch.cuda.synchronize()
@@ -111,6 +113,40 @@ def test_stream_layer_small_d_ff(base, x_dtype, f, k, bits_table):
     ref2 = y0.cpu().numpy().astype(np.float64) + g1.cpu().numpy()[:, None] * oracle.expert_ffn(
         orc_experts[0], cfg.d_model, cfg.d_ff, cfg.group, int(cfg.swiglu), xh)
     assert np.abs(y2.cpu().numpy() - ref2).max() < TOL * np.abs(ref2).max()
+
+
+@pytest.mark.parametrize("base,x_dtype,f,k,bits_table,T", [
+    ("c4", "bf16", 1024, 2, [2, 4, 8, 4], 70),      # SwiGLU, bf16 hidden states, top-2, ragged token tiles
+    ("c4", "f32", 512, 2, [8, 4, 2], 130),          # 130 tokens: work items of 128 + a rest
+    ("c1", "f32", 1024, 1, [4, 2, 8], 45),          # ReLU, top-1
+    ("c4", "bf16", 768, 2, [4, 2, 8, 4], 40),       # d_ff outside the GEMMs' shape rule: the streaming kernel in chunks
+], ids=("swiglu-bf16", "swiglu-f32", "relu-f32", "chunks"))
+def test_stream_layer_with_many_tokens(base, x_dtype, f, k, bits_table, T):
+    """Calls of 32 tokens or more on a layer in the stream layout: the grouped GEMMs read the stream buffers of
+    W_in / W_gate (and W_out in columns) - one copy of the weights serves decode and prefill - or, where their
+    shape rule does not hold, the streaming kernel runs in launches of 32 tokens."""
+    cfg = replace(gen.tiny_config(base, 4096, f, n_experts=len(bits_table), n_layers=1, group=128), top_k=k,
+                  x_dtype=x_dtype)
+    layer, orc_experts, Wr, bias = build_layer_pair(cfg, 0, DEV, bits_table, stream=True)
+    grouped_ok = f % 256 == 0 and (f // 128) % 4 == 0
+    assert layer.path(T) == (moeq.MOEQ_PATH_GROUPED_GEMM if grouped_ok else moeq.MOEQ_PATH_STREAM)
+    x = gen.hidden(cfg, 0, 0, T, DEV)
+    y, idx, gate = moeq.moe_layer_forward(layer, x, want_routing=True)
+    torch.cuda.synchronize()
+    y_ref, idx_ref, gate_ref = oracle_layer(cfg, orc_experts, Wr, bias, x)
+    skip = set(near_tie_tokens(cfg, Wr, bias, x).tolist())
+    keep = [t for t in range(T) if t not in skip]
+    assert len(keep) >= T - 2
+    assert np.array_equal(idx.cpu().numpy()[keep], idx_ref[keep])
+    assert np.allclose(gate.cpu().numpy()[keep], gate_ref[keep], rtol=2e-5, atol=1e-7)
+    assert rel_err(y.cpu().numpy()[keep], y_ref[keep]).max() < TOL        # (the decode bar; the grouped path's is 2e-2)
+    # the same tokens through the decode kernel, one by one
+    y_dec = torch.cat([moeq.moe_layer_forward(layer, x[t:t + 1]) for t in range(4)])
+    torch.cuda.synchronize()
+    assert rel_err(y.cpu().numpy()[:4], y_dec.cpu().numpy()).max() < TOL
+    y_b = moeq.moe_layer_forward(layer, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_b)
 
 
 @pytest.mark.parametrize("scale", [2.0 ** -13, 2.0 ** -10, 1.0, 2.0 ** 12, 2.0 ** 20], ids=lambda v: "x2^%d" % int(np.log2(v)))
